@@ -1,0 +1,198 @@
+/*
+ * ctcspec.h - C ABI of libctcspec: the per-step device work of CTC-drafted speculative decoding
+ * (draft head -> CTC transform -> tree verification attention -> greedy acceptance) on one AMD
+ * MI355X (gfx950).
+ *
+ * Conventions that hold for every call
+ *  - Plain C.  Every data pointer is a DEVICE pointer owned by the caller unless a comment says
+ *    "host".  The library never allocates, frees or keeps caller buffers; it owns only the
+ *    workspace that ctcspec_create allocates inside the context.
+ *  - All work is enqueued on the HIP stream given to ctcspec_create / ctcspec_set_stream.  No call
+ *    synchronises with the host.  Sizes that depend on the data (n_cand, n_nodes) are written to
+ *    device memory and read from there by the later calls, so the four stage calls can be issued
+ *    back to back.
+ *  - Return value: CTCSPEC_OK (0) or a negative error code.  On error nothing has been launched and
+ *    ctcspec_last_error(ctx) describes the reason.  No C++ exception crosses this boundary.
+ *  - One context serves one stream at a time: calls on the same context from several threads, or
+ *    overlapping on the GPU, race on its workspace.
+ *  - Row-major, innermost index last, no padding unless stated.  bf16 is the upper half of an IEEE
+ *    float32 (1-8-7).  int32_t/int64_t/uint64_t are little endian device integers.
+ *
+ * Notation: B sequences, T draft slots, D hidden size, V vocabulary size (the blank is one extra
+ * row, id V, so the head has V+1 rows), k tokens kept per slot, H heads, dh head dimension.
+ */
+#ifndef CTCSPEC_H
+#define CTCSPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ctcspec_ctx ctcspec_ctx;
+
+typedef enum { CTCSPEC_F32 = 0, CTCSPEC_BF16 = 1 } ctcspec_dtype;
+
+enum {
+  CTCSPEC_OK = 0,
+  CTCSPEC_EINVAL = -1,       /* null / misaligned pointer, non-positive size, inconsistent arguments */
+  CTCSPEC_EUNSUPPORTED = -2, /* shape outside the compiled limits or the context's limits */
+  CTCSPEC_EHIP = -3          /* the HIP runtime reported a failure */
+};
+
+/* Compiled limits (also returned by ctcspec_query_limit). */
+#define CTCSPEC_MAX_SLOTS 8        /* T */
+#define CTCSPEC_MAX_TOPK 8         /* k */
+#define CTCSPEC_MAX_ALIGNMENTS 65536 /* k^T */
+#define CTCSPEC_MAX_BEAM 128
+#define CTCSPEC_MAX_NODES 128      /* tree nodes per sequence, root included */
+#define CTCSPEC_MAX_COLUMNS 64     /* B*T columns of one draft-head call */
+#define CTCSPEC_MAX_HEAD_DIM 128
+
+/* Sizes the context's workspace is dimensioned for.  Calls that exceed them fail with
+ * CTCSPEC_EUNSUPPORTED. */
+typedef struct {
+  int max_batch;      /* B */
+  int max_slots;      /* T  <= CTCSPEC_MAX_SLOTS */
+  int max_topk;       /* k  <= CTCSPEC_MAX_TOPK */
+  int max_vocab_rows; /* V+1 */
+  int max_nodes;      /* <= CTCSPEC_MAX_NODES */
+  int max_heads;      /* H */
+  int max_head_dim;   /* dh <= CTCSPEC_MAX_HEAD_DIM */
+} ctcspec_limits;
+
+/* Create a context: allocates the device workspace on the current HIP device (this is the only
+ * place the library allocates device memory) and binds `hip_stream` (a hipStream_t; NULL = the
+ * default stream).  *out is set to NULL on failure.  Host pointers. */
+int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec_limits* limits);
+
+/* Free the workspace.  The caller must have synchronised the stream.  NULL is ignored. */
+void ctcspec_destroy(ctcspec_ctx* ctx);
+
+/* Bind another stream for subsequent calls (work already enqueued stays where it is). */
+int ctcspec_set_stream(ctcspec_ctx* ctx, void* hip_stream);
+
+/* Static, NUL-terminated description of the last error on this context ("" if none).  With
+ * ctx == NULL: the reason the last ctcspec_create failed in this thread. */
+const char* ctcspec_last_error(const ctcspec_ctx* ctx);
+
+/* Bytes of device workspace the context holds. */
+size_t ctcspec_workspace_bytes(const ctcspec_ctx* ctx);
+
+/*
+ * Stage 1+2 - draft head.  For every draft slot, project its hidden state through the LM head of
+ * the augmented vocabulary (tokens plus blank), take the log-softmax over all V+1 entries and keep
+ * the k most probable entries in descending order (paper Sec. 3.2: P^ = Softmax(LmHead(F^)), the
+ * blank being one more output symbol, Sec. 2.2; Sec. 3.3: "for every position the top k tokens").
+ *
+ *   z[b,t,v]   = sum_d hidden[b,t,d] * w[v,d] + bias[v]       (fp32 accumulate)
+ *   lse[b,t]   = log sum_v exp z[b,t,v]
+ *   topk_id    = the k indices of largest z[b,t,:], descending; equal z -> smaller index first
+ *   topk_logp  = z[topk_id] - lse
+ *
+ * dt           element type of hidden and w (CTCSPEC_F32: float, CTCSPEC_BF16: bf16)
+ * hidden       [B,T,D]            16-byte aligned
+ * w            [Vp1,D] row-major  16-byte aligned; row Vp1-1 is the blank unless the caller decides
+ *                                 otherwise (this call does not treat any row specially)
+ * bias         [Vp1] float or NULL (= 0)
+ * topk_id      [B,T,k] int32   out
+ * topk_logp    [B,T,k] float   out
+ * lse          [B,T]   float   out, may be NULL
+ * logits_out   [B,T,Vp1] float out, may be NULL; when given, receives exactly the z values the
+ *              ranking used (for parity checks; costs extra HBM writes)
+ * Limits: B*T <= CTCSPEC_MAX_COLUMNS, 1 <= k <= min(CTCSPEC_MAX_TOPK, Vp1), Vp1 <= limits.
+ */
+int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hidden, const void* w,
+                   const float* bias, int B, int T, int D, int Vp1, int k, int32_t* topk_id,
+                   float* topk_logp, float* lse, float* logits_out);
+
+/*
+ * Stage 3 - CTC transform and token tree (paper Sec. 3.1 "CTC Transform Module", Sec. 3.3; collapse
+ * rule beta^-1 of Sec. 2.2; candidate value = Eq. 6; tree verification layout of Sec. 2.1).
+ *
+ * Every rank tuple r in {0..k-1}^T is a raw candidate a_t = topk_id[t, r_t] with index
+ * idx(r) = sum_t r_t * k^(T-1-t) and score s(r) = (((l_0 + l_1) + l_2) + ...), l_t =
+ * topk_logp[t, r_t], summed in float32 in that order.  Raw candidates are collapsed (merge adjacent
+ * equal symbols, then delete blank_id); equal collapsed sequences are one draft whose score is its
+ * best raw candidate's and whose representative is the best-scoring raw candidate of smallest idx;
+ * the empty draft is dropped.  Drafts ordered by (score descending, representative idx ascending);
+ * the first `beam` are kept.  They are inserted in that order into a prefix tree below node 0 (the
+ * root, token root_token[b]): node ids are creation order, nothing is created once the tree holds
+ * max_nodes nodes (drafts cut short keep their created prefix).
+ *
+ * topk_id, topk_logp  [B,T,k]   in (as written by ctc_draft_topk; logp descending per slot is
+ *                     not required)
+ * root_token   [B] int32        in: the base model's own greedy token
+ * n_cand       [B] int32        out: drafts kept (<= beam)
+ * cand_tokens  [B,beam,T] int32 out, unused positions -1
+ * cand_len     [B,beam] int32   out, 0 beyond n_cand
+ * cand_score   [B,beam] float   out, -inf beyond n_cand
+ * cand_leaf    [B,beam] int32   out: node of the draft's last token, -1 if cut by the node cap or
+ *                               beyond n_cand
+ * n_nodes      [B] int32        out: 1..max_nodes
+ * node_token, node_parent, node_depth  [B,max_nodes] int32 out; root: parent -1, depth 0; entries
+ *                               beyond n_nodes are -1
+ * anc_mask     [B,max_nodes,ceil(max_nodes/64)] uint64 out: bit (j%64) of word j/64 of row i is 1
+ *              iff node j is on the path root..i (both ends included); rows beyond n_nodes are 0
+ * Limits: T <= CTCSPEC_MAX_SLOTS, k <= CTCSPEC_MAX_TOPK, k^T <= CTCSPEC_MAX_ALIGNMENTS,
+ * 1 <= beam <= CTCSPEC_MAX_BEAM, 1 <= max_nodes <= CTCSPEC_MAX_NODES.
+ */
+int ctc_collapse_tree(ctcspec_ctx* ctx, const int32_t* topk_id, const float* topk_logp,
+                      const int32_t* root_token, int B, int T, int k, int32_t blank_id, int beam,
+                      int max_nodes, int32_t* n_cand, int32_t* cand_tokens, int32_t* cand_len,
+                      float* cand_score, int32_t* cand_leaf, int32_t* n_nodes, int32_t* node_token,
+                      int32_t* node_parent, int32_t* node_depth, uint64_t* anc_mask);
+
+/*
+ * Stage 4a - one attention layer of the base model's parallel verification pass over the token tree
+ * (paper Sec. 2.1 tree verification, Sec. 3.1 masked attention map, Sec. 3.3 "all candidates are
+ * verified parallelly").  For sequence b, head h and node i < n_nodes[b]:
+ *
+ *   keys(i) = the ctx_len[b] cached positions (all visible) + the tree nodes j with bit j of
+ *             anc_mask row i set
+ *   out[b,h,i,:] = sum_{j in keys(i)} softmax_j(scale * q[b,h,i,:] . key_j) * value_j
+ *
+ * No positional encoding is applied here: q and keys arrive as the attention operands.
+ *
+ * dt           element type of q, k_cache, v_cache, k_tree, v_tree
+ * q, k_tree, v_tree   [B,H,max_nodes,dh]   16-byte aligned; rows >= n_nodes[b] are never used
+ * k_cache, v_cache    base pointers; sequence b's block starts kv_off[b] ELEMENTS after the base and
+ *                     is laid out [H][kv_cap][dh]; only the first ctx_len[b] rows of each head are
+ *                     read (rows beyond may hold anything, NaN included).  kv_off[b]*sizeof(elem)
+ *                     must be a multiple of 16.
+ * kv_off       [B] int64 device, ctx_len [B] int32 device (0 <= ctx_len[b] <= kv_cap)
+ * n_nodes      [B] int32 device, anc_mask as written by ctc_collapse_tree
+ * scale        softmax scale, normally 1/sqrt(dh)
+ * out          [B,H,max_nodes,dh] float out; rows >= n_nodes[b] are unspecified
+ * Limits: dh <= CTCSPEC_MAX_HEAD_DIM and dh % 8 == 0, max_nodes <= CTCSPEC_MAX_NODES, H <= limits.
+ */
+int tree_verify_attn(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* q, const void* k_cache,
+                     const void* v_cache, const int64_t* kv_off, const int32_t* ctx_len, int kv_cap,
+                     const void* k_tree, const void* v_tree, const int32_t* n_nodes,
+                     const uint64_t* anc_mask, int B, int H, int dh, int max_nodes, float scale,
+                     float* out);
+
+/*
+ * Stage 4b - greedy acceptance (paper Sec. 2.1: accept what matches the target model's greedy
+ * output; Sec. 3.3: "the longest sequence that satisfies the criterion").  target_argmax[b,i] is
+ * the base model's greedy token after node i.  From the root, step to the child whose token equals
+ * target_argmax at the current node; stop when there is none.
+ *
+ * n_nodes, node_token, node_parent, node_depth   as written by ctc_collapse_tree
+ * target_argmax [B,max_nodes] int32 in
+ * accept_len    [B] int32 out: draft tokens accepted (0..T); the root is always part of the output
+ * accept_nodes  [B,T+1] int32 out: the accepted path, root first, -1 beyond
+ * accept_tokens [B,T+1] int32 out: tokens of those nodes, -1 beyond
+ * next_token    [B] int32 out: target_argmax at the last accepted node (the bonus token)
+ */
+int accept_longest(ctcspec_ctx* ctx, const int32_t* n_nodes, const int32_t* node_token,
+                   const int32_t* node_parent, const int32_t* node_depth,
+                   const int32_t* target_argmax, int B, int T, int max_nodes, int32_t* accept_len,
+                   int32_t* accept_nodes, int32_t* accept_tokens, int32_t* next_token);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CTCSPEC_H */

@@ -1,0 +1,17 @@
+"""MI355X-native per-step device work of CTC-drafted speculative decoding.
+
+The product is `libctcspec.so`, a C-ABI library of hand-written HIP kernels for gfx950 (see
+`include/ctcspec.h`).  This package is the thin Python binding over it: it marshals torch device
+tensors into the C calls and nothing else.  There is no CPU fallback: importing the binding without
+the built library raises.
+"""
+from .binding import (  # noqa: F401
+    Context,
+    CtcspecError,
+    accept_longest,
+    ctc_collapse_tree,
+    ctc_draft_topk,
+    library_path,
+    load_library,
+    tree_verify_attn,
+)

@@ -1,0 +1,225 @@
+"""ctypes binding of libctcspec.so.  Argument marshalling only: every step runs in the HIP kernels.
+
+Each function has the name of the C entry point it calls and takes torch tensors that already live on
+the GPU.  Output tensors are allocated with torch when the caller does not pass them in `out`.
+"""
+import ctypes
+import os
+from ctypes import POINTER, c_char_p, c_float, c_int, c_int32, c_int64, c_size_t, c_void_p
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTS = (
+    "ctcspec_create", "ctcspec_destroy", "ctcspec_set_stream", "ctcspec_last_error",
+    "ctcspec_workspace_bytes", "ctc_draft_topk", "ctc_collapse_tree", "tree_verify_attn",
+    "accept_longest",
+)
+
+CTCSPEC_F32, CTCSPEC_BF16 = 0, 1
+
+
+class CtcspecError(RuntimeError):
+    pass
+
+
+class _Limits(ctypes.Structure):
+    _fields_ = [(n, c_int) for n in ("max_batch", "max_slots", "max_topk", "max_vocab_rows",
+                                     "max_nodes", "max_heads", "max_head_dim")]
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libctcspec.so")
+
+
+def load_library():
+    """Load the built library; fail loudly when it is missing (there is no fallback path)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise CtcspecError(
+            f"{path} is missing: build it with `python -m paper_2412_00061_amd.build` "
+            "(the HIP library is the only implementation; there is no CPU fallback)")
+    lib = ctypes.CDLL(path)
+    lib.ctcspec_create.restype = c_int
+    lib.ctcspec_create.argtypes = [POINTER(c_void_p), c_void_p, POINTER(_Limits)]
+    lib.ctcspec_destroy.restype = None
+    lib.ctcspec_destroy.argtypes = [c_void_p]
+    lib.ctcspec_set_stream.restype = c_int
+    lib.ctcspec_set_stream.argtypes = [c_void_p, c_void_p]
+    lib.ctcspec_last_error.restype = c_char_p
+    lib.ctcspec_last_error.argtypes = [c_void_p]
+    lib.ctcspec_workspace_bytes.restype = c_size_t
+    lib.ctcspec_workspace_bytes.argtypes = [c_void_p]
+    lib.ctc_draft_topk.restype = c_int
+    lib.ctc_draft_topk.argtypes = [c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int,
+                                   c_int, c_int, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.ctc_collapse_tree.restype = c_int
+    lib.ctc_collapse_tree.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int32,
+                                      c_int, c_int] + [c_void_p] * 10
+    lib.tree_verify_attn.restype = c_int
+    lib.tree_verify_attn.argtypes = [c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                     c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int,
+                                     c_int, c_float, c_void_p]
+    lib.accept_longest.restype = c_int
+    lib.accept_longest.argtypes = [c_void_p] * 6 + [c_int, c_int, c_int] + [c_void_p] * 4
+    _LIB = lib
+    return lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return CTCSPEC_F32
+    if t.dtype == torch.bfloat16:
+        return CTCSPEC_BF16
+    raise CtcspecError(f"unsupported element type {t.dtype}")
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise CtcspecError("tensors must be contiguous GPU tensors")
+    if dtype is not None and t.dtype != dtype:
+        raise CtcspecError(f"expected {dtype}, got {t.dtype}")
+    return c_void_p(t.data_ptr())
+
+
+class Context:
+    """Owns a ctcspec_ctx: the library's device workspace bound to one HIP stream."""
+
+    def __init__(self, *, max_batch, max_slots, max_topk, max_vocab_rows, max_nodes, max_heads,
+                 max_head_dim, stream=None):
+        self.lib = load_library()
+        if not torch.cuda.is_available():
+            raise CtcspecError("no GPU visible: libctcspec runs on an MI355X only")
+        lim = _Limits(max_batch, max_slots, max_topk, max_vocab_rows, max_nodes, max_heads, max_head_dim)
+        stream = torch.cuda.current_stream() if stream is None else stream
+        self.stream = stream
+        handle = c_void_p()
+        rc = self.lib.ctcspec_create(ctypes.byref(handle), c_void_p(stream.cuda_stream), ctypes.byref(lim))
+        if rc != 0:
+            raise CtcspecError(f"ctcspec_create failed ({rc}): {self.lib.ctcspec_last_error(None).decode()}")
+        self.handle = handle
+
+    @classmethod
+    def for_config(cls, cfg, stream=None):
+        return cls(max_batch=cfg.B, max_slots=cfg.T, max_topk=cfg.k, max_vocab_rows=cfg.Vp1,
+                   max_nodes=cfg.max_nodes, max_heads=cfg.H, max_head_dim=cfg.dh, stream=stream)
+
+    def set_stream(self, stream):
+        self.stream = stream
+        self._check(self.lib.ctcspec_set_stream(self.handle, c_void_p(stream.cuda_stream)), "ctcspec_set_stream")
+
+    def workspace_bytes(self) -> int:
+        return int(self.lib.ctcspec_workspace_bytes(self.handle))
+
+    def last_error(self) -> str:
+        return self.lib.ctcspec_last_error(self.handle).decode()
+
+    def _check(self, rc, what):
+        if rc != 0:
+            raise CtcspecError(f"{what} failed ({rc}): {self.last_error()}")
+
+    def close(self):
+        if getattr(self, "handle", None):
+            self.lib.ctcspec_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _out(out, name, shape, dtype, device):
+    if out is not None and name in out:
+        t = out[name]
+        if tuple(t.shape) != tuple(shape) or t.dtype != dtype:
+            raise CtcspecError(f"out[{name!r}] must be {dtype} {tuple(shape)}")
+        return t
+    return torch.empty(shape, dtype=dtype, device=device)
+
+
+def ctc_draft_topk(ctx, hidden, w, bias, k, *, want_logits=False, out=None):
+    """hidden [B,T,D], w [V+1,D] (same dtype), bias [V+1] f32 or None -> dict(topk_id, topk_logp, lse[, logits])."""
+    B, T, D = hidden.shape
+    Vp1 = w.shape[0]
+    if w.shape[1] != D or w.dtype != hidden.dtype:
+        raise CtcspecError("w must be [V+1, D] with hidden's dtype")
+    dev = hidden.device
+    res = {
+        "topk_id": _out(out, "topk_id", (B, T, k), torch.int32, dev),
+        "topk_logp": _out(out, "topk_logp", (B, T, k), torch.float32, dev),
+        "lse": _out(out, "lse", (B, T), torch.float32, dev),
+    }
+    if want_logits:
+        res["logits"] = _out(out, "logits", (B, T, Vp1), torch.float32, dev)
+    rc = ctx.lib.ctc_draft_topk(ctx.handle, _dtype_code(hidden), _ptr(hidden), _ptr(w),
+                                _ptr(bias, torch.float32), B, T, D, Vp1, k, _ptr(res["topk_id"]),
+                                _ptr(res["topk_logp"]), _ptr(res["lse"]), _ptr(res.get("logits")))
+    ctx._check(rc, "ctc_draft_topk")
+    return res
+
+
+def ctc_collapse_tree(ctx, topk_id, topk_logp, root_token, blank_id, beam, max_nodes, *, out=None):
+    """topk_id/topk_logp [B,T,k], root_token [B] -> dict of the drafts, the tree and its ancestor mask."""
+    B, T, k = topk_id.shape
+    dev = topk_id.device
+    words = (max_nodes + 63) // 64
+    res = {
+        "n_cand": _out(out, "n_cand", (B,), torch.int32, dev),
+        "cand_tokens": _out(out, "cand_tokens", (B, beam, T), torch.int32, dev),
+        "cand_len": _out(out, "cand_len", (B, beam), torch.int32, dev),
+        "cand_score": _out(out, "cand_score", (B, beam), torch.float32, dev),
+        "cand_leaf": _out(out, "cand_leaf", (B, beam), torch.int32, dev),
+        "n_nodes": _out(out, "n_nodes", (B,), torch.int32, dev),
+        "node_token": _out(out, "node_token", (B, max_nodes), torch.int32, dev),
+        "node_parent": _out(out, "node_parent", (B, max_nodes), torch.int32, dev),
+        "node_depth": _out(out, "node_depth", (B, max_nodes), torch.int32, dev),
+        "anc_mask": _out(out, "anc_mask", (B, max_nodes, words), torch.int64, dev),
+    }
+    rc = ctx.lib.ctc_collapse_tree(
+        ctx.handle, _ptr(topk_id, torch.int32), _ptr(topk_logp, torch.float32), _ptr(root_token, torch.int32),
+        B, T, k, blank_id, beam, max_nodes, _ptr(res["n_cand"]), _ptr(res["cand_tokens"]),
+        _ptr(res["cand_len"]), _ptr(res["cand_score"]), _ptr(res["cand_leaf"]), _ptr(res["n_nodes"]),
+        _ptr(res["node_token"]), _ptr(res["node_parent"]), _ptr(res["node_depth"]), _ptr(res["anc_mask"]))
+    ctx._check(rc, "ctc_collapse_tree")
+    return res
+
+
+def tree_verify_attn(ctx, q, k_cache, v_cache, kv_off, ctx_len, kv_cap, k_tree, v_tree, n_nodes, anc_mask,
+                     scale, *, out=None):
+    """q/k_tree/v_tree [B,H,max_nodes,dh]; k_cache/v_cache flat buffers addressed through kv_off -> out f32."""
+    B, H, max_nodes, dh = q.shape
+    o = _out(None if out is None else {"out": out}, "out", (B, H, max_nodes, dh), torch.float32, q.device)
+    rc = ctx.lib.tree_verify_attn(
+        ctx.handle, _dtype_code(q), _ptr(q), _ptr(k_cache, q.dtype), _ptr(v_cache, q.dtype),
+        _ptr(kv_off, torch.int64), _ptr(ctx_len, torch.int32), kv_cap, _ptr(k_tree, q.dtype),
+        _ptr(v_tree, q.dtype), _ptr(n_nodes, torch.int32), _ptr(anc_mask, torch.int64), B, H, dh, max_nodes,
+        c_float(scale), _ptr(o))
+    ctx._check(rc, "tree_verify_attn")
+    return o
+
+
+def accept_longest(ctx, n_nodes, node_token, node_parent, node_depth, target_argmax, T, *, out=None):
+    """Greedy acceptance walk -> dict(accept_len [B], accept_nodes [B,T+1], accept_tokens [B,T+1], next_token [B])."""
+    B, max_nodes = node_token.shape
+    dev = node_token.device
+    res = {
+        "accept_len": _out(out, "accept_len", (B,), torch.int32, dev),
+        "accept_nodes": _out(out, "accept_nodes", (B, T + 1), torch.int32, dev),
+        "accept_tokens": _out(out, "accept_tokens", (B, T + 1), torch.int32, dev),
+        "next_token": _out(out, "next_token", (B,), torch.int32, dev),
+    }
+    rc = ctx.lib.accept_longest(
+        ctx.handle, _ptr(n_nodes, torch.int32), _ptr(node_token, torch.int32), _ptr(node_parent, torch.int32),
+        _ptr(node_depth, torch.int32), _ptr(target_argmax, torch.int32), B, T, max_nodes,
+        _ptr(res["accept_len"]), _ptr(res["accept_nodes"]), _ptr(res["accept_tokens"]), _ptr(res["next_token"]))
+    ctx._check(rc, "accept_longest")
+    return res

@@ -1,0 +1,67 @@
+// accept_longest: greedy acceptance walk over the token tree, one wavefront per sequence.
+#include "common.h"
+
+namespace ctcspec {
+
+// Lane l looks at nodes l and l+64.  At each step the lanes whose node is a child of the current
+// node carrying the target token raise a ballot; sibling tokens are distinct, so at most one does.
+__global__ __launch_bounds__(64) void accept_longest_kernel(const int32_t* n_nodes, const int32_t* node_token,
+                                                            const int32_t* node_parent,
+                                                            const int32_t* target, int T, int max_nodes,
+                                                            int32_t* accept_len, int32_t* accept_nodes,
+                                                            int32_t* accept_tokens, int32_t* next_token) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  int n = n_nodes[b];
+  n = n < 1 ? 1 : (n > max_nodes ? max_nodes : n);
+  const int32_t* tok = node_token + (size_t)b * max_nodes;
+  const int32_t* par = node_parent + (size_t)b * max_nodes;
+  const int32_t* tgt = target + (size_t)b * max_nodes;
+  const int j0 = lane, j1 = lane + 64;
+  const int t0 = j0 < n ? tok[j0] : -1, p0 = j0 < n ? par[j0] : -2;
+  const int t1 = j1 < n ? tok[j1] : -1, p1 = j1 < n ? par[j1] : -2;
+  int cur = 0, len = 0;
+  int32_t* out_nodes = accept_nodes + (size_t)b * (T + 1);
+  int32_t* out_tokens = accept_tokens + (size_t)b * (T + 1);
+  if (lane == 0) { out_nodes[0] = 0; out_tokens[0] = tok[0]; }
+  while (len < T) {
+    const int want = tgt[cur];
+    unsigned long long hit0 = __ballot(j0 > 0 && p0 == cur && t0 == want);
+    unsigned long long hit1 = __ballot(p1 == cur && t1 == want);
+    int nxt = -1;
+    if (hit0) nxt = __builtin_ctzll(hit0);
+    else if (hit1) nxt = 64 + __builtin_ctzll(hit1);
+    if (nxt < 0) break;
+    cur = nxt;
+    ++len;
+    if (lane == 0) { out_nodes[len] = cur; out_tokens[len] = want; }
+  }
+  if (lane == 0) {
+    for (int i = len + 1; i <= T; ++i) { out_nodes[i] = -1; out_tokens[i] = -1; }
+    accept_len[b] = len;
+    next_token[b] = tgt[cur];
+  }
+}
+
+}  // namespace ctcspec
+
+using namespace ctcspec;
+
+extern "C" int accept_longest(ctcspec_ctx* ctx, const int32_t* n_nodes, const int32_t* node_token,
+                              const int32_t* node_parent, const int32_t* node_depth,
+                              const int32_t* target_argmax, int B, int T, int max_nodes, int32_t* accept_len,
+                              int32_t* accept_nodes, int32_t* accept_tokens, int32_t* next_token) {
+  if (!ctx) return CTCSPEC_EINVAL;
+  (void)node_depth;  // the walk needs parents and tokens only; depth is accepted for symmetry with stage 3
+  CTCSPEC_REQUIRE(ctx,
+                  n_nodes && node_token && node_parent && target_argmax && accept_len && accept_nodes &&
+                      accept_tokens && next_token,
+                  CTCSPEC_EINVAL, "accept_longest: null pointer");
+  CTCSPEC_REQUIRE(ctx, B > 0 && T > 0 && max_nodes > 0, CTCSPEC_EINVAL, "accept_longest: sizes must be positive");
+  CTCSPEC_REQUIRE(ctx, max_nodes <= CTCSPEC_MAX_NODES && T <= CTCSPEC_MAX_SLOTS, CTCSPEC_EUNSUPPORTED,
+                  "accept_longest: max_nodes<=%d and T<=%d required", CTCSPEC_MAX_NODES, CTCSPEC_MAX_SLOTS);
+  hipLaunchKernelGGL(accept_longest_kernel, dim3(B), dim3(64), 0, ctx->stream, n_nodes, node_token,
+                     node_parent, target_argmax, T, max_nodes, accept_len, accept_nodes, accept_tokens,
+                     next_token);
+  CTCSPEC_HIP(ctx, hipGetLastError());
+  return CTCSPEC_OK;
+}

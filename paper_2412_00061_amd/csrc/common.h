@@ -1,0 +1,149 @@
+// Internal definitions shared by the translation units of libctcspec (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "ctcspec.h"
+
+namespace ctcspec {
+
+constexpr int kWave = 64;
+
+// ---- draft head workspace geometry -------------------------------------------------------------
+// A workgroup of the draft-head kernels owns kRowsPerBlock consecutive vocabulary rows and leaves one
+// partial result per column: running max, sum of exponentials and its k best (logit, id) keys.
+constexpr int kRowsPerBlock = 128;
+constexpr int kMaxCols = CTCSPEC_MAX_COLUMNS;
+constexpr int kMaxTopk = CTCSPEC_MAX_TOPK;
+
+// ---- collapse/tree workspace geometry ----------------------------------------------------------
+constexpr int kMaxAlign = CTCSPEC_MAX_ALIGNMENTS;
+// Per sequence, for the rare case that more raw candidates than fit in LDS must be ordered:
+// sort keys, collapsed-sequence keys (8 B each) and a hash table of 2*kMaxAlign 4-byte slots.
+constexpr size_t kCollapseWsBytesPerSeq = (size_t)kMaxAlign * 8 * 2 + (size_t)kMaxAlign * 2 * 4;
+
+// ---- attention workspace geometry --------------------------------------------------------------
+constexpr int kMaxKvSplits = 8;
+
+}  // namespace ctcspec
+
+struct ctcspec_ctx {
+  hipStream_t stream;
+  int device;
+  ctcspec_limits lim;
+  char err[256];
+  // one device allocation, carved up below
+  void* ws;
+  size_t ws_bytes;
+  // draft head
+  int lm_max_blocks;
+  float* lm_pmax;               // [lm_max_blocks][kMaxCols]
+  float* lm_psum;               // [lm_max_blocks][kMaxCols]
+  unsigned long long* lm_pkey;  // [lm_max_blocks][kMaxCols][kMaxTopk]
+  unsigned int* lm_ticket;      // [1], zero between calls
+  // collapse / tree
+  unsigned char* collapse_ws;   // [max_batch][kCollapseWsBytesPerSeq]
+  // attention
+  int attn_units;               // number of (sequence, head, split) partial slots
+  float* attn_po;               // [attn_units][max_nodes][max_head_dim]
+  float* attn_pm;               // [attn_units][max_nodes]
+  float* attn_pl;               // [attn_units][max_nodes]
+};
+
+namespace ctcspec {
+
+int fail(ctcspec_ctx* ctx, int code, const char* fmt, ...);
+
+#define CTCSPEC_REQUIRE(ctx, cond, code, ...) \
+  do {                                        \
+    if (!(cond)) return ::ctcspec::fail((ctx), (code), __VA_ARGS__); \
+  } while (0)
+
+#define CTCSPEC_HIP(ctx, expr)                                                              \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return ::ctcspec::fail((ctx), CTCSPEC_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---- device helpers ----------------------------------------------------------------------------
+#if defined(__HIPCC__)
+
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// Monotone map float -> uint32 (a < b  <=>  ord(a) < ord(b)); -0 is first turned into +0.
+__device__ __forceinline__ unsigned int float_to_ordered(float f) {
+  f = f + 0.0f;
+  unsigned int u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ordered_to_float(unsigned int o) {
+  unsigned int u = (o & 0x80000000u) ? (o & 0x7fffffffu) : ~o;
+  return __uint_as_float(u);
+}
+
+// Ranking key of a (value, index) pair: larger value first, then smaller index first.
+__device__ __forceinline__ unsigned long long rank_key(float v, unsigned int idx) {
+  return ((unsigned long long)float_to_ordered(v) << 32) | (unsigned long long)(0xffffffffu - idx);
+}
+__device__ __forceinline__ float rank_key_value(unsigned long long key) {
+  return ordered_to_float((unsigned int)(key >> 32));
+}
+__device__ __forceinline__ unsigned int rank_key_index(unsigned long long key) {
+  return 0xffffffffu - (unsigned int)(key & 0xffffffffu);
+}
+
+__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int mask) {
+  unsigned int lo = (unsigned int)v, hi = (unsigned int)(v >> 32);
+  lo = __shfl_xor(lo, mask, kWave);
+  hi = __shfl_xor(hi, mask, kWave);
+  return ((unsigned long long)hi << 32) | lo;
+}
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    unsigned long long o = shfl_xor_u64(v, m);
+    v = o > v ? o : v;
+  }
+  return v;
+}
+__device__ __forceinline__ float wave_max_f32(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
+  return v;
+}
+__device__ __forceinline__ float wave_sum_f32(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+__device__ __forceinline__ int wave_sum_i32(int v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(unsigned short b) {
+  return __uint_as_float(((unsigned int)b) << 16);
+}
+
+template <typename T>
+__device__ __forceinline__ float load_as_float(const T* p);
+template <>
+__device__ __forceinline__ float load_as_float<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float load_as_float<unsigned short>(const unsigned short* p) {
+  return bf16_bits_to_float(*p);
+}
+
+#endif  // __HIPCC__
+
+}  // namespace ctcspec

@@ -1,0 +1,120 @@
+// Context of libctcspec: stream binding, limits, the one device workspace, error reporting.
+#include <stdarg.h>
+#include <stdlib.h>
+
+#include <new>
+
+#include "common.h"
+
+namespace ctcspec {
+
+static thread_local char g_create_err[256] = "";
+
+int fail(ctcspec_ctx* ctx, int code, const char* fmt, ...) {
+  char* dst = ctx ? ctx->err : g_create_err;
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(dst, 256, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace ctcspec
+
+using namespace ctcspec;
+
+extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec_limits* lim) {
+  if (out) *out = nullptr;
+  CTCSPEC_REQUIRE(nullptr, out && lim, CTCSPEC_EINVAL, "ctcspec_create: null argument");
+  CTCSPEC_REQUIRE(nullptr,
+                  lim->max_batch > 0 && lim->max_slots > 0 && lim->max_topk > 0 &&
+                      lim->max_vocab_rows > 0 && lim->max_nodes > 0 && lim->max_heads > 0 &&
+                      lim->max_head_dim > 0,
+                  CTCSPEC_EINVAL, "ctcspec_create: every limit must be positive");
+  CTCSPEC_REQUIRE(nullptr,
+                  lim->max_slots <= CTCSPEC_MAX_SLOTS && lim->max_topk <= CTCSPEC_MAX_TOPK &&
+                      lim->max_nodes <= CTCSPEC_MAX_NODES &&
+                      lim->max_head_dim <= CTCSPEC_MAX_HEAD_DIM &&
+                      (long long)lim->max_batch * lim->max_slots <= CTCSPEC_MAX_COLUMNS,
+                  CTCSPEC_EUNSUPPORTED,
+                  "ctcspec_create: limits exceed the compiled maxima (T<=%d, k<=%d, nodes<=%d, "
+                  "dh<=%d, B*T<=%d)",
+                  CTCSPEC_MAX_SLOTS, CTCSPEC_MAX_TOPK, CTCSPEC_MAX_NODES, CTCSPEC_MAX_HEAD_DIM,
+                  CTCSPEC_MAX_COLUMNS);
+  ctcspec_ctx* ctx = new (std::nothrow) ctcspec_ctx();
+  CTCSPEC_REQUIRE(nullptr, ctx, CTCSPEC_EINVAL, "ctcspec_create: out of host memory");
+  memset(ctx, 0, sizeof(*ctx));
+  ctx->stream = (hipStream_t)hip_stream;
+  ctx->lim = *lim;
+  hipError_t e = hipGetDevice(&ctx->device);
+  if (e != hipSuccess) {
+    delete ctx;
+    return fail(nullptr, CTCSPEC_EHIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+  }
+
+  ctx->lm_max_blocks = (lim->max_vocab_rows + kRowsPerBlock - 1) / kRowsPerBlock;
+  long long bh = (long long)lim->max_batch * lim->max_heads;
+  ctx->attn_units = (int)(bh > 256 ? bh : 256);
+
+  size_t off = 0;
+  auto carve = [&](size_t bytes) {
+    size_t at = off;
+    off = align_up(off + bytes, 256);
+    return at;
+  };
+  size_t o_pmax = carve((size_t)ctx->lm_max_blocks * kMaxCols * sizeof(float));
+  size_t o_psum = carve((size_t)ctx->lm_max_blocks * kMaxCols * sizeof(float));
+  size_t o_pkey = carve((size_t)ctx->lm_max_blocks * kMaxCols * kMaxTopk * sizeof(unsigned long long));
+  size_t o_tick = carve(256);
+  size_t o_coll = carve((size_t)lim->max_batch * kCollapseWsBytesPerSeq);
+  size_t o_po = carve((size_t)ctx->attn_units * lim->max_nodes * lim->max_head_dim * sizeof(float));
+  size_t o_pm = carve((size_t)ctx->attn_units * lim->max_nodes * sizeof(float));
+  size_t o_pl = carve((size_t)ctx->attn_units * lim->max_nodes * sizeof(float));
+  ctx->ws_bytes = off;
+  e = hipMalloc(&ctx->ws, ctx->ws_bytes);
+  if (e != hipSuccess) {
+    delete ctx;
+    return fail(nullptr, CTCSPEC_EHIP, "hipMalloc of %zu workspace bytes failed: %s", off,
+                hipGetErrorString(e));
+  }
+  unsigned char* base = (unsigned char*)ctx->ws;
+  ctx->lm_pmax = (float*)(base + o_pmax);
+  ctx->lm_psum = (float*)(base + o_psum);
+  ctx->lm_pkey = (unsigned long long*)(base + o_pkey);
+  ctx->lm_ticket = (unsigned int*)(base + o_tick);
+  ctx->collapse_ws = base + o_coll;
+  ctx->attn_po = (float*)(base + o_po);
+  ctx->attn_pm = (float*)(base + o_pm);
+  ctx->attn_pl = (float*)(base + o_pl);
+  // the ticket must start at zero; kernels leave it at zero again
+  e = hipMemsetAsync(ctx->lm_ticket, 0, 256, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) {
+    (void)hipFree(ctx->ws);
+    delete ctx;
+    return fail(nullptr, CTCSPEC_EHIP, "workspace initialisation failed: %s", hipGetErrorString(e));
+  }
+  g_create_err[0] = 0;
+  *out = ctx;
+  return CTCSPEC_OK;
+}
+
+extern "C" void ctcspec_destroy(ctcspec_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->ws) (void)hipFree(ctx->ws);
+  delete ctx;
+}
+
+extern "C" int ctcspec_set_stream(ctcspec_ctx* ctx, void* hip_stream) {
+  if (!ctx) return CTCSPEC_EINVAL;
+  ctx->stream = (hipStream_t)hip_stream;
+  return CTCSPEC_OK;
+}
+
+extern "C" const char* ctcspec_last_error(const ctcspec_ctx* ctx) {
+  return ctx ? ctx->err : g_create_err;
+}
+
+extern "C" size_t ctcspec_workspace_bytes(const ctcspec_ctx* ctx) { return ctx ? ctx->ws_bytes : 0; }

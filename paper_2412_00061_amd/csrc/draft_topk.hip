@@ -1,0 +1,357 @@
+// ctc_draft_topk: LM head over vocabulary + blank, log-softmax and per-slot top-k in one pass over W.
+//
+// The head weights are read exactly once.  A workgroup owns 128 consecutive vocabulary rows; it
+// leaves, per column (= draft slot of some sequence), the running max, the sum of exponentials and
+// its k best (logit, id) pairs.  The workgroup that finishes last (atomic ticket) merges the
+// partials of all workgroups into lse / topk_id / topk_logp, so the whole stage is one launch.
+//
+// Two producers of the 128 x columns logit block exist:
+//   * lmhead_bf16_mfma_kernel  - bf16 operands, v_mfma_f32_16x16x32_bf16, HBM-streaming design
+//   * lmhead_generic_kernel    - any dtype/shape within the limits, plain fp32 FMA
+// Both hand the block over in LDS to the same epilogue.
+#include "common.h"
+
+namespace ctcspec {
+
+constexpr int kZStride = kRowsPerBlock + 4;  // floats per column in the LDS logit block
+constexpr int kWRowStride = 512 + 16;        // bytes per staged W row (256 bf16 + pad, conflict-free)
+constexpr int kWStageBytes = 16 * kWRowStride;  // per wave
+constexpr int kMfmaWaves = 8;
+
+struct LmHeadParams {
+  const void* hidden;
+  const void* w;
+  const float* bias;
+  int BT, D, Vp1, k;
+  int KC;        // mfma kernel: hidden-state chunk held in LDS (elements)
+  int hs_bytes;  // mfma kernel: bytes of the LDS hidden-state region
+  int n_blocks;
+  float* pmax;
+  float* psum;
+  unsigned long long* pkey;
+  unsigned int* ticket;
+  int32_t* topk_id;
+  float* topk_logp;
+  float* lse;
+  float* logits_out;
+};
+
+// Sorted (descending) register list of the best keys seen by one lane.
+template <int KMAX>
+struct KeyList {
+  unsigned long long v[KMAX];
+  __device__ __forceinline__ void clear() {
+#pragma unroll
+    for (int i = 0; i < KMAX; ++i) v[i] = 0ull;
+  }
+  __device__ __forceinline__ void insert(unsigned long long key) {
+#pragma unroll
+    for (int i = 0; i < KMAX; ++i) {
+      unsigned long long hi = key > v[i] ? key : v[i];
+      unsigned long long lo = key > v[i] ? v[i] : key;
+      v[i] = hi;
+      key = lo;
+    }
+  }
+  __device__ __forceinline__ void pop() {
+#pragma unroll
+    for (int i = 0; i + 1 < KMAX; ++i) v[i] = v[i + 1];
+    v[KMAX - 1] = 0ull;
+  }
+};
+
+// Epilogue shared by both producers.  zbuf holds the block's logits column-major:
+// zbuf[col * kZStride + r] = z of row (blockIdx.x*128 + r), -inf for rows >= Vp1.
+// All threads of the workgroup must call this (it contains barriers).
+__device__ void lmhead_block_epilogue(const LmHeadParams& p, const float* zbuf, unsigned int* flag_lds) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nwaves = blockDim.x >> 6;
+  const int row_base = blockIdx.x * kRowsPerBlock;
+  const int k = p.k;
+
+  if (p.logits_out) {
+    for (int idx = tid; idx < p.BT * kRowsPerBlock; idx += blockDim.x) {
+      int m = idx / kRowsPerBlock, r = idx % kRowsPerBlock;
+      if (row_base + r < p.Vp1) p.logits_out[(size_t)m * p.Vp1 + row_base + r] = zbuf[m * kZStride + r];
+    }
+  }
+
+  // per column: max, sum of exponentials, k best keys of this block's 128 rows
+  for (int m = wave; m < p.BT; m += nwaves) {
+    float z0 = zbuf[m * kZStride + lane];
+    float z1 = zbuf[m * kZStride + lane + 64];
+    int id0 = row_base + lane, id1 = row_base + lane + 64;
+    float mx = wave_max_f32(fmaxf(z0, z1));
+    float e = 0.f;
+    if (mx > -INFINITY) e = __expf(z0 - mx) + __expf(z1 - mx);
+    float s = wave_sum_f32(e);
+    unsigned long long a = id0 < p.Vp1 ? rank_key(z0, (unsigned)id0) : 0ull;
+    unsigned long long b = id1 < p.Vp1 ? rank_key(z1, (unsigned)id1) : 0ull;
+    if (b > a) { unsigned long long t = a; a = b; b = t; }
+    size_t slot = (size_t)blockIdx.x * kMaxCols + m;
+    for (int r = 0; r < k; ++r) {
+      unsigned long long best = wave_max_u64(a);
+      if (lane == 0) p.pkey[slot * kMaxTopk + r] = best;
+      if (a == best) { a = b; b = 0ull; }
+    }
+    if (lane == 0) { p.pmax[slot] = mx; p.psum[slot] = s; }
+  }
+
+  // ticket: the last workgroup to arrive merges everything
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) *flag_lds = atomicAdd(p.ticket, 1u);
+  __syncthreads();
+  if (*flag_lds != (unsigned)(gridDim.x - 1)) return;
+  __threadfence();
+
+  const int nb = gridDim.x;
+  for (int m = wave; m < p.BT; m += nwaves) {
+    float mx = -INFINITY;
+    for (int b = lane; b < nb; b += 64) mx = fmaxf(mx, p.pmax[(size_t)b * kMaxCols + m]);
+    mx = wave_max_f32(mx);
+    float s = 0.f;
+    KeyList<kMaxTopk> list;
+    list.clear();
+    for (int b = lane; b < nb; b += 64) {
+      size_t slot = (size_t)b * kMaxCols + m;
+      float bm = p.pmax[slot];
+      if (bm > -INFINITY) s += p.psum[slot] * __expf(bm - mx);
+      for (int r = 0; r < k; ++r) list.insert(p.pkey[slot * kMaxTopk + r]);
+    }
+    s = wave_sum_f32(s);
+    float lse = mx + __logf(s);
+    if (lane == 0 && p.lse) p.lse[m] = lse;
+    for (int r = 0; r < k; ++r) {
+      unsigned long long best = wave_max_u64(list.v[0]);
+      if (list.v[0] == best) list.pop();
+      if (lane == 0) {
+        p.topk_id[m * k + r] = (int32_t)rank_key_index(best);
+        p.topk_logp[m * k + r] = rank_key_value(best) - lse;
+      }
+    }
+  }
+  if (tid == 0) *p.ticket = 0u;  // ready for the next call on this stream
+}
+
+// ---- generic producer ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void lmhead_generic_kernel(LmHeadParams p) {
+  __shared__ float zbuf[kMaxCols * kZStride];
+  __shared__ unsigned int flag;
+  const int tid = threadIdx.x;
+  const int row_base = blockIdx.x * kRowsPerBlock;
+  const T* hidden = (const T*)p.hidden;
+  const T* w = (const T*)p.w;
+  for (int idx = tid; idx < p.BT * kRowsPerBlock; idx += 256) {
+    int m = idx / kRowsPerBlock, r = idx % kRowsPerBlock;
+    int row = row_base + r;
+    float z = -INFINITY;
+    if (row < p.Vp1) {
+      const T* hp = hidden + (size_t)m * p.D;
+      const T* wp = w + (size_t)row * p.D;
+      float acc = 0.f;
+      for (int d = 0; d < p.D; ++d) acc = fmaf(load_as_float(hp + d), load_as_float(wp + d), acc);
+      z = acc + (p.bias ? p.bias[row] : 0.f);
+    }
+    zbuf[m * kZStride + r] = z;
+  }
+  __syncthreads();
+  lmhead_block_epilogue(p, zbuf, &flag);
+}
+
+// ---- bf16 MFMA streaming producer -----------------------------------------------------------------
+// 8 waves; wave w owns the 16 rows [block*128 + 16w, +16) over the whole hidden dimension.
+// Per step of 256 hidden elements a wave issues 8 coalesced 16-byte loads (each instruction covers
+// two rows x 512 contiguous bytes), parks them in its private LDS strip and reads them back in the
+// MFMA A-operand layout (lane = row, 8 consecutive k).  Loads run STAGES-1 steps ahead in registers.
+// The hidden states (the B operand) sit in LDS for the whole workgroup.
+template <int NT, int STAGES>
+__global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHeadParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ unsigned int flag;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int c = lane & 15, g = lane >> 4;
+  const int lrow = lane >> 5, lch = lane & 31;
+  unsigned char* hs = smem;
+  const int HSS = p.KC * 2 + 16;
+  unsigned char* wst = smem + p.hs_bytes + wave * kWStageBytes;
+  const int row0 = blockIdx.x * kRowsPerBlock + wave * 16;
+  const bool active = row0 < p.Vp1;
+
+  const unsigned char* wp[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    int row = row0 + 2 * j + lrow;
+    row = row < p.Vp1 ? row : p.Vp1 - 1;  // the ragged last tile re-reads the last valid row
+    wp[j] = (const unsigned char*)p.w + (size_t)row * p.D * 2 + lch * 16;
+  }
+  int bcol[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    int col = nt * 16 + c;
+    bcol[nt] = (col < p.BT ? col : p.BT - 1) * HSS + g * 16;
+  }
+
+  f32x4 acc[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int SPC = p.KC / 256;
+  const int nchunks = p.D / p.KC;
+  const int total_steps = p.D / 256;
+  u32x4 v[STAGES][8];
+  if (active) {
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        v[s][j] = __builtin_nontemporal_load((const u32x4*)(wp[j] + (size_t)s * 512));
+  }
+
+  for (int ch = 0; ch < nchunks; ++ch) {
+    if (ch > 0) __syncthreads();
+    {
+      const int per_row = p.KC / 8;  // 16-byte pieces per column
+      const unsigned char* src = (const unsigned char*)p.hidden + (size_t)ch * p.KC * 2;
+      for (int idx = tid; idx < p.BT * per_row; idx += 64 * kMfmaWaves) {
+        int m = idx / per_row, q = idx % per_row;
+        *(u32x4*)(hs + m * HSS + q * 16) = *(const u32x4*)(src + (size_t)m * p.D * 2 + q * 16);
+      }
+    }
+    __syncthreads();
+    if (active) {
+      for (int i0 = 0; i0 < SPC; i0 += STAGES) {
+#pragma unroll
+        for (int ss = 0; ss < STAGES; ++ss) {
+          const int i = i0 + ss;
+          const int pf = ch * SPC + i + STAGES - 1;
+          if (pf < total_steps) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+              v[(ss + STAGES - 1) % STAGES][j] =
+                  __builtin_nontemporal_load((const u32x4*)(wp[j] + (size_t)pf * 512));
+          }
+#pragma unroll
+          for (int j = 0; j < 8; ++j) *(u32x4*)(wst + (2 * j + lrow) * kWRowStride + lch * 16) = v[ss][j];
+#pragma unroll
+          for (int kk = 0; kk < 8; ++kk) {
+            bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(wst + c * kWRowStride + kk * 64 + g * 16));
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+              bf16x8 b = __builtin_bit_cast(bf16x8, *(const u32x4*)(hs + bcol[nt] + (i * 256 + kk * 32) * 2));
+              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[nt], 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+  }
+
+  // hand the 128 x BT logit block to the epilogue (the W strips are no longer needed)
+  __syncthreads();
+  float* zbuf = (float*)(smem + p.hs_bytes);
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    int col = nt * 16 + c;
+    if (col < p.BT) {
+      f32x4 z;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int row = row0 + g * 4 + i;
+        z[i] = row < p.Vp1 ? acc[nt][i] + (p.bias ? p.bias[row] : 0.f) : -INFINITY;
+      }
+      *(f32x4*)(zbuf + col * kZStride + wave * 16 + g * 4) = z;
+    }
+  }
+  __syncthreads();
+  lmhead_block_epilogue(p, zbuf, &flag);
+}
+
+static int pick_kc(int BT, int D, int stages, int budget) {
+  const int unit = 256 * stages;
+  if (D % unit != 0) return 0;
+  for (int kc = D; kc >= unit; kc -= unit) {
+    if (D % kc != 0) continue;
+    if ((long long)BT * (2 * kc + 16) <= budget) return kc;
+  }
+  return 0;
+}
+
+template <int NT, int STAGES>
+static hipError_t launch_mfma(const LmHeadParams& p, int lds_bytes, hipStream_t stream) {
+  auto kern = lmhead_bf16_mfma_kernel<NT, STAGES>;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(64 * kMfmaWaves), lds_bytes, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace ctcspec
+
+using namespace ctcspec;
+
+extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hidden, const void* w,
+                              const float* bias, int B, int T, int D, int Vp1, int k, int32_t* topk_id,
+                              float* topk_logp, float* lse, float* logits_out) {
+  if (!ctx) return CTCSPEC_EINVAL;
+  CTCSPEC_REQUIRE(ctx, hidden && w && topk_id && topk_logp, CTCSPEC_EINVAL, "ctc_draft_topk: null pointer");
+  CTCSPEC_REQUIRE(ctx, dt == CTCSPEC_F32 || dt == CTCSPEC_BF16, CTCSPEC_EINVAL, "ctc_draft_topk: bad dtype");
+  CTCSPEC_REQUIRE(ctx, B > 0 && T > 0 && D > 0 && Vp1 > 0 && k > 0, CTCSPEC_EINVAL,
+                  "ctc_draft_topk: sizes must be positive");
+  CTCSPEC_REQUIRE(ctx, aligned16(hidden) && aligned16(w), CTCSPEC_EINVAL,
+                  "ctc_draft_topk: hidden and w must be 16-byte aligned");
+  CTCSPEC_REQUIRE(ctx, (long long)B * T <= kMaxCols, CTCSPEC_EUNSUPPORTED, "ctc_draft_topk: B*T=%lld > %d",
+                  (long long)B * T, kMaxCols);
+  CTCSPEC_REQUIRE(ctx, B <= ctx->lim.max_batch && T <= ctx->lim.max_slots && k <= ctx->lim.max_topk &&
+                           Vp1 <= ctx->lim.max_vocab_rows,
+                  CTCSPEC_EUNSUPPORTED, "ctc_draft_topk: shape exceeds the context's limits");
+  CTCSPEC_REQUIRE(ctx, k <= Vp1, CTCSPEC_EINVAL, "ctc_draft_topk: k=%d > vocabulary rows %d", k, Vp1);
+
+  LmHeadParams p;
+  p.hidden = hidden; p.w = w; p.bias = bias;
+  p.BT = B * T; p.D = D; p.Vp1 = Vp1; p.k = k;
+  p.KC = 0; p.hs_bytes = 0;
+  p.n_blocks = (Vp1 + kRowsPerBlock - 1) / kRowsPerBlock;
+  p.pmax = ctx->lm_pmax; p.psum = ctx->lm_psum; p.pkey = ctx->lm_pkey; p.ticket = ctx->lm_ticket;
+  p.topk_id = topk_id; p.topk_logp = topk_logp; p.lse = lse; p.logits_out = logits_out;
+
+  if (dt == CTCSPEC_BF16) {
+    const int budget = 160 * 1024 - kMfmaWaves * kWStageBytes - 64;
+    int stages = 4;
+    int kc = pick_kc(p.BT, D, stages, budget);
+    if (kc == 0) {
+      stages = 2;
+      kc = pick_kc(p.BT, D, stages, budget);
+    }
+    if (kc > 0) {
+      p.KC = kc;
+      p.hs_bytes = p.BT * (2 * kc + 16);
+      int lds = p.hs_bytes + kMfmaWaves * kWStageBytes;
+      int nt = (p.BT + 15) / 16;
+      hipError_t e;
+      if (stages == 4) {
+        switch (nt) {
+          case 1: e = launch_mfma<1, 4>(p, lds, ctx->stream); break;
+          case 2: e = launch_mfma<2, 4>(p, lds, ctx->stream); break;
+          case 3: e = launch_mfma<3, 4>(p, lds, ctx->stream); break;
+          default: e = launch_mfma<4, 4>(p, lds, ctx->stream); break;
+        }
+      } else {
+        switch (nt) {
+          case 1: e = launch_mfma<1, 2>(p, lds, ctx->stream); break;
+          case 2: e = launch_mfma<2, 2>(p, lds, ctx->stream); break;
+          case 3: e = launch_mfma<3, 2>(p, lds, ctx->stream); break;
+          default: e = launch_mfma<4, 2>(p, lds, ctx->stream); break;
+        }
+      }
+      CTCSPEC_HIP(ctx, e);
+      return CTCSPEC_OK;
+    }
+    hipLaunchKernelGGL(lmhead_generic_kernel<unsigned short>, dim3(p.n_blocks), dim3(256), 0, ctx->stream, p);
+  } else {
+    hipLaunchKernelGGL(lmhead_generic_kernel<float>, dim3(p.n_blocks), dim3(256), 0, ctx->stream, p);
+  }
+  CTCSPEC_HIP(ctx, hipGetLastError());
+  return CTCSPEC_OK;
+}

@@ -1,0 +1,421 @@
+"""GPU parity: every stage of libctcspec against the CPU oracle on the same seeded inputs.
+
+Tolerances: logits and attention outputs within 2e-3 (relative, RMS floor; bf16 inputs with fp32
+accumulation); top-k ids, drafts, tree, mask and acceptance bit-exact when the oracle's discrete stage is
+fed the GPU's output of the stage before (fp32 logits -> ids; fp32 log-probabilities -> drafts/tree/mask;
+GPU attention output -> verifier argmax -> acceptance).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from gpu_harness import (cached_inputs, compare_stage3, dev_f32, dev_i32, dev_i64, oracle_stage3,
+                         rel_err_rms_floor, to_device)
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2412_00061_amd as m
+    m.load_library()
+    return m
+
+
+def _ctx(pkg, cfg, **over):
+    lim = dict(max_batch=cfg.B, max_slots=cfg.T, max_topk=cfg.k, max_vocab_rows=cfg.Vp1,
+               max_nodes=cfg.max_nodes, max_heads=cfg.H, max_head_dim=cfg.dh)
+    lim.update(over)
+    return pkg.Context(**lim)
+
+
+# ------------------------------------------------------------------------------------------ stage 1+2
+def _check_draft(pkg, ctx, hidden, w, bias, k, dtype):
+    dh, dw = to_device(hidden, dtype), to_device(w, dtype)
+    db = dev_f32(bias) if bias is not None else None
+    res = pkg.ctc_draft_topk(ctx, dh, dw, db, k, want_logits=True)
+    fast = pkg.ctc_draft_topk(ctx, dh, dw, db, k)  # the call the benchmark times: no logits dump
+    torch.cuda.synchronize()
+    z_gpu = res["logits"].cpu().numpy()
+    ref = oracle.draft_topk(hidden, w, bias, k)
+    err = rel_err_rms_floor(z_gpu, ref["z"])
+    assert err <= TOL, f"logits rel err {err}"
+    # discrete part chained on the GPU's own fp32 logits
+    ids_ref = oracle.topk_per_slot(z_gpu, k)
+    ids = res["topk_id"].cpu().numpy()
+    assert np.array_equal(ids, ids_ref)
+    logp_ref, lse_ref = oracle.log_softmax(z_gpu)
+    # fp32 log-sum-exp: 1e-5 of accumulated rounding plus a few ulps of the result's magnitude
+    tol_lse = 2e-5 + 4 * float(np.spacing(np.float32(np.max(np.abs(z_gpu)))))
+    assert np.max(np.abs(res["lse"].cpu().numpy() - lse_ref)) <= tol_lse
+    got_logp = res["topk_logp"].cpu().numpy()
+    assert np.max(np.abs(got_logp - np.take_along_axis(logp_ref, ids_ref, -1))) <= tol_lse
+    # float64 oracle on its own logits: lse within tolerance of the arithmetic
+    assert np.max(np.abs(res["lse"].cpu().numpy() - ref["lse"])) <= 5e-3
+    for name in ("topk_id", "topk_logp", "lse"):
+        assert torch.equal(res[name], fast[name]), name
+    return res
+
+
+@pytest.mark.parametrize("variant", ["literal", "ar1", "structured"])
+def test_draft_topk_tiny(pkg, variant):
+    cfg = workloads.get_config(0)
+    x = workloads.make_inputs(cfg, 0, variant)
+    ctx = _ctx(pkg, cfg)
+    _check_draft(pkg, ctx, x.hidden, x.w, x.bias, cfg.k, cfg.dtype)
+    ctx.close()
+
+
+@pytest.mark.parametrize("cfg_index,variant", [(1, "literal"), (1, "structured"), (3, "literal"), (4, "literal")])
+def test_draft_topk_full_size(pkg, cfg_index, variant):
+    cfg = workloads.get_config(cfg_index)
+    x = cached_inputs(cfg_index, 0, variant)
+    ctx = _ctx(pkg, cfg)
+    _check_draft(pkg, ctx, x.hidden, x.w, x.bias, cfg.k, cfg.dtype)
+    ctx.close()
+
+
+@pytest.mark.parametrize("B,T,D,Vp1,k,dtype", [
+    (1, 8, 512, 1000, 4, "bf16"),     # smallest hidden size of the streaming kernel, ragged last tile
+    (1, 8, 1024, 129, 4, "bf16"),     # vocabulary barely past one block
+    (2, 8, 1024, 2049, 8, "bf16"),    # 16 columns, k = 8
+    (3, 7, 2048, 777, 3, "bf16"),     # 21 columns: two column tiles, one ragged
+    (8, 8, 1024, 4097, 4, "bf16"),    # 64 columns: hidden states chunked through LDS
+    (1, 5, 320, 300, 2, "bf16"),      # hidden size the streaming kernel does not take: generic kernel
+    (2, 3, 48, 11, 5, "f32"),         # fewer rows than a tile
+    (1, 1, 8, 1, 1, "f32"),           # a single row, a single slot
+    (1, 4, 64, 640, 8, "f32"),
+])
+def test_draft_topk_shapes(pkg, B, T, D, Vp1, k, dtype):
+    rng = np.random.Generator(np.random.PCG64(B * 1000 + D))
+    hidden = workloads.round_to_storage(rng.standard_normal((B, T, D), dtype=np.float32), dtype)
+    w = workloads.round_to_storage(rng.standard_normal((Vp1, D), dtype=np.float32) * 0.05, dtype)
+    bias = rng.standard_normal(Vp1).astype(np.float32) * 0.1
+    ctx = pkg.Context(max_batch=B, max_slots=T, max_topk=k, max_vocab_rows=Vp1, max_nodes=16, max_heads=1,
+                      max_head_dim=16)
+    _check_draft(pkg, ctx, hidden, w, bias, k, dtype)
+    _check_draft(pkg, ctx, hidden, w, None, k, dtype)
+    ctx.close()
+
+
+def test_draft_topk_forced_ties(pkg):
+    # duplicate head rows give exactly equal logits: ids must come out in ascending order among equals
+    rng = np.random.Generator(np.random.PCG64(9))
+    T, D, Vp1, k = 4, 512, 300, 6
+    hidden = workloads.round_to_storage(rng.standard_normal((1, T, D), dtype=np.float32), "bf16")
+    w = workloads.round_to_storage(rng.standard_normal((Vp1, D), dtype=np.float32), "bf16")
+    w[5] = w[200]
+    w[17] = w[200]
+    w[130] = w[131]
+    bias = np.zeros(Vp1, dtype=np.float32)
+    bias[[5, 17, 200]] = 500.0  # the three equal rows are the top three of every slot
+    ctx = pkg.Context(max_batch=1, max_slots=T, max_topk=k, max_vocab_rows=Vp1, max_nodes=16, max_heads=1,
+                      max_head_dim=16)
+    res = _check_draft(pkg, ctx, hidden, w, bias, k, "bf16")
+    assert (res["topk_id"].cpu().numpy()[0, :, :3] == np.array([5, 17, 200])).all()
+    ctx.close()
+
+
+# -------------------------------------------------------------------------------------------- stage 3
+def _run_stage3(pkg, ctx, ids, logp, root, blank, beam, max_nodes):
+    res = pkg.ctc_collapse_tree(ctx, dev_i32(ids), dev_f32(logp), dev_i32(root), blank, beam, max_nodes)
+    torch.cuda.synchronize()
+    compare_stage3(res, oracle_stage3(ids, logp, root, blank, beam, max_nodes))
+    return res
+
+
+def _stage3_ctx(pkg, B, T, k, max_nodes=128):
+    return pkg.Context(max_batch=B, max_slots=T, max_topk=k, max_vocab_rows=64, max_nodes=max_nodes,
+                       max_heads=1, max_head_dim=16)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_collapse_tree_blank_and_repeat_heavy(pkg, seed):
+    B, T, k, blank = 4, 8, 4, 32000
+    ids, logp = workloads.make_topk_case(seed, B, T, k, blank, vocab=14, p_blank=0.7)
+    ctx = _stage3_ctx(pkg, B, T, k)
+    for beam, max_nodes in ((128, 128), (64, 128), (64, 64), (7, 9), (128, 20)):
+        _run_stage3(pkg, ctx, ids, logp, np.arange(B) + 5, blank, beam, max_nodes)
+    ctx.close()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_collapse_tree_blank_first_everywhere(pkg, seed):
+    # blank is the most probable symbol of every slot (what a trained CTC head tends to give): few
+    # distinct drafts among the best raw candidates, so the search has to widen several times
+    B, T, k, blank = 2, 8, 4, 99
+    ids, logp = workloads.make_topk_case(100 + seed, B, T, k, blank, vocab=6, first_blank=True)
+    logp[:, :, 0] = -0.05
+    logp[:, :, 1:] -= 3.0
+    ctx = _stage3_ctx(pkg, B, T, k)
+    _run_stage3(pkg, ctx, ids, logp, np.zeros(B), blank, 128, 128)
+    _run_stage3(pkg, ctx, ids, logp, np.zeros(B), blank, 32, 40)
+    ctx.close()
+
+
+@pytest.mark.parametrize("quantum", [0.5, 0.25])
+def test_collapse_tree_score_ties(pkg, quantum):
+    B, T, k, blank = 3, 8, 4, 50
+    ids, logp = workloads.make_topk_case(int(quantum * 100), B, T, k, blank, vocab=10, p_blank=0.4, quantum=quantum)
+    ctx = _stage3_ctx(pkg, B, T, k)
+    _run_stage3(pkg, ctx, ids, logp, np.arange(B), blank, 128, 128)
+    ctx.close()
+
+
+def test_collapse_tree_all_scores_equal(pkg):
+    # every raw candidate has the same score: order is by idx alone and all 65536 must be ordered
+    B, T, k, blank = 1, 8, 4, 1000
+    ids, _ = workloads.make_topk_case(3, B, T, k, blank, vocab=9, p_blank=0.5)
+    logp = np.full((B, T, k), -1.25, dtype=np.float32)
+    ctx = _stage3_ctx(pkg, B, T, k)
+    _run_stage3(pkg, ctx, ids, logp, np.array([1]), blank, 128, 128)
+    ctx.close()
+
+
+def test_collapse_tree_degenerate_inputs(pkg):
+    blank = 7
+    ctx = _stage3_ctx(pkg, 2, 8, 4)
+    # all blanks: no draft, the tree is the root alone
+    ids = np.full((2, 8, 4), blank, dtype=np.int32)
+    logp = -np.abs(np.random.Generator(np.random.PCG64(0)).standard_normal((2, 8, 4))).astype(np.float32)
+    res = _run_stage3(pkg, ctx, ids, logp, np.array([3, 4]), blank, 16, 32)
+    assert res["n_nodes"].tolist() == [1, 1] and res["n_cand"].tolist() == [0, 0]
+    # the same token in every slot: one draft of length 1
+    ids = np.full((2, 8, 4), 5, dtype=np.int32)
+    res = _run_stage3(pkg, ctx, ids, logp, np.array([3, 4]), blank, 16, 32)
+    assert res["n_nodes"].tolist() == [2, 2] and res["n_cand"].tolist() == [1, 1]
+    # max_nodes = 1: nothing can be created
+    ids2, logp2 = workloads.make_topk_case(1, 2, 8, 4, blank, vocab=12)
+    res = _run_stage3(pkg, ctx, ids2, logp2, np.array([3, 4]), blank, 16, 1)
+    assert res["n_nodes"].tolist() == [1, 1]
+    ctx.close()
+
+
+@pytest.mark.parametrize("T,k", [(1, 1), (1, 8), (4, 2), (3, 5), (5, 8), (6, 6), (8, 2), (2, 7), (7, 3)])
+def test_collapse_tree_shapes(pkg, T, k):
+    B, blank = 2, 40
+    ids, logp = workloads.make_topk_case(T * 10 + k, B, T, k, blank, vocab=max(k + 1, 9), p_blank=0.5)
+    ctx = _stage3_ctx(pkg, B, T, k)
+    _run_stage3(pkg, ctx, ids, logp, np.array([1, 2]), blank, 128, 128)
+    _run_stage3(pkg, ctx, ids, logp, np.array([1, 2]), blank, 5, 11)
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------------------- stage 4a
+def _attention_case(pkg, cfg, x, trees, atol_name=""):
+    """trees: per sequence dict with n_nodes, node_parent, anc_mask (from stage 3, GPU == oracle)."""
+    B, H, N, dh = cfg.B, cfg.H, cfg.max_nodes, cfg.dh
+    ctx = _ctx(pkg, cfg)
+    q, kt, vt = x.q.copy(), x.k_tree.copy(), x.v_tree.copy()
+    n_nodes = np.array([t["n_nodes"] for t in trees], dtype=np.int32)
+    for b in range(B):  # rows beyond the tree may hold anything: poison them
+        q[b, :, n_nodes[b]:] = np.nan
+        kt[b, :, n_nodes[b]:] = np.nan
+        vt[b, :, n_nodes[b]:] = np.nan
+    mask = np.stack([t["anc_mask"] for t in trees]).view(np.int64)
+    out = pkg.tree_verify_attn(
+        ctx, to_device(q, cfg.dtype), to_device(x.k_cache, cfg.dtype), to_device(x.v_cache, cfg.dtype),
+        dev_i64(x.kv_off), dev_i32(x.ctx_len), cfg.kv_cap, to_device(kt, cfg.dtype), to_device(vt, cfg.dtype),
+        dev_i32(n_nodes), torch.from_numpy(mask).cuda(), 1.0 / math.sqrt(dh))
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    worst = 0.0
+    for b in range(B):
+        n = int(n_nodes[b])
+        ref = oracle.tree_attention(x.q[b], x.k_cache[b], x.v_cache[b], int(x.ctx_len[b]), x.k_tree[b],
+                                    x.v_tree[b], n, trees[b]["mask"], 1.0 / math.sqrt(dh))
+        assert np.isfinite(out[b, :, :n]).all()
+        worst = max(worst, rel_err_rms_floor(out[b, :, :n], ref))
+    assert worst <= TOL, f"attention rel err {worst}"
+    ctx.close()
+    return out
+
+
+def _oracle_trees(cfg, seed, variant_ids=None):
+    ids, logp = workloads.make_topk_case(seed, cfg.B, cfg.T, cfg.k, cfg.blank_id, vocab=20, p_blank=0.3)
+    return [oracle.collapse_tree(ids[b], logp[b], 1, cfg.blank_id, cfg.beam, cfg.max_nodes) for b in range(cfg.B)]
+
+
+@pytest.mark.parametrize("cfg_index", [0, 1, 2, 4])
+def test_tree_attention_configs(pkg, cfg_index):
+    cfg = workloads.get_config(cfg_index)
+    x = cached_inputs(cfg_index, 0, "literal")
+    _attention_case(pkg, cfg, x, _oracle_trees(cfg, cfg_index))
+
+
+def test_tree_attention_13b_shape(pkg):
+    cfg = workloads.get_config(3)
+    x = workloads.make_inputs(cfg, 1, "literal")
+    _attention_case(pkg, cfg, x, _oracle_trees(cfg, 3))
+
+
+def _tree_with_cap(cfg, seed, cap):
+    """A tree of at most `cap` nodes, laid out for cfg.max_nodes."""
+    ids, logp = workloads.make_topk_case(seed, 1, cfg.T, cfg.k, cfg.blank_id, vocab=20, p_blank=0.3)
+    t = oracle.collapse_tree(ids[0], logp[0], 1, cfg.blank_id, cfg.beam, cap)
+    return {"n_nodes": t["n_nodes"], "mask": t["mask"], "anc_mask": oracle.pack_mask_u64(t["mask"], cfg.max_nodes)}
+
+
+@pytest.mark.parametrize("ctx_len,n_keep", [(0, 5), (1, 1), (63, 17), (64, 64), (65, 128), (1000, 33), (2047, 128)])
+def test_tree_attention_ragged_edges(pkg, ctx_len, n_keep):
+    # context lengths around tile boundaries (and none at all), trees of 1..128 nodes
+    import dataclasses
+    cfg = dataclasses.replace(workloads.get_config(2), H=4, ctx=(ctx_len, ctx_len), beam=128)
+    x = workloads.make_inputs(cfg, ctx_len, "literal")
+    tree = _tree_with_cap(cfg, ctx_len, n_keep)
+    assert tree["n_nodes"] == n_keep
+    _attention_case(pkg, cfg, x, [tree])
+
+
+def test_tree_attention_chain_tree_is_causal(pkg):
+    # a chain-shaped tree reproduces ordinary causal attention (checked against the oracle, which is
+    # itself pinned to a textbook causal attention on the CPU)
+    import dataclasses
+    cfg = dataclasses.replace(workloads.get_config(1), H=2, ctx=(100, 100), max_nodes=128)
+    x = workloads.make_inputs(cfg, 5, "literal")
+    n = 128
+    parent = [-1] + list(range(n - 1))
+    mask = oracle.ancestor_mask(parent)
+    tree = {"n_nodes": n, "mask": mask, "anc_mask": oracle.pack_mask_u64(mask, cfg.max_nodes)}
+    _attention_case(pkg, cfg, x, [tree])
+
+
+# ------------------------------------------------------------------------------------------- stage 4b
+def _accept_case(pkg, ctx, trees, targets, T, max_nodes):
+    B = len(trees)
+    res = pkg.accept_longest(
+        ctx, dev_i32([t["n_nodes"] for t in trees]), dev_i32(np.stack([t["node_token"] for t in trees])),
+        dev_i32(np.stack([t["node_parent"] for t in trees])), dev_i32(np.stack([t["node_depth"] for t in trees])),
+        dev_i32(targets), T)
+    torch.cuda.synchronize()
+    for b in range(B):
+        length, nodes, toks, nxt = oracle.accept_longest(trees[b]["node_token"], trees[b]["node_parent"],
+                                                         trees[b]["n_nodes"], targets[b], T)
+        assert int(res["accept_len"][b]) == length
+        assert np.array_equal(res["accept_nodes"][b].cpu().numpy(), nodes)
+        assert np.array_equal(res["accept_tokens"][b].cpu().numpy(), toks)
+        assert int(res["next_token"][b]) == nxt
+    return res
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_accept_planted_and_random_targets(pkg, seed):
+    cfg = workloads.get_config(4)
+    trees = _oracle_trees(cfg, 40 + seed)
+    ctx = _ctx(pkg, cfg)
+    rng = np.random.Generator(np.random.PCG64(seed))
+    seen_lengths = set()
+    for rep in range(6):
+        targets = np.full((cfg.B, cfg.max_nodes), 123456, dtype=np.int32)
+        for b, t in enumerate(trees):
+            node = int(rng.integers(0, t["n_nodes"]))
+            while node > 0:
+                par = int(t["node_parent"][node])
+                targets[b, par] = t["node_token"][node]
+                node = par
+        res = _accept_case(pkg, ctx, trees, targets, cfg.T, cfg.max_nodes)
+        seen_lengths |= set(res["accept_len"].tolist())
+        # random targets from a small vocabulary: frequent partial matches
+        rnd = rng.integers(0, 20, size=(cfg.B, cfg.max_nodes)).astype(np.int32)
+        _accept_case(pkg, ctx, trees, rnd, cfg.T, cfg.max_nodes)
+    assert len(seen_lengths) >= 4
+    ctx.close()
+
+
+# -------------------------------------------------------------------------------------- the whole step
+@pytest.mark.parametrize("cfg_index,variant,seed", [
+    (0, "literal", 0), (0, "ar1", 0), (0, "structured", 1), (0, "ar1", 3),
+    (1, "literal", 0), (1, "structured", 0), (2, "literal", 0), (2, "structured", 2),
+    (3, "structured", 0), (4, "literal", 0), (4, "structured", 1),
+])
+def test_whole_step_chained(pkg, cfg_index, variant, seed):
+    """All four calls back to back on one stream without host synchronisation, then every stage against
+    the oracle fed with the GPU's output of the stage before."""
+    cfg = workloads.get_config(cfg_index)
+    x = cached_inputs(cfg_index, seed, variant)
+    ctx = _ctx(pkg, cfg)
+    B, T, k, N, H, dh = cfg.B, cfg.T, cfg.k, cfg.max_nodes, cfg.H, cfg.dh
+    d_hidden, d_w, d_bias = to_device(x.hidden, cfg.dtype), to_device(x.w, cfg.dtype), dev_f32(x.bias)
+    d_q, d_kt, d_vt = (to_device(a, cfg.dtype) for a in (x.q, x.k_tree, x.v_tree))
+    d_kc, d_vc = to_device(x.k_cache, cfg.dtype), to_device(x.v_cache, cfg.dtype)
+    d_off, d_len, d_root = dev_i64(x.kv_off), dev_i32(x.ctx_len), dev_i32(x.root_token)
+    scale = 1.0 / math.sqrt(dh)
+
+    s12 = pkg.ctc_draft_topk(ctx, d_hidden, d_w, d_bias, k, want_logits=True)
+    s3 = pkg.ctc_collapse_tree(ctx, s12["topk_id"], s12["topk_logp"], d_root, cfg.blank_id, cfg.beam, N)
+    out = pkg.tree_verify_attn(ctx, d_q, d_kc, d_vc, d_off, d_len, cfg.kv_cap, d_kt, d_vt, s3["n_nodes"],
+                               s3["anc_mask"], scale)
+    torch.cuda.synchronize()
+
+    # stage 1+2
+    z_gpu = s12["logits"].cpu().numpy()
+    ref12 = oracle.draft_topk(x.hidden, x.w, x.bias, k)
+    assert rel_err_rms_floor(z_gpu, ref12["z"]) <= TOL
+    ids = s12["topk_id"].cpu().numpy()
+    assert np.array_equal(ids, oracle.topk_per_slot(z_gpu, k))
+    # stage 3 on the GPU's top-k lists
+    logp = s12["topk_logp"].cpu().numpy()
+    trees = oracle_stage3(ids, logp, x.root_token, cfg.blank_id, cfg.beam, N)
+    compare_stage3(s3, trees)
+    # stage 4a
+    o = out.cpu().numpy()
+    for b in range(B):
+        n = trees[b]["n_nodes"]
+        ref = oracle.tree_attention(x.q[b], x.k_cache[b], x.v_cache[b], int(x.ctx_len[b]), x.k_tree[b],
+                                    x.v_tree[b], n, trees[b]["mask"], scale)
+        assert rel_err_rms_floor(o[b, :, :n], ref) <= TOL
+    # stage 4b: verifier stand-in on the GPU's attention output (tiny config), planted path otherwise
+    targets = np.full((B, N), 7, dtype=np.int32)
+    rng = np.random.Generator(np.random.PCG64(seed))
+    for b in range(B):
+        n = trees[b]["n_nodes"]
+        if x.proj is not None:
+            targets[b, :n] = oracle.verifier_argmax(o[b, :, :n], x.proj)
+        else:
+            node = int(rng.integers(0, n))
+            targets[b] = cfg.V + 5
+            while node > 0:
+                par = int(trees[b]["node_parent"][node])
+                targets[b, par] = trees[b]["node_token"][node]
+                node = par
+    acc = pkg.accept_longest(ctx, s3["n_nodes"], s3["node_token"], s3["node_parent"], s3["node_depth"],
+                             dev_i32(targets), T)
+    torch.cuda.synchronize()
+    for b in range(B):
+        length, nodes, toks, nxt = oracle.accept_longest(trees[b]["node_token"], trees[b]["node_parent"],
+                                                         trees[b]["n_nodes"], targets[b], T)
+        assert int(acc["accept_len"][b]) == length
+        assert np.array_equal(acc["accept_nodes"][b].cpu().numpy(), nodes)
+        assert np.array_equal(acc["accept_tokens"][b].cpu().numpy(), toks)
+        assert int(acc["next_token"][b]) == nxt
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------------------ error paths
+def test_calls_reject_bad_arguments_without_launching(pkg):
+    cfg = workloads.get_config(0)
+    ctx = _ctx(pkg, cfg)
+    h = torch.zeros((1, 4, 64), device="cuda")
+    w = torch.zeros((101, 64), device="cuda")
+    with pytest.raises(pkg.CtcspecError, match="k="):
+        pkg.ctc_draft_topk(ctx, h, w[:1].contiguous(), None, 2)
+    with pytest.raises(pkg.CtcspecError, match="limits"):
+        pkg.ctc_draft_topk(ctx, h, torch.zeros((500, 64), device="cuda"), None, 2)
+    ids = torch.zeros((1, 4, 2), dtype=torch.int32, device="cuda")
+    lp = torch.zeros((1, 4, 2), device="cuda")
+    root = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    with pytest.raises(pkg.CtcspecError, match="beam"):
+        pkg.ctc_collapse_tree(ctx, ids, lp, root, 100, 129, 128)
+    with pytest.raises(pkg.CtcspecError, match="max_nodes"):
+        pkg.ctc_collapse_tree(ctx, ids, lp, root, 100, 16, 129)
+    assert "max_nodes" in ctx.last_error()
+    # the context still works after errors
+    x = workloads.make_inputs(cfg, 0, "literal")
+    _check_draft(pkg, ctx, x.hidden, x.w, x.bias, cfg.k, cfg.dtype)
+    ctx.close()
