@@ -1,0 +1,285 @@
+#!/usr/bin/env python3
+"""Benchmark of one draft+verify step of CTC-drafted speculative decoding on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 7b_ctx2048] [--no-cpu-baseline]
+
+A step is the whole hot path on one batch of seeded synthetic input that is already resident in HBM:
+ctc_draft_topk -> ctc_collapse_tree -> tree_verify_attn (one attention layer) -> accept_longest, issued
+back to back on one stream with no host synchronisation in between.  W untimed warm-up steps, then
+exactly K timed steps between two device synchronisations.  To keep the 256 MB Infinity Cache from
+serving the streams, the head weights rotate over several identical copies and the KV cache / Q / tree
+K,V over many buffer sets, so every step reads memory that is not cached.
+
+Prints ONE JSON line.  `value` is verified tokens per second (tree nodes pushed through verification
+per second of step time); `roofline` describes the dominant kernel (the draft head, HBM-bound);
+`cpu_baseline` is the float64 oracle timed on this machine's host cores on a bounded sample.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", default="7b_ctx2048")
+    ap.add_argument("--variant", default="literal", choices=["literal", "ar1", "structured"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--w-copies", type=int, default=6)
+    ap.add_argument("--kv-sets", type=int, default=32)
+    ap.add_argument("--graph", action="store_true", help="replay the steps from a captured HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=2)
+    return ap.parse_args()
+
+
+def algorithmic_bytes(cfg, ctx_len, n_nodes):
+    """Bytes one step must move by the method's own definition (weights and KV read once, small
+    tensors once).  Returns (draft_head_bytes, attention_bytes, total)."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    head = cfg.Vp1 * cfg.D * es + cfg.B * cfg.T * cfg.D * es + cfg.Vp1 * 4 + cfg.B * cfg.T * (2 * cfg.k + 1) * 4
+    kv = int(sum(2 * int(L) * cfg.H * cfg.dh * es for L in ctx_len))
+    qkv_tree = int(sum(3 * int(n) * cfg.H * cfg.dh * es for n in n_nodes))
+    out = int(sum(int(n) * cfg.H * cfg.dh * 4 for n in n_nodes))
+    small = cfg.B * (cfg.max_nodes * (16 + 8 * ((cfg.max_nodes + 63) // 64)) + cfg.beam * (cfg.T + 3) * 4)
+    attn = kv + qkv_tree + out
+    return head, attn, head + attn + small
+
+
+def read_traffic_summary():
+    """HBM bytes per draft-head launch from the committed rocprofv3 counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", "ctc_draft_topk_7b_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(cfg, x, n_steps):
+    """Time the float64 oracle, as it stands, on this host for n_steps whole steps of the same workload."""
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    scale = 1.0 / math.sqrt(cfg.dh)
+    best, nodes = None, 0
+    for _ in range(n_steps):
+        t0 = time.perf_counter()
+        d = oracle.draft_topk(x.hidden, x.w, x.bias, cfg.k)
+        nodes = 0
+        for b in range(cfg.B):
+            tree = oracle.collapse_tree(d["topk_id"][b], d["topk_logp"][b].astype(np.float32),
+                                        int(x.root_token[b]), cfg.blank_id, cfg.beam, cfg.max_nodes)
+            n = tree["n_nodes"]
+            o = oracle.tree_attention(x.q[b], x.k_cache[b], x.v_cache[b], int(x.ctx_len[b]), x.k_tree[b],
+                                      x.v_tree[b], n, tree["mask"], scale)
+            target = np.full(n, -1, dtype=np.int32)
+            oracle.accept_longest(tree["node_token"], tree["node_parent"], n, target, cfg.T)
+            nodes += n
+            del o
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    return {"value": nodes / best, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n_steps} whole step(s) of the same workload and seed, best taken; "
+                      f"{best * 1e3:.0f} ms per step"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+    import torch
+    import workloads
+    import paper_2412_00061_amd as lib
+    from paper_2412_00061_amd.binding import CTCSPEC_BF16, CTCSPEC_F32
+    from workloads.device import dev_f32, dev_i32, dev_i64, to_device
+
+    cfg = workloads.get_config(args.config if not args.config.isdigit() else int(args.config))
+    torch.cuda.set_device(0)
+    x = workloads.make_inputs(cfg, args.seed, args.variant)
+    ctx = lib.Context.for_config(cfg)
+    B, T, k, N, H, dh = cfg.B, cfg.T, cfg.k, cfg.max_nodes, cfg.H, cfg.dh
+    scale = 1.0 / math.sqrt(dh)
+    dt = CTCSPEC_BF16 if cfg.dtype == "bf16" else CTCSPEC_F32
+
+    d_hidden, d_bias, d_root = to_device(x.hidden, cfg.dtype), dev_f32(x.bias), dev_i32(x.root_token)
+    w0 = to_device(x.w, cfg.dtype)
+    d_w = [w0] + [w0.clone() for _ in range(args.w_copies - 1)]
+    base = [to_device(a, cfg.dtype) for a in (x.q, x.k_tree, x.v_tree, x.k_cache, x.v_cache)]
+    sets = [base] + [[t.clone() for t in base] for _ in range(args.kv_sets - 1)]
+    d_off, d_len = dev_i64(x.kv_off), dev_i32(x.ctx_len)
+
+    def i32(*shape):
+        return torch.empty(shape, dtype=torch.int32, device="cuda")
+
+    def f32(*shape):
+        return torch.empty(shape, dtype=torch.float32, device="cuda")
+
+    words = (N + 63) // 64
+    topk_id, topk_logp, lse = i32(B, T, k), f32(B, T, k), f32(B, T)
+    n_cand, cand_tokens, cand_len, cand_score, cand_leaf = i32(B), i32(B, cfg.beam, T), i32(B, cfg.beam), \
+        f32(B, cfg.beam), i32(B, cfg.beam)
+    n_nodes_d, node_token, node_parent, node_depth = i32(B), i32(B, N), i32(B, N), i32(B, N)
+    anc_mask = torch.empty((B, N, words), dtype=torch.int64, device="cuda")
+    out_attn = f32(B, H, N, dh)
+    targets = torch.full((B, N), -1, dtype=torch.int32, device="cuda")
+    accept_len, accept_nodes, accept_tokens, next_token = i32(B), i32(B, T + 1), i32(B, T + 1), i32(B)
+
+    # the four C calls of one step, marshalled once per rotation slot (weights copy x buffer set)
+    period = len(d_w) * len(sets) // math.gcd(len(d_w), len(sets))
+    slots = []
+    for i in range(period):
+        w = d_w[i % len(d_w)]
+        q, kt, vt, kc, vc = sets[i % len(sets)]
+        slots.append((
+            lib.prepared(ctx, "ctc_draft_topk", dt, d_hidden, w, d_bias, B, T, cfg.D, cfg.Vp1, k, topk_id,
+                         topk_logp, lse, None),
+            lib.prepared(ctx, "ctc_collapse_tree", topk_id, topk_logp, d_root, B, T, k, cfg.blank_id, cfg.beam,
+                         N, n_cand, cand_tokens, cand_len, cand_score, cand_leaf, n_nodes_d, node_token,
+                         node_parent, node_depth, anc_mask),
+            lib.prepared(ctx, "tree_verify_attn", dt, q, kc, vc, d_off, d_len, cfg.kv_cap, kt, vt, n_nodes_d,
+                         anc_mask, B, H, dh, N, scale, out_attn),
+            lib.prepared(ctx, "accept_longest", n_nodes_d, node_token, node_parent, node_depth, targets, B, T,
+                         N, accept_len, accept_nodes, accept_tokens, next_token),
+        ))
+
+    def step(i):
+        c1, c2, c3, c4 = slots[i % period]
+        c1(); c2(); c3(); c4()
+
+    def step_with_events(i, ev):
+        calls = slots[i % period]
+        ev[0].record()
+        for j in range(4):
+            calls[j]()
+            ev[j + 1].record()
+
+    # one untimed step to learn the (deterministic) tree, then plant an accepted path so that the
+    # acceptance walk does real work: the deepest node's root path is what the verifier "agrees" with
+    step(0)
+    torch.cuda.synchronize()
+    n_nodes = n_nodes_d.cpu().numpy()
+    parent, token, depth = node_parent.cpu().numpy(), node_token.cpu().numpy(), node_depth.cpu().numpy()
+    tgt = np.full((B, N), -1, dtype=np.int32)
+    for b in range(B):
+        node = int(np.argmax(depth[b, :n_nodes[b]]))
+        while node > 0:
+            tgt[b, parent[b, node]] = token[b, node]
+            node = parent[b, node]
+    targets.copy_(torch.from_numpy(tgt))
+
+    graph = None
+    if args.graph:
+        # capture `period` consecutive steps (each on its own weights copy / buffer set) into one HIP
+        # graph; K must then be a multiple of the period
+        if args.steps % period != 0:
+            args.steps = max(period, args.steps // period * period)
+        cap_stream = torch.cuda.Stream()
+        ctx.set_stream(cap_stream)
+        with torch.cuda.stream(cap_stream):
+            for i in range(2):
+                step(i)
+            cap_stream.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=cap_stream):
+                for i in range(period):
+                    step(i)
+        torch.cuda.synchronize()
+
+    def run(n, first):
+        if graph is not None:
+            for _ in range(n // period):
+                graph.replay()
+        else:
+            for i in range(n):
+                step(first + i)
+
+    if graph is not None:
+        graph.replay()
+    else:
+        run(args.warmup, 0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps, args.warmup)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    us_per_step = wall / args.steps * 1e6
+    accepted = accept_len.cpu().numpy()
+
+    # second pass with HIP events around every call (on the stream the kernels run on): per-call times
+    if graph is not None:
+        ctx.set_stream(torch.cuda.current_stream())
+    n_ev = min(args.steps, 200)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(n_ev)]
+    for i in range(n_ev):
+        step_with_events(args.warmup + args.steps + i, evs[i])
+    torch.cuda.synchronize()
+    per_call = np.array([[e[j].elapsed_time(e[j + 1]) * 1e3 for j in range(4)] for e in evs])  # us
+    call_us = per_call.mean(axis=0)
+    call_med = np.median(per_call, axis=0)
+
+    head_b, attn_b, total_b = algorithmic_bytes(cfg, x.ctx_len, n_nodes)
+    head_us = float(call_us[0])
+    achieved = head_b / (head_us * 1e-6) / 1e9
+    nodes_total = int(n_nodes.sum())
+    result = {
+        "metric": "verified_tokens_per_sec",
+        "value": nodes_total / (us_per_step * 1e-6),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": us_per_step / 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: one draft+verify step, B={B} D={cfg.D} V+1={cfg.Vp1} T={T} k={k} "
+                               f"beam={cfg.beam} max_nodes={N} H={H} dh={dh} ctx={x.ctx_len.tolist()}",
+                   "variant": args.variant, "seed": args.seed, "n_nodes": n_nodes.tolist(),
+                   "accepted_plus_bonus": (accepted + 1).tolist(),
+                   "w_copies": len(d_w), "kv_sets": len(sets), "launch": "hip_graph" if graph is not None else "eager"},
+        "us_per_step": us_per_step,
+        "step_algorithmic_bytes": total_b,
+        "step_hbm_gbps": total_b / (us_per_step * 1e-6) / 1e9,
+        "step_frac_of_hbm_peak": total_b / (us_per_step * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+        "per_call_us_mean": {"ctc_draft_topk": float(call_us[0]), "ctc_collapse_tree": float(call_us[1]),
+                             "tree_verify_attn": float(call_us[2]), "accept_longest": float(call_us[3])},
+        "per_call_us_median": {"ctc_draft_topk": float(call_med[0]), "ctc_collapse_tree": float(call_med[1]),
+                               "tree_verify_attn": float(call_med[2]), "accept_longest": float(call_med[3])},
+        "attention_hbm_gbps": attn_b / (float(call_us[2]) * 1e-6) / 1e9,
+        "roofline": {"kernel": "lmhead_bf16_mfma_kernel (ctc_draft_topk)", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": read_traffic_summary(), "algorithmic_bytes_per_launch": head_b,
+                     "launch_us": head_us},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, x, args.cpu_steps)
+    print(json.dumps(result))
+    ctx.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -13,5 +13,6 @@ from .binding import (  # noqa: F401
     ctc_draft_topk,
     library_path,
     load_library,
+    prepared,
     tree_verify_attn,
 )

@@ -137,6 +137,32 @@ class Context:
             pass
 
 
+def prepared(ctx, name, *args):
+    """Marshal the arguments of C entry point `name` once and return a zero-argument callable that
+    issues the call (for launch loops where per-call marshalling would dominate).  `args` follow the C
+    parameter order after the context; tensors become device pointers, None becomes NULL."""
+    fn = getattr(ctx.lib, name)
+    keep, cargs = [], [ctx.handle]
+    for a, ctype in zip(args, fn.argtypes[1:]):
+        if isinstance(a, torch.Tensor):
+            keep.append(a)
+            cargs.append(_ptr(a))
+        elif a is None:
+            cargs.append(None)
+        else:
+            cargs.append(ctype(a))
+    if len(cargs) != len(fn.argtypes):
+        raise CtcspecError(f"{name}: expected {len(fn.argtypes) - 1} arguments, got {len(args)}")
+    cargs = tuple(cargs)
+
+    def call(_fn=fn, _args=cargs, _keep=keep, _ctx=ctx, _name=name):
+        rc = _fn(*_args)
+        if rc != 0:
+            _ctx._check(rc, _name)
+
+    return call
+
+
 def _out(out, name, shape, dtype, device):
     if out is not None and name in out:
         t = out[name]

@@ -43,7 +43,6 @@ struct ctcspec_ctx {
   float* lm_pmax;               // [lm_max_blocks][kMaxCols]
   float* lm_psum;               // [lm_max_blocks][kMaxCols]
   unsigned long long* lm_pkey;  // [lm_max_blocks][kMaxCols][kMaxTopk]
-  unsigned int* lm_ticket;      // [1], zero between calls
   // collapse / tree
   unsigned char* collapse_ws;   // [max_batch][kCollapseWsBytesPerSeq]
   // attention
@@ -101,34 +100,69 @@ __device__ __forceinline__ unsigned int rank_key_index(unsigned long long key) {
   return 0xffffffffu - (unsigned int)(key & 0xffffffffu);
 }
 
-__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int mask) {
-  unsigned int lo = (unsigned int)v, hi = (unsigned int)(v >> 32);
-  lo = __shfl_xor(lo, mask, kWave);
-  hi = __shfl_xor(hi, mask, kWave);
-  return ((unsigned long long)hi << 32) | lo;
+// ---- wavefront reductions ------------------------------------------------------------------------
+// Inside each row of 16 lanes the partial results travel by DPP row rotations (no LDS round trip);
+// the four row results are then combined through v_readlane.  Every lane returns the full result.
+template <int ROT>
+__device__ __forceinline__ unsigned int dpp_row_ror(unsigned int v) {
+  return (unsigned int)__builtin_amdgcn_update_dpp(0, (int)v, 0x120 + ROT, 0xf, 0xf, false);
 }
-__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) {
-    unsigned long long o = shfl_xor_u64(v, m);
-    v = o > v ? o : v;
+__device__ __forceinline__ unsigned int readlane_u32(unsigned int v, int lane) {
+  return (unsigned int)__builtin_amdgcn_readlane((int)v, lane);
+}
+
+#define CTCSPEC_ROW_STEP_U64(ROT)                                                   \
+  {                                                                                 \
+    unsigned int olo = dpp_row_ror<ROT>(lo), ohi = dpp_row_ror<ROT>(hi);            \
+    bool take = ohi > hi || (ohi == hi && olo > lo);                                \
+    lo = take ? olo : lo;                                                           \
+    hi = take ? ohi : hi;                                                           \
   }
-  return v;
-}
-__device__ __forceinline__ float wave_max_f32(float v) {
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
+  unsigned int lo = (unsigned int)v, hi = (unsigned int)(v >> 32);
+  CTCSPEC_ROW_STEP_U64(1)
+  CTCSPEC_ROW_STEP_U64(2)
+  CTCSPEC_ROW_STEP_U64(4)
+  CTCSPEC_ROW_STEP_U64(8)
+  unsigned long long best = 0ull;
 #pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
-  return v;
+  for (int r = 0; r < 4; ++r) {
+    unsigned long long x = ((unsigned long long)readlane_u32(hi, 16 * r) << 32) | readlane_u32(lo, 16 * r);
+    best = x > best ? x : best;
+  }
+  return best;
+}
+#undef CTCSPEC_ROW_STEP_U64
+
+__device__ __forceinline__ float wave_max_f32(float v) {
+  v = fmaxf(v, __uint_as_float(dpp_row_ror<1>(__float_as_uint(v))));
+  v = fmaxf(v, __uint_as_float(dpp_row_ror<2>(__float_as_uint(v))));
+  v = fmaxf(v, __uint_as_float(dpp_row_ror<4>(__float_as_uint(v))));
+  v = fmaxf(v, __uint_as_float(dpp_row_ror<8>(__float_as_uint(v))));
+  float a = __uint_as_float(readlane_u32(__float_as_uint(v), 0));
+  float b = __uint_as_float(readlane_u32(__float_as_uint(v), 16));
+  float c = __uint_as_float(readlane_u32(__float_as_uint(v), 32));
+  float d = __uint_as_float(readlane_u32(__float_as_uint(v), 48));
+  return fmaxf(fmaxf(a, b), fmaxf(c, d));
 }
 __device__ __forceinline__ float wave_sum_f32(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
-  return v;
+  v += __uint_as_float(dpp_row_ror<1>(__float_as_uint(v)));
+  v += __uint_as_float(dpp_row_ror<2>(__float_as_uint(v)));
+  v += __uint_as_float(dpp_row_ror<4>(__float_as_uint(v)));
+  v += __uint_as_float(dpp_row_ror<8>(__float_as_uint(v)));
+  float a = __uint_as_float(readlane_u32(__float_as_uint(v), 0));
+  float b = __uint_as_float(readlane_u32(__float_as_uint(v), 16));
+  float c = __uint_as_float(readlane_u32(__float_as_uint(v), 32));
+  float d = __uint_as_float(readlane_u32(__float_as_uint(v), 48));
+  return (a + b) + (c + d);
 }
 __device__ __forceinline__ int wave_sum_i32(int v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
-  return v;
+  v += (int)dpp_row_ror<1>((unsigned)v);
+  v += (int)dpp_row_ror<2>((unsigned)v);
+  v += (int)dpp_row_ror<4>((unsigned)v);
+  v += (int)dpp_row_ror<8>((unsigned)v);
+  return (int)(readlane_u32((unsigned)v, 0) + readlane_u32((unsigned)v, 16) + readlane_u32((unsigned)v, 32) +
+               readlane_u32((unsigned)v, 48));
 }
 
 __device__ __forceinline__ float bf16_bits_to_float(unsigned short b) {

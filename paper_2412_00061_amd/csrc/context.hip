@@ -67,7 +67,6 @@ extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec
   size_t o_pmax = carve((size_t)ctx->lm_max_blocks * kMaxCols * sizeof(float));
   size_t o_psum = carve((size_t)ctx->lm_max_blocks * kMaxCols * sizeof(float));
   size_t o_pkey = carve((size_t)ctx->lm_max_blocks * kMaxCols * kMaxTopk * sizeof(unsigned long long));
-  size_t o_tick = carve(256);
   size_t o_coll = carve((size_t)lim->max_batch * kCollapseWsBytesPerSeq);
   size_t o_po = carve((size_t)ctx->attn_units * lim->max_nodes * lim->max_head_dim * sizeof(float));
   size_t o_pm = carve((size_t)ctx->attn_units * lim->max_nodes * sizeof(float));
@@ -83,19 +82,10 @@ extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec
   ctx->lm_pmax = (float*)(base + o_pmax);
   ctx->lm_psum = (float*)(base + o_psum);
   ctx->lm_pkey = (unsigned long long*)(base + o_pkey);
-  ctx->lm_ticket = (unsigned int*)(base + o_tick);
   ctx->collapse_ws = base + o_coll;
   ctx->attn_po = (float*)(base + o_po);
   ctx->attn_pm = (float*)(base + o_pm);
   ctx->attn_pl = (float*)(base + o_pl);
-  // the ticket must start at zero; kernels leave it at zero again
-  e = hipMemsetAsync(ctx->lm_ticket, 0, 256, ctx->stream);
-  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
-  if (e != hipSuccess) {
-    (void)hipFree(ctx->ws);
-    delete ctx;
-    return fail(nullptr, CTCSPEC_EHIP, "workspace initialisation failed: %s", hipGetErrorString(e));
-  }
   g_create_err[0] = 0;
   *out = ctx;
   return CTCSPEC_OK;

@@ -2,8 +2,10 @@
 //
 // The head weights are read exactly once.  A workgroup owns 128 consecutive vocabulary rows; it
 // leaves, per column (= draft slot of some sequence), the running max, the sum of exponentials and
-// its k best (logit, id) pairs.  The workgroup that finishes last (atomic ticket) merges the
-// partials of all workgroups into lse / topk_id / topk_logp, so the whole stage is one launch.
+// its k best (logit, id) pairs.  A second, tiny kernel merges the partials of all workgroups into
+// lse / topk_id / topk_logp.  (Merging inside the first kernel behind an atomic ticket needs a
+// device-scope release fence in every workgroup; on this GPU that is an L2 write-back per workgroup
+// and costs far more than the launch of a second kernel.)
 //
 // Two producers of the 128 x columns logit block exist:
 //   * lmhead_bf16_mfma_kernel  - bf16 operands, v_mfma_f32_16x16x32_bf16, HBM-streaming design
@@ -29,7 +31,6 @@ struct LmHeadParams {
   float* pmax;
   float* psum;
   unsigned long long* pkey;
-  unsigned int* ticket;
   int32_t* topk_id;
   float* topk_logp;
   float* lse;
@@ -62,8 +63,8 @@ struct KeyList {
 
 // Epilogue shared by both producers.  zbuf holds the block's logits column-major:
 // zbuf[col * kZStride + r] = z of row (blockIdx.x*128 + r), -inf for rows >= Vp1.
-// All threads of the workgroup must call this (it contains barriers).
-__device__ void lmhead_block_epilogue(const LmHeadParams& p, const float* zbuf, unsigned int* flag_lds) {
+// Whole wavefronts must call this (the reductions use every lane).
+__device__ void lmhead_block_epilogue(const LmHeadParams& p, const float* zbuf) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nwaves = blockDim.x >> 6;
   const int row_base = blockIdx.x * kRowsPerBlock;
@@ -96,49 +97,60 @@ __device__ void lmhead_block_epilogue(const LmHeadParams& p, const float* zbuf, 
     }
     if (lane == 0) { p.pmax[slot] = mx; p.psum[slot] = s; }
   }
+}
 
-  // ticket: the last workgroup to arrive merges everything
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) *flag_lds = atomicAdd(p.ticket, 1u);
-  __syncthreads();
-  if (*flag_lds != (unsigned)(gridDim.x - 1)) return;
-  __threadfence();
-
-  const int nb = gridDim.x;
-  for (int m = wave; m < p.BT; m += nwaves) {
-    float mx = -INFINITY;
-    for (int b = lane; b < nb; b += 64) mx = fmaxf(mx, p.pmax[(size_t)b * kMaxCols + m]);
-    mx = wave_max_f32(mx);
-    float s = 0.f;
-    KeyList<kMaxTopk> list;
-    list.clear();
-    for (int b = lane; b < nb; b += 64) {
-      size_t slot = (size_t)b * kMaxCols + m;
-      float bm = p.pmax[slot];
-      if (bm > -INFINITY) s += p.psum[slot] * __expf(bm - mx);
-      for (int r = 0; r < k; ++r) list.insert(p.pkey[slot * kMaxTopk + r]);
+// Merge of the per-workgroup partials: one wavefront per column.  Lane l owns workgroups l, l+64, ...;
+// all of a lane's partials are requested before any is used, so the kernel costs about one memory
+// round trip.
+template <int KMAX>
+__global__ __launch_bounds__(64) void lmhead_merge_kernel(LmHeadParams p) {
+  const int m = blockIdx.x, lane = threadIdx.x;
+  const int nb = p.n_blocks, k = p.k;
+  float m_run = -INFINITY, s_run = 0.f;
+  KeyList<KMAX> list;
+  list.clear();
+  for (int b0 = 0; b0 < nb; b0 += 256) {
+    float pm[4], ps[4];
+    unsigned long long pk[4][KMAX];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int b = b0 + u * 64 + lane;
+      const bool ok = b < nb;
+      const size_t slot = (size_t)(ok ? b : 0) * kMaxCols + m;
+      pm[u] = ok ? p.pmax[slot] : -INFINITY;
+      ps[u] = ok ? p.psum[slot] : 0.f;
+#pragma unroll
+      for (int r = 0; r < KMAX; ++r) pk[u][r] = (ok && r < k) ? p.pkey[slot * kMaxTopk + r] : 0ull;
     }
-    s = wave_sum_f32(s);
-    float lse = mx + __logf(s);
-    if (lane == 0 && p.lse) p.lse[m] = lse;
-    for (int r = 0; r < k; ++r) {
-      unsigned long long best = wave_max_u64(list.v[0]);
-      if (list.v[0] == best) list.pop();
-      if (lane == 0) {
-        p.topk_id[m * k + r] = (int32_t)rank_key_index(best);
-        p.topk_logp[m * k + r] = rank_key_value(best) - lse;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (pm[u] > -INFINITY) {
+        const float mn = fmaxf(m_run, pm[u]);
+        s_run = s_run * __expf(m_run - mn) + ps[u] * __expf(pm[u] - mn);
+        m_run = mn;
       }
+#pragma unroll
+      for (int r = 0; r < KMAX; ++r) list.insert(pk[u][r]);
     }
   }
-  if (tid == 0) *p.ticket = 0u;  // ready for the next call on this stream
+  const float mx = wave_max_f32(m_run);
+  const float s = wave_sum_f32(m_run > -INFINITY ? s_run * __expf(m_run - mx) : 0.f);
+  const float lse = mx + __logf(s);
+  if (lane == 0 && p.lse) p.lse[m] = lse;
+  for (int r = 0; r < k; ++r) {
+    const unsigned long long best = wave_max_u64(list.v[0]);
+    if (list.v[0] == best) list.pop();
+    if (lane == 0) {
+      p.topk_id[m * k + r] = (int32_t)rank_key_index(best);
+      p.topk_logp[m * k + r] = rank_key_value(best) - lse;
+    }
+  }
 }
 
 // ---- generic producer ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void lmhead_generic_kernel(LmHeadParams p) {
   __shared__ float zbuf[kMaxCols * kZStride];
-  __shared__ unsigned int flag;
   const int tid = threadIdx.x;
   const int row_base = blockIdx.x * kRowsPerBlock;
   const T* hidden = (const T*)p.hidden;
@@ -157,7 +169,7 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(LmHeadParams p) {
     zbuf[m * kZStride + r] = z;
   }
   __syncthreads();
-  lmhead_block_epilogue(p, zbuf, &flag);
+  lmhead_block_epilogue(p, zbuf);
 }
 
 // ---- bf16 MFMA streaming producer -----------------------------------------------------------------
@@ -166,10 +178,9 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(LmHeadParams p) {
 // two rows x 512 contiguous bytes), parks them in its private LDS strip and reads them back in the
 // MFMA A-operand layout (lane = row, 8 consecutive k).  Loads run STAGES-1 steps ahead in registers.
 // The hidden states (the B operand) sit in LDS for the whole workgroup.
-template <int NT, int STAGES>
+template <int NT, int STAGES, bool CHUNKED>
 __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHeadParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ unsigned int flag;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c = lane & 15, g = lane >> 4;
   const int lrow = lane >> 5, lch = lane & 31;
@@ -198,8 +209,39 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHea
   for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   const int SPC = p.KC / 256;
-  const int nchunks = p.D / p.KC;
+  const int nchunks = CHUNKED ? p.D / p.KC : 1;  // !CHUNKED: the host guarantees KC == D
   const int total_steps = p.D / 256;
+
+  // Hidden-state chunk staging: every thread carries up to kHsPieces 16-byte pieces of the chunk
+  // through registers.  The loads of chunk ch+1 are issued before chunk ch is consumed, so only the
+  // very first chunk exposes its latency - and that one is requested before the first W loads.
+  constexpr int kHsPieces = 12;
+  const int per_row = p.KC / 8;  // 16-byte pieces per column
+  const int hs_total = p.BT * per_row;
+  u32x4 hreg[kHsPieces];
+  auto hs_request = [&](int ch) {
+    const unsigned char* src = (const unsigned char*)p.hidden + (size_t)ch * p.KC * 2;
+#pragma unroll
+    for (int u = 0; u < kHsPieces; ++u) {
+      const int idx = tid + u * 64 * kMfmaWaves;
+      if (idx < hs_total) {
+        const int m = idx / per_row, q = idx % per_row;
+        hreg[u] = *(const u32x4*)(src + (size_t)m * p.D * 2 + q * 16);
+      }
+    }
+  };
+  auto hs_commit = [&]() {
+#pragma unroll
+    for (int u = 0; u < kHsPieces; ++u) {
+      const int idx = tid + u * 64 * kMfmaWaves;
+      if (idx < hs_total) {
+        const int m = idx / per_row, q = idx % per_row;
+        *(u32x4*)(hs + m * HSS + q * 16) = hreg[u];
+      }
+    }
+  };
+
+  hs_request(0);
   u32x4 v[STAGES][8];
   if (active) {
 #pragma unroll
@@ -210,16 +252,10 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHea
   }
 
   for (int ch = 0; ch < nchunks; ++ch) {
-    if (ch > 0) __syncthreads();
-    {
-      const int per_row = p.KC / 8;  // 16-byte pieces per column
-      const unsigned char* src = (const unsigned char*)p.hidden + (size_t)ch * p.KC * 2;
-      for (int idx = tid; idx < p.BT * per_row; idx += 64 * kMfmaWaves) {
-        int m = idx / per_row, q = idx % per_row;
-        *(u32x4*)(hs + m * HSS + q * 16) = *(const u32x4*)(src + (size_t)m * p.D * 2 + q * 16);
-      }
-    }
+    if (ch > 0) __syncthreads();  // every wave is done reading the previous chunk
+    hs_commit();
     __syncthreads();
+    if (CHUNKED && ch + 1 < nchunks) hs_request(ch + 1);
     if (active) {
       for (int i0 = 0; i0 < SPC; i0 += STAGES) {
 #pragma unroll
@@ -265,7 +301,14 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHea
     }
   }
   __syncthreads();
-  lmhead_block_epilogue(p, zbuf, &flag);
+  lmhead_block_epilogue(p, zbuf);
+}
+
+static void launch_merge(const LmHeadParams& p, hipStream_t stream) {
+  if (p.k <= 1) hipLaunchKernelGGL(lmhead_merge_kernel<1>, dim3(p.BT), dim3(64), 0, stream, p);
+  else if (p.k <= 2) hipLaunchKernelGGL(lmhead_merge_kernel<2>, dim3(p.BT), dim3(64), 0, stream, p);
+  else if (p.k <= 4) hipLaunchKernelGGL(lmhead_merge_kernel<4>, dim3(p.BT), dim3(64), 0, stream, p);
+  else hipLaunchKernelGGL(lmhead_merge_kernel<8>, dim3(p.BT), dim3(64), 0, stream, p);
 }
 
 static int pick_kc(int BT, int D, int stages, int budget) {
@@ -278,11 +321,15 @@ static int pick_kc(int BT, int D, int stages, int budget) {
   return 0;
 }
 
-template <int NT, int STAGES>
+template <int NT, int STAGES, bool CHUNKED>
 static hipError_t launch_mfma(const LmHeadParams& p, int lds_bytes, hipStream_t stream) {
-  auto kern = lmhead_bf16_mfma_kernel<NT, STAGES>;
-  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-  if (e != hipSuccess) return e;
+  auto kern = lmhead_bf16_mfma_kernel<NT, STAGES, CHUNKED>;
+  static int lds_allowed = 0;  // per instantiation; raising the limit is needed once per process
+  if (lds_bytes > lds_allowed) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return e;
+    lds_allowed = lds_bytes;
+  }
   hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(64 * kMfmaWaves), lds_bytes, stream, p);
   return hipGetLastError();
 }
@@ -313,14 +360,16 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
   p.BT = B * T; p.D = D; p.Vp1 = Vp1; p.k = k;
   p.KC = 0; p.hs_bytes = 0;
   p.n_blocks = (Vp1 + kRowsPerBlock - 1) / kRowsPerBlock;
-  p.pmax = ctx->lm_pmax; p.psum = ctx->lm_psum; p.pkey = ctx->lm_pkey; p.ticket = ctx->lm_ticket;
+  p.pmax = ctx->lm_pmax; p.psum = ctx->lm_psum; p.pkey = ctx->lm_pkey;
   p.topk_id = topk_id; p.topk_logp = topk_logp; p.lse = lse; p.logits_out = logits_out;
 
   if (dt == CTCSPEC_BF16) {
     const int budget = 160 * 1024 - kMfmaWaves * kWStageBytes - 64;
+    // deep prefetch (4 stages) when the whole hidden dimension fits in LDS at once; otherwise the
+    // hidden states are chunked through LDS and the prefetch is 2 stages deep (register budget)
     int stages = 4;
     int kc = pick_kc(p.BT, D, stages, budget);
-    if (kc == 0) {
+    if (kc != D) {
       stages = 2;
       kc = pick_kc(p.BT, D, stages, budget);
     }
@@ -332,26 +381,37 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
       hipError_t e;
       if (stages == 4) {
         switch (nt) {
-          case 1: e = launch_mfma<1, 4>(p, lds, ctx->stream); break;
-          case 2: e = launch_mfma<2, 4>(p, lds, ctx->stream); break;
-          case 3: e = launch_mfma<3, 4>(p, lds, ctx->stream); break;
-          default: e = launch_mfma<4, 4>(p, lds, ctx->stream); break;
+          case 1: e = launch_mfma<1, 4, false>(p, lds, ctx->stream); break;
+          case 2: e = launch_mfma<2, 4, false>(p, lds, ctx->stream); break;
+          case 3: e = launch_mfma<3, 4, false>(p, lds, ctx->stream); break;
+          default: e = launch_mfma<4, 4, false>(p, lds, ctx->stream); break;
+        }
+      } else if (kc == D) {
+        switch (nt) {
+          case 1: e = launch_mfma<1, 2, false>(p, lds, ctx->stream); break;
+          case 2: e = launch_mfma<2, 2, false>(p, lds, ctx->stream); break;
+          case 3: e = launch_mfma<3, 2, false>(p, lds, ctx->stream); break;
+          default: e = launch_mfma<4, 2, false>(p, lds, ctx->stream); break;
         }
       } else {
         switch (nt) {
-          case 1: e = launch_mfma<1, 2>(p, lds, ctx->stream); break;
-          case 2: e = launch_mfma<2, 2>(p, lds, ctx->stream); break;
-          case 3: e = launch_mfma<3, 2>(p, lds, ctx->stream); break;
-          default: e = launch_mfma<4, 2>(p, lds, ctx->stream); break;
+          case 1: e = launch_mfma<1, 2, true>(p, lds, ctx->stream); break;
+          case 2: e = launch_mfma<2, 2, true>(p, lds, ctx->stream); break;
+          case 3: e = launch_mfma<3, 2, true>(p, lds, ctx->stream); break;
+          default: e = launch_mfma<4, 2, true>(p, lds, ctx->stream); break;
         }
       }
       CTCSPEC_HIP(ctx, e);
+      launch_merge(p, ctx->stream);
+      CTCSPEC_HIP(ctx, hipGetLastError());
       return CTCSPEC_OK;
     }
     hipLaunchKernelGGL(lmhead_generic_kernel<unsigned short>, dim3(p.n_blocks), dim3(256), 0, ctx->stream, p);
   } else {
     hipLaunchKernelGGL(lmhead_generic_kernel<float>, dim3(p.n_blocks), dim3(256), 0, ctx->stream, p);
   }
+  CTCSPEC_HIP(ctx, hipGetLastError());
+  launch_merge(p, ctx->stream);
   CTCSPEC_HIP(ctx, hipGetLastError());
   return CTCSPEC_OK;
 }

@@ -2,30 +2,10 @@
 import functools
 
 import numpy as np
-import torch
 
 import oracle
 import workloads
-
-
-def to_device(x: np.ndarray, dtype: str) -> torch.Tensor:
-    """numpy float32 (already storage-rounded) -> GPU tensor of the storage dtype."""
-    if dtype == "bf16":
-        bits = workloads.f32_to_bf16_bits(x).view(np.int16)
-        return torch.from_numpy(bits).cuda().view(torch.bfloat16)
-    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
-
-
-def dev_i32(x):
-    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).cuda()
-
-
-def dev_i64(x):
-    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.int64)).cuda()
-
-
-def dev_f32(x):
-    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+from workloads.device import dev_f32, dev_i32, dev_i64, to_device  # noqa: F401
 
 
 @functools.lru_cache(maxsize=2)
