@@ -13,8 +13,17 @@
 // candidate.  The half-sum score fl(X+Y) used for thresholding differs from the exact score only by
 // rounding; a margin delta on the threshold makes the walked prefix exactly the global order.
 //
+// The kernel runs on ONE compute unit, so what it costs is dependent LDS round trips and
+// instruction count, not bandwidth.  Hence: sorting happens in registers (bitonic network over DPP
+// lane exchanges per wavefront, then a rank merge of the wavefronts' runs), independent binary
+// searches advance in lockstep, base-k digits come from multiply-high instead of division, and the
+// prefix tree is built level by level by a single wavefront with LDS atomics while the other
+// wavefronts write the draft arrays.
+//
 // Sorted candidates live in LDS while they fit (4096) and in the context's global workspace
 // otherwise (mass ties, or nearly every raw candidate needed).
+#include <type_traits>
+
 #include "common.h"
 
 namespace ctcspec {
@@ -49,18 +58,16 @@ struct CollapseShared {
   int ids[64];
   float logp[64];
   int code[64];
-  float Xv[kHalfMax];  // sorted descending
-  int Xi[kHalfMax];
+  float Xv[kHalfMax];  // first-half sums, sorted descending
+  int Xi[kHalfMax];    // their rank combination
   float Yv[kHalfMax];
   int Yi[kHalfMax];
   int prefix[kHalfMax + 1];
   int red[kWaves];
-  float redf[kWaves];
   float delta;
+  int n_nodes;
   unsigned long long kept_ck[CTCSPEC_MAX_BEAM];
-  unsigned long long kept_first[CTCSPEC_MAX_BEAM];  // per draft: first earlier draft sharing each prefix length
   int kept_len[CTCSPEC_MAX_BEAM];
-  int kept_tok[CTCSPEC_MAX_BEAM][CTCSPEC_MAX_SLOTS];
   int kept_m[CTCSPEC_MAX_BEAM];
   int kept_base[CTCSPEC_MAX_BEAM];
   unsigned long long keys[kLdsCap];
@@ -68,6 +75,7 @@ struct CollapseShared {
   unsigned int table[2 * kLdsCap];
 };
 
+// ---- workgroup / wavefront primitives -------------------------------------------------------------
 // inclusive prefix sum over the wavefront (DPP row shifts, then the row totals through readlane)
 __device__ __forceinline__ int wave_inclusive_scan_i32(int v) {
   v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);
@@ -78,30 +86,6 @@ __device__ __forceinline__ int wave_inclusive_scan_i32(int v) {
             t2 = __builtin_amdgcn_readlane(v, 47);
   const int row = (threadIdx.x & 63) >> 4;
   return v + (row > 0 ? t0 : 0) + (row > 1 ? t1 : 0) + (row > 2 ? t2 : 0);
-}
-
-__device__ __forceinline__ int block_sum(int v, int* red) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  v = wave_sum_i32(v);
-  __syncthreads();
-  if (lane == 0) red[wave] = v;
-  __syncthreads();
-  int s = 0;
-#pragma unroll
-  for (int w = 0; w < kWaves; ++w) s += red[w];
-  return s;
-}
-
-__device__ __forceinline__ float block_max(float v, float* red) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  v = wave_max_f32(v);
-  __syncthreads();
-  if (lane == 0) red[wave] = v;
-  __syncthreads();
-  float s = red[0];
-#pragma unroll
-  for (int w = 1; w < kWaves; ++w) s = fmaxf(s, red[w]);
-  return s;
 }
 
 // exclusive prefix of v over the workgroup's threads (thread order), total in *total
@@ -122,20 +106,35 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* red, int* total)
   return base + incl - v;
 }
 
-// number of second-half combinations j (sorted descending) with fl(x + Yv[j]) >= tau
-__device__ __forceinline__ int count_ge(float x, const float* Yv, int n2, float tau) {
-  int lo = 0, hi = n2;  // invariant: entries < lo pass, entries >= hi fail
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (x + Yv[mid] >= tau) lo = mid + 1; else hi = mid;
+// number of binary-search steps that empty an interval of n entries
+__device__ __forceinline__ int search_steps(int n) { return n > 0 ? 32 - __builtin_clz((unsigned)n) : 0; }
+
+// Two independent searches in lockstep: number of leading entries i of [0, n) with pred(i), where pred
+// is true exactly on a prefix.  Both probes of a step are issued before either result is used, so a
+// step costs one LDS round trip.
+template <typename P0, typename P1>
+__device__ __forceinline__ void prefix_count2(int n, P0 pred0, P1 pred1, int& out0, int& out1) {
+  int pos0 = 0, len0 = n, pos1 = 0, len1 = n;
+  const int steps = search_steps(n);
+  for (int it = 0; it < steps; ++it) {
+    const int h0 = len0 >> 1, h1 = len1 >> 1;
+    const int m0 = min(pos0 + h0, n - 1), m1 = min(pos1 + h1, n - 1);
+    const bool t0 = pred0(m0), t1 = pred1(m1);
+    const bool ok0 = len0 > 0 && t0, ok1 = len1 > 0 && t1;
+    pos0 = ok0 ? m0 + 1 : pos0;
+    len0 = ok0 ? len0 - h0 - 1 : h0;
+    pos1 = ok1 ? m1 + 1 : pos1;
+    len1 = ok1 ? len1 - h1 - 1 : h1;
   }
-  return lo;
+  out0 = pos0;
+  out1 = pos1;
 }
 
 __device__ __forceinline__ unsigned int hash_slot(unsigned long long ck, int log2_size) {
   return (unsigned int)((ck * 0x9E3779B97F4A7C15ull) >> (64 - log2_size));
 }
 
+// ---- sorting in LDS / global memory (any size; the slow path) -------------------------------------
 #define CTCSPEC_CE(a, b, desc)                         \
   {                                                    \
     const unsigned long long x_ = a, y_ = b;           \
@@ -179,8 +178,7 @@ __device__ void block_bitonic_sort_desc(unsigned long long* keys, int n) {
 }
 #undef CTCSPEC_CE
 
-
-// ---- register-resident sorting -------------------------------------------------------------------
+// ---- sorting in registers (the fast path) -----------------------------------------------------------
 // value held by lane (l ^ D), D a power of two below 64
 template <int D>
 __device__ __forceinline__ unsigned int xor_fetch_u32(unsigned int v, bool ror4_is_up) {
@@ -237,52 +235,63 @@ __device__ __forceinline__ void bitonic_sort_upto(unsigned long long (&v)[E], in
   if constexpr (SIZE > 2) bitonic_sort_upto<E, SIZE / 2>(v, lane, ror4_is_up);
   bitonic_merge<E, SIZE, SIZE / 2>(v, lane, ror4_is_up);
 }
-// Sort the 64*E keys of one wavefront descending; key index inside the wavefront = lane*E + e.
-template <int E>
-__device__ __forceinline__ void wave_bitonic_sort_desc(unsigned long long (&v)[E], int lane, bool ror4_is_up) {
-  bitonic_sort_upto<E, 64 * E>(v, lane, ror4_is_up);
-}
 
-// Sort kThreads*E keys descending: every wavefront sorts its 64*E keys in registers, the kWaves sorted
-// runs are merged by rank (position in the own run + number of larger keys in every other run, found
-// by binary search; equal keys are ordered by run).  v[e] is key number (tid*E + e) on entry.
-// runs: LDS scratch of kThreads*E keys; out: kThreads*E keys, sorted on return (barrier included).
-template <int E>
+// Sort keys descending, kThreads*E of them (v[e] is key number tid*E + e on entry).  Every wavefront
+// sorts its 64*E keys in registers; the sorted runs of each group of GROUP consecutive wavefronts are
+// then merged by rank: position in the own run + number of keys in each other run of the group that
+// come first (found by binary search, all searches of a thread in lockstep; equal keys are ordered by
+// run).  Group g's result is out[g*GROUP*64*E ...].  runs: LDS scratch of kThreads*E keys.
+// Barriers included; `out` is complete on return.
+template <int E, int GROUP>
 __device__ __forceinline__ void block_sort_desc_fast(unsigned long long (&v)[E], unsigned long long* runs,
                                                      unsigned long long* out, bool ror4_is_up) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   constexpr int RUN = 64 * E;
-  wave_bitonic_sort_desc<E>(v, lane, ror4_is_up);
+  bitonic_sort_upto<E, RUN>(v, lane, ror4_is_up);
 #pragma unroll
   for (int e = 0; e < E; ++e) runs[wave * RUN + lane * E + e] = v[e];
   __syncthreads();
+  const int group0 = wave & ~(GROUP - 1);  // first wavefront of my group
+  int pos[E][GROUP];
+#pragma unroll
+  for (int e = 0; e < E; ++e)
+#pragma unroll
+    for (int w = 0; w < GROUP; ++w) pos[e][w] = 0;
+  // all keys of run w that come before mine form a prefix of the run; RUN is a power of two
+#pragma unroll
+  for (int h = RUN / 2; h >= 1; h >>= 1) {
+    unsigned long long x[E][GROUP];
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+#pragma unroll
+      for (int w = 0; w < GROUP; ++w) x[e][w] = runs[(group0 + w) * RUN + pos[e][w] + h - 1];
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+#pragma unroll
+      for (int w = 0; w < GROUP; ++w) {
+        const bool before = (group0 + w < wave) ? (x[e][w] >= v[e]) : (x[e][w] > v[e]);
+        pos[e][w] += before ? h : 0;
+      }
+  }
 #pragma unroll
   for (int e = 0; e < E; ++e) {
-    const unsigned long long key = v[e];
     int rank = lane * E + e;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      if (w == wave) continue;
-      const unsigned long long* r = runs + w * RUN;
-      // number of keys of run w that come before `key`: strictly larger, or equal when w < wave
-      int lo = 0, hi = RUN;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        const unsigned long long x = r[mid];
-        const bool before = (w < wave) ? (x >= key) : (x > key);
-        if (before) lo = mid + 1; else hi = mid;
-      }
-      rank += lo;
+    for (int w = 0; w < GROUP; ++w) {
+      const unsigned long long x = runs[(group0 + w) * RUN + pos[e][w]];
+      const bool before = (group0 + w < wave) ? (x >= v[e]) : (x > v[e]);
+      rank += (group0 + w == wave) ? 0 : pos[e][w] + (before ? 1 : 0);
     }
-    out[rank] = key;
+    out[group0 * RUN + rank] = v[e];
   }
   __syncthreads();
 }
 
-// a / k and a % k for 0 <= a < 65536, magic = ceil(2^32 / k)
+// ---- raw candidates ---------------------------------------------------------------------------------
+// a / k for 0 <= a < 65536, magic = ceil(2^32 / k)
 __device__ __forceinline__ int div_small(int a, unsigned int magic) { return (int)__umulhi((unsigned)a, magic); }
 
-// The four rank digits of a half-combination, most significant slot first.  a counts in base k with
+// The rank digits of a half-combination, most significant slot first.  a counts in base k with
 // nt <= 4 digits; it is first shifted up to exactly four digits so that digit positions are static.
 struct Digits4 {
   int r[4];  // r[t] = rank chosen for the half's slot t (valid for t < nt)
@@ -299,43 +308,41 @@ __device__ __forceinline__ Digits4 split_digits(int a, int pad, int k, unsigned 
   return d;
 }
 
-// left-to-right float32 sum: acc, then the half's slots t0.. in order
+// left-to-right float32 sum: acc (if have_acc), then the half's slots t0.. in order
 __device__ __forceinline__ float add_slots(float acc, bool have_acc, const float* logp, const Digits4& d, int t0,
                                            int nt, int k) {
+  float l[4];
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    if (t < nt) {
-      const float l = logp[(t0 + t) * k + d.r[t]];
-      acc = (have_acc || t > 0) ? acc + l : l;
-    }
-  }
+  for (int t = 0; t < 4; ++t) l[t] = t < nt ? logp[(t0 + t) * k + d.r[t]] : 0.f;
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+    if (t < nt) acc = (have_acc || t > 0) ? acc + l[t] : l[t];
   return acc;
 }
 
 // Collapsed-sequence key of the raw candidate (a, b): 7-bit local token codes, position 0 in the low
-// bits, unused positions = kBlankCode.  Optionally writes the collapsed token ids.
+// bits, unused positions = kBlankCode.
 __device__ __forceinline__ unsigned long long collapse_key(const CollapseShared& s, const Digits4& da,
-                                                           const Digits4& db, int T1, int T2, int k, int* len_out,
-                                                           int* tok_out) {
-  unsigned long long key = 0x00ffffffffffffffull;
-  int len = 0, prev = -1;
+                                                           const Digits4& db, int T1, int T2, int k, int* len_out) {
+  int cd[8];
 #pragma unroll
   for (int u = 0; u < 8; ++u) {
     const bool first_half = u < 4;
     const int t_in = first_half ? u : u - 4;
     const bool live = first_half ? (t_in < T1) : (t_in < T2);
-    if (live) {
-      const int slot = first_half ? t_in : T1 + t_in;
-      const int r = first_half ? da.r[t_in] : db.r[t_in];
-      const int cd = s.code[slot * k + r];
-      if (cd != prev && cd != kBlankCode) {
-        key &= ~(0x7full << (7 * len));
-        key |= (unsigned long long)cd << (7 * len);
-        if (tok_out) tok_out[len] = s.ids[slot * k + r];
-        ++len;
-      }
-      prev = cd;
-    }
+    const int slot = first_half ? t_in : T1 + t_in;
+    const int r = first_half ? da.r[t_in] : db.r[t_in];
+    cd[u] = live ? s.code[slot * k + r] : -2;  // -2: slot does not exist
+  }
+  unsigned long long key = 0x00ffffffffffffffull;
+  int len = 0, prev = -1;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const bool emit = cd[u] >= 0 && cd[u] != prev && cd[u] != kBlankCode;
+    const int sh = 7 * len;
+    key = emit ? ((key & ~(0x7full << sh)) | ((unsigned long long)cd[u] << sh)) : key;
+    len += emit ? 1 : 0;
+    prev = cd[u] >= 0 ? cd[u] : prev;
   }
   *len_out = len;
   return key;
@@ -387,37 +394,38 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
   __syncthreads();
   const float delta = s.delta;
 
-  // ---- half sums X (slots < T1) and Y (the rest), both sorted descending in one sort ------------
-  // key = [is X : 1][ordered value : 32][~index : 31]: all X sort before all Y
+  // ---- half sums X (slots < T1) and Y (the rest), each sorted descending ---------------------------
+  // wavefronts 0,1 sort X, wavefronts 2,3 sort Y: key slot gi belongs to X for gi < 128*E
   {
-    const int nxy = n1 + n2;
-    auto make_key = [&](int gi) -> unsigned long long {
-      if (gi >= nxy) return 0ull;
-      const bool is_x = gi < n1;
-      const int a = is_x ? gi : gi - n1;
-      const Digits4 d = split_digits(a, is_x ? pad1 : pad2, k, magic);
-      const float v = add_slots(0.f, false, s.logp, d, is_x ? 0 : T1, is_x ? T1 : T2, k);
-      return ((unsigned long long)(is_x ? 1 : 0) << 63) | ((unsigned long long)float_to_ordered(v) << 31) |
-             (unsigned long long)(0x7fffffff - a);
+    auto sort_halves = [&](auto e_tag) {
+      constexpr int E = decltype(e_tag)::value;
+      unsigned long long v[E];
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const int gi = tid * E + e;
+        const bool is_x = gi < 128 * E;
+        const int a = is_x ? gi : gi - 128 * E;
+        unsigned long long key = 0ull;
+        if (a < (is_x ? n1 : n2)) {
+          const Digits4 d = split_digits(a, is_x ? pad1 : pad2, k, magic);
+          key = rank_key(add_slots(0.f, false, s.logp, d, is_x ? 0 : T1, is_x ? T1 : T2, k), (unsigned)a);
+        }
+        v[e] = key;
+      }
+      block_sort_desc_fast<E, 2>(v, s.ckeys, s.keys, ror4_is_up);
+      for (int i = tid; i < n1; i += kThreads) {
+        s.Xv[i] = rank_key_value(s.keys[i]);
+        s.Xi[i] = (int)rank_key_index(s.keys[i]);
+      }
+      for (int i = tid; i < n2; i += kThreads) {
+        s.Yv[i] = rank_key_value(s.keys[128 * E + i]);
+        s.Yi[i] = (int)rank_key_index(s.keys[128 * E + i]);
+      }
     };
-    if (nxy <= 2 * kThreads) {
-      unsigned long long v[2];
-#pragma unroll
-      for (int e = 0; e < 2; ++e) v[e] = make_key(tid * 2 + e);
-      block_sort_desc_fast<2>(v, s.ckeys, s.keys, ror4_is_up);
-    } else {
-      unsigned long long v[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = make_key(tid * 4 + e);
-      block_sort_desc_fast<4>(v, s.ckeys, s.keys, ror4_is_up);
-    }
-    for (int i = tid; i < nxy; i += kThreads) {
-      const unsigned long long key = s.keys[i];
-      const float v = ordered_to_float((unsigned int)(key >> 31));
-      const int a = 0x7fffffff - (int)(key & 0x7fffffffull);
-      if (i < n1) { s.Xv[i] = v; s.Xi[i] = a; }
-      else { s.Yv[i - n1] = v; s.Yi[i - n1] = a; }
-    }
+    const int nmax = n1 > n2 ? n1 : n2;
+    if (nmax <= 128) sort_halves(std::integral_constant<int, 1>{});
+    else if (nmax <= 256) sort_halves(std::integral_constant<int, 2>{});
+    else sort_halves(std::integral_constant<int, 4>{});
     __syncthreads();
   }
 
@@ -427,19 +435,22 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
   bool in_lds = true;
 
   int M = beam;
-  int n_v = 0, n_d = 0, log2_ts = 6;
+  int n_d = 0;
   for (;;) {
     if (M > total) M = total;
     const bool final_level = (M >= total);
     float tau_valid = -INFINITY, tau_f = -INFINITY;
     if (!final_level) {
-      // X_(i) + Y_(j) with (i+1)(j+1) >= M is passed by at least M raw candidates
+      // X_(i) + Y_(j) with (i+1)(j+1) >= M is passed by at least M raw candidates; every wavefront
+      // evaluates all i (j = ceil(M/(i+1)) - 1 = floor((M-1)/(i+1))), so no exchange is needed
       float best = -INFINITY;
-      for (int i = tid; i < n1; i += kThreads) {
-        const int j = (M + i) / (i + 1) - 1;
+      for (int i = lane; i < n1; i += 64) {
+        int j = (int)((float)(M - 1) / (float)(i + 1));
+        j -= (j * (i + 1) > M - 1) ? 1 : 0;
+        j += ((j + 1) * (i + 1) <= M - 1) ? 1 : 0;
         if (j < n2) best = fmaxf(best, s.Xv[i] + s.Yv[j]);
       }
-      const float tau = block_max(best, s.redf);
+      const float tau = wave_max_f32(best);
       tau_valid = tau - delta;
       tau_f = tau_valid - delta;
     }
@@ -448,8 +459,12 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
     {
       // kHalfMax <= 2 * kThreads: thread t owns entries 2t and 2t+1
       const int i0 = 2 * tid, i1 = 2 * tid + 1;
-      const int c0 = i0 < n1 ? count_ge(s.Xv[i0], s.Yv, n2, tau_f) : 0;
-      const int c1 = i1 < n1 ? count_ge(s.Xv[i1], s.Yv, n2, tau_f) : 0;
+      const float x0 = s.Xv[i0 < n1 ? i0 : 0], x1 = s.Xv[i1 < n1 ? i1 : 0];
+      int c0, c1;
+      prefix_count2(
+          n2, [&](int m) { return x0 + s.Yv[m] >= tau_f; }, [&](int m) { return x1 + s.Yv[m] >= tau_f; }, c0, c1);
+      c0 = i0 < n1 ? c0 : 0;
+      c1 = i1 < n1 ? c1 : 0;
       const int excl = block_exclusive_scan(c0 + c1, s.red, &n_s);
       if (i0 < n1) s.prefix[i0] = excl;
       if (i1 < n1) s.prefix[i1] = excl + c0;
@@ -462,61 +477,72 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
       table = reinterpret_cast<unsigned int*>(ckeys + kMaxAlign);
     }
     __syncthreads();
-    // exact key of survivor number i (row = sorted X entry, column = sorted Y entry)
-    auto survivor_key = [&](int i) -> unsigned long long {
-      if (i >= n_s) return 0ull;
-      int lo_a = 0, hi_a = n1;  // largest row with prefix[row] <= i
-      while (hi_a - lo_a > 1) {
-        const int mid = (lo_a + hi_a) >> 1;
-        if (s.prefix[mid] <= i) lo_a = mid; else hi_a = mid;
-      }
-      const int ib = s.Yi[i - s.prefix[lo_a]];
+    // exact key of a survivor at (row of sorted X, column of sorted Y): the first half's partial sum is
+    // exactly the left-to-right prefix of the score
+    auto key_at = [&](int row, int col, bool live) -> unsigned long long {
+      const int ib = s.Yi[col];
       const Digits4 db = split_digits(ib, pad2, k, magic);
-      // the first half's partial sum is exactly the left-to-right prefix of the score
-      const float sc = add_slots(s.Xv[lo_a], true, s.logp, db, T1, T2, k);
-      return rank_key(sc, (unsigned)(s.Xi[lo_a] * n2 + ib));
+      const float sc = add_slots(s.Xv[row], true, s.logp, db, T1, T2, k);
+      return live ? rank_key(sc, (unsigned)(s.Xi[row] * n2 + ib)) : 0ull;
+    };
+    // keys of survivors i0 and i0+1: their rows are (number of rows starting at or before them) - 1
+    auto key_pair = [&](int i0, unsigned long long& k0, unsigned long long& k1) {
+      const int i1 = i0 + 1;
+      int r0, r1;
+      prefix_count2(
+          n1, [&](int m) { return s.prefix[m] <= i0; }, [&](int m) { return s.prefix[m] <= i1; }, r0, r1);
+      const bool l0 = i0 < n_s, l1 = i1 < n_s;
+      r0 = l0 ? r0 - 1 : 0;
+      r1 = l1 ? r1 - 1 : 0;
+      k0 = key_at(r0, l0 ? i0 - s.prefix[r0] : 0, l0);
+      k1 = key_at(r1, l1 ? i1 - s.prefix[r1] : 0, l1);
+    };
+    auto sort_survivors_fast = [&](auto e_tag) {
+      constexpr int E = decltype(e_tag)::value;
+      unsigned long long v[E];
+#pragma unroll
+      for (int e = 0; e < E; e += 2) key_pair(tid * E + e, v[e], v[e + 1]);
+      block_sort_desc_fast<E, kWaves>(v, s.ckeys, s.keys, ror4_is_up);
     };
     if (n_s <= 2 * kThreads) {
-      unsigned long long v[2];
-#pragma unroll
-      for (int e = 0; e < 2; ++e) v[e] = survivor_key(tid * 2 + e);
-      block_sort_desc_fast<2>(v, s.ckeys, s.keys, ror4_is_up);
+      sort_survivors_fast(std::integral_constant<int, 2>{});
     } else if (n_s <= 8 * kThreads) {
-      unsigned long long v[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = survivor_key(tid * 8 + e);
-      block_sort_desc_fast<8>(v, s.ckeys, s.keys, ror4_is_up);
+      sort_survivors_fast(std::integral_constant<int, 8>{});
     } else {
       int P2 = 64;
       while (P2 < n_s) P2 <<= 1;
-      for (int i = tid; i < P2; i += kThreads) keys[i] = survivor_key(i);
+      for (int i0 = 2 * tid; i0 < P2; i0 += 2 * kThreads) {
+        unsigned long long k0, k1;
+        key_pair(i0, k0, k1);
+        keys[i0] = k0;
+        keys[i0 + 1] = k1;
+      }
       __syncthreads();
       block_bitonic_sort_desc(keys, P2);
     }
 
-    // the prefix that is exactly the global (score desc, idx asc) order
-    if (final_level) {
-      n_v = n_s;
-    } else {
-      int c = 0;
-      for (int i = tid; i < n_s; i += kThreads) c += (rank_key_value(keys[i]) >= tau_valid) ? 1 : 0;
-      n_v = block_sum(c, s.red);
-    }
-    // collapse every walked candidate and find first occurrences through a hash table of positions
-    log2_ts = 6;
-    while ((1 << log2_ts) < 2 * n_v) ++log2_ts;
+    // Walk the sorted survivors.  Down to score tau_valid the list is exactly the global order (every
+    // raw candidate that good is a survivor); those positions are collapsed and first occurrences are
+    // found through a hash table of positions.
+    int log2_ts = 6;
+    while ((1 << log2_ts) < 2 * n_s) ++log2_ts;
     const int TS = 1 << log2_ts;
     for (int i = tid; i < TS; i += kThreads) table[i] = kEmptySlot;
-    for (int i = tid; i < n_v; i += kThreads) {
-      const int idx = (int)rank_key_index(keys[i]);
-      const int a = idx / n2, bb = idx - a * n2;
-      int len;
-      const unsigned long long ck = collapse_key(s, split_digits(a, pad1, k, magic), split_digits(bb, pad2, k, magic),
-                                                 T1, T2, k, &len, nullptr);
-      ckeys[i] = len ? ck : ~0ull;  // ~0 marks the empty draft (no real key has the top byte set)
+    for (int i = tid; i < n_s; i += kThreads) {
+      const unsigned long long key = keys[i];
+      unsigned long long ck = ~0ull;  // ~0: not walked (below tau_valid) or the empty draft
+      if (final_level || rank_key_value(key) >= tau_valid) {
+        const int idx = (int)rank_key_index(key);
+        const int a = idx / n2, bb = idx - a * n2;
+        int len;
+        const unsigned long long c =
+            collapse_key(s, split_digits(a, pad1, k, magic), split_digits(bb, pad2, k, magic), T1, T2, k, &len);
+        ck = len ? c : ~0ull;
+      }
+      ckeys[i] = ck;
     }
     __syncthreads();
-    for (int i = tid; i < n_v; i += kThreads) {
+    for (int i = tid; i < n_s; i += kThreads) {
       const unsigned long long ck = ckeys[i];
       if (ck == ~0ull) continue;
       unsigned int slot = hash_slot(ck, log2_ts);
@@ -531,31 +557,38 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
       }
     }
     __syncthreads();
-    // count distinct non-empty drafts; thread t scans positions [t*per, (t+1)*per)
-    const int per = (n_v + kThreads - 1) / kThreads;
+    // distinct non-empty drafts in walk order; thread t owns positions [t*per, (t+1)*per)
+    const int per = (n_s + kThreads - 1) / kThreads;
+    const int i_begin = tid * per, i_end = min(n_s, (tid + 1) * per);
     int first_cnt = 0;
-    for (int i = tid * per; i < (tid + 1) * per && i < n_v; ++i) {
+    unsigned int first_bits = 0u;  // flags of my first 32 positions, so that they are not looked up twice
+    for (int i = i_begin; i < i_end; ++i) {
       const unsigned long long ck = ckeys[i];
       if (ck == ~0ull) continue;
       unsigned int slot = hash_slot(ck, log2_ts);
       while (ckeys[table[slot]] != ck) slot = (slot + 1) & (TS - 1);
-      first_cnt += (table[slot] == (unsigned)i) ? 1 : 0;
+      const bool is_first = table[slot] == (unsigned)i;
+      first_cnt += is_first ? 1 : 0;
+      if (is_first && i - i_begin < 32) first_bits |= 1u << (i - i_begin);
     }
     const int rank0 = block_exclusive_scan(first_cnt, s.red, &n_d);
     if (n_d >= beam || final_level) {
-      // write the kept drafts (rank < beam)
       int rank = rank0;
-      for (int i = tid * per; i < (tid + 1) * per && i < n_v && rank < beam; ++i) {
+      for (int i = i_begin; i < i_end && rank < beam; ++i) {
         const unsigned long long ck = ckeys[i];
-        if (ck == ~0ull) continue;
-        unsigned int slot = hash_slot(ck, log2_ts);
-        while (ckeys[table[slot]] != ck) slot = (slot + 1) & (TS - 1);
-        if (table[slot] != (unsigned)i) continue;
-        const int idx = (int)rank_key_index(keys[i]);
-        const int a = idx / n2, bb = idx - a * n2;
-        int len;
-        collapse_key(s, split_digits(a, pad1, k, magic), split_digits(bb, pad2, k, magic), T1, T2, k, &len,
-                     s.kept_tok[rank]);
+        bool is_first;
+        if (i - i_begin < 32) {
+          is_first = (first_bits >> (i - i_begin)) & 1u;
+        } else {
+          if (ck == ~0ull) continue;
+          unsigned int slot = hash_slot(ck, log2_ts);
+          while (ckeys[table[slot]] != ck) slot = (slot + 1) & (TS - 1);
+          is_first = table[slot] == (unsigned)i;
+        }
+        if (!is_first) continue;
+        int len = 0;
+#pragma unroll
+        for (int d = 0; d < 8; ++d) len += (((ck >> (7 * d)) & 0x7f) != kBlankCode) ? 1 : 0;
         s.kept_ck[rank] = ck;
         s.kept_len[rank] = len;
         p.cand_score[(size_t)b * beam + rank] = rank_key_value(keys[i]);
@@ -566,89 +599,97 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
     M *= 4;
     __syncthreads();
   }
+  // the hash table is done with; the tree build below uses it as a zeroed direct-address table
+  __syncthreads();
+  for (int i = tid; i < 2 * kLdsCap; i += kThreads) s.table[i] = 0u;
   __syncthreads();
 
-  // ---- outputs: drafts --------------------------------------------------------------------------
   const int n_c = n_d < beam ? n_d : beam;
-  for (int i = tid; i < beam * T; i += kThreads) {
-    const int c = i / T, d = i - c * T;
-    p.cand_tokens[(size_t)b * beam * T + i] = (c < n_c && d < s.kept_len[c]) ? s.kept_tok[c][d] : -1;
-  }
-  for (int c = tid; c < beam; c += kThreads) {
-    p.cand_len[(size_t)b * beam + c] = c < n_c ? s.kept_len[c] : 0;
-    if (c >= n_c) p.cand_score[(size_t)b * beam + c] = -INFINITY;
-  }
+  const int W = (max_nodes + 63) / 64;
+  int32_t* node_token = p.node_token + (size_t)b * max_nodes;
+  int32_t* node_parent = p.node_parent + (size_t)b * max_nodes;
+  int32_t* node_depth = p.node_depth + (size_t)b * max_nodes;
+  unsigned long long* mask = p.anc_mask + (size_t)b * max_nodes * W;
 
-  // ---- prefix tree --------------------------------------------------------------------------------
-  // Draft c needs m = the longest prefix it shares with any earlier draft and, for every prefix length
-  // d <= m, the FIRST earlier draft sharing it (that draft created the node).  Thread (c, half) walks
-  // half of the earlier drafts; the halves are combined through LDS.  Tokens beyond m create nodes;
-  // node ids are handed out in (draft, depth) order.
-  {
-    const int c = tid & 127, half = tid >> 7;  // beam <= 128, kThreads == 256
-    int have = 0;
-    unsigned long long first = 0ull;  // byte d-1 = first draft sharing the prefix of length d
-    if (c < n_c) {
-      const unsigned long long mine = s.kept_ck[c];
-      const int lo2 = half * 64;
-      const int hi2 = c < lo2 + 64 ? c : lo2 + 64;
-      for (int c2 = lo2; c2 < hi2; ++c2) {
-        const int lcp = (__builtin_ctzll(mine ^ s.kept_ck[c2]) * 37) >> 8;  // ctz / 7 for ctz < 64
-        while (have < lcp) {
-          first |= (unsigned long long)c2 << (8 * have);
-          ++have;
+  if (wave == 0) {
+    // ---- prefix tree, by one wavefront; lane l owns drafts l and l+64 --------------------------
+    // A node is a distinct draft prefix; it is created by the first (best-ranked) draft that has it.
+    // Level by level, drafts announce (creator of their parent node, token code) in a direct-address
+    // table with an atomic max of (level, 127 - draft): per entry the current level's smallest draft
+    // number wins and is read back as the creator of the draft's node on that level.  LDS operations
+    // of one wavefront execute in order, so no barrier is needed between the levels.
+    unsigned long long ck[2], creators[2] = {0ull, 0ull};  // byte d-1: creator of my node at depth d
+    int len[2], fprev[2] = {0, 0};
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int c = lane + 64 * u;
+      ck[u] = c < n_c ? s.kept_ck[c] : 0ull;
+      len[u] = c < n_c ? s.kept_len[c] : 0;
+    }
+    for (int d = 1; d <= T; ++d) {
+      unsigned int key[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        key[u] = ((unsigned)fprev[u] << 6) | (unsigned)((ck[u] >> (7 * (d - 1))) & 0x3f);
+        if (d <= len[u]) atomicMax(&s.table[key[u]], ((unsigned)d << 8) | (unsigned)(127 - (lane + 64 * u)));
+      }
+      // every lane's announcements must be issued before any lane reads a winner back: keep the
+      // compiler from moving the reads up (the hardware executes a wavefront's LDS operations in order)
+      __atomic_signal_fence(__ATOMIC_SEQ_CST);
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        if (d <= len[u]) {
+          const unsigned int won = __hip_atomic_load(&s.table[key[u]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          fprev[u] = 127 - (int)(won & 0xffu);
+          creators[u] |= (unsigned long long)fprev[u] << (8 * (d - 1));
         }
       }
     }
-    if (half == 1) {
-      s.kept_m[c] = have;       // scratch: second half's result
-      s.kept_first[c] = first;
+    // m = number of leading levels whose node another draft created; my tokens beyond m create nodes,
+    // node ids are handed out in (draft, depth) order
+    int m[2], excl[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int c = lane + 64 * u;
+      int mm = 0;
+#pragma unroll
+      for (int d = 0; d < 8; ++d) mm += (d < len[u] && (int)((creators[u] >> (8 * d)) & 0xff) != c) ? 1 : 0;
+      m[u] = mm;
     }
-    __syncthreads();
-    int my_new = 0;
-    if (half == 0 && c < n_c) {
-      const int have1 = s.kept_m[c];
-      const unsigned long long first1 = s.kept_first[c];
-      // prefix lengths <= have come from the lower half (smaller draft numbers win); longer ones, if
-      // any, from the upper half
-      if (have1 > have) {
-        const unsigned long long keep = have ? (~0ull >> (64 - 8 * have)) : 0ull;
-        first = (first & keep) | (first1 & ~keep);
-        have = have1;
+    const int inc0 = wave_inclusive_scan_i32(len[0] - m[0]);
+    const int tot0 = __builtin_amdgcn_readlane(inc0, 63);
+    const int inc1 = wave_inclusive_scan_i32(len[1] - m[1]);
+    const int total_new = tot0 + __builtin_amdgcn_readlane(inc1, 63);
+    excl[0] = inc0 - (len[0] - m[0]);
+    excl[1] = tot0 + inc1 - (len[1] - m[1]);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int c = lane + 64 * u;
+      if (c < n_c) {
+        s.kept_m[c] = m[u];
+        s.kept_base[c] = 1 + excl[u];
       }
-      my_new = s.kept_len[c] - have;
     }
-    __syncthreads();
-    if (half == 0 && c < n_c) {
-      s.kept_m[c] = have;
-      s.kept_first[c] = first;
-    }
-    int total_new;
-    const int excl = block_exclusive_scan(my_new, s.red, &total_new);  // drafts are threads 0..127
-    if (half == 0 && c < n_c) s.kept_base[c] = 1 + excl;
-    __syncthreads();
     const int n_nodes = (1 + total_new) < max_nodes ? (1 + total_new) : max_nodes;
-    const int W = (max_nodes + 63) / 64;
-    int32_t* node_token = p.node_token + (size_t)b * max_nodes;
-    int32_t* node_parent = p.node_parent + (size_t)b * max_nodes;
-    int32_t* node_depth = p.node_depth + (size_t)b * max_nodes;
-    unsigned long long* mask = p.anc_mask + (size_t)b * max_nodes * W;
-    if (half == 0 && c < n_c) {
-      const int len = s.kept_len[c], m = have, my_base = 1 + excl;
+    if (lane == 0) {
+      s.n_nodes = n_nodes;
+      p.n_cand[b] = n_c;
+      p.n_nodes[b] = n_nodes;
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int c = lane + 64 * u;
+      if (c >= n_c) continue;
       int par = 0, leaf = -1;
       unsigned long long m0 = 1ull, m1 = 0ull;  // ancestors so far: the root
-      for (int d = 0; d < len; ++d) {
-        int node;
-        if (d < m) {
-          const int f = (int)((first >> (8 * d)) & 0xff);
-          node = s.kept_base[f] + (d - s.kept_m[f]);
-        } else {
-          node = my_base + (d - m);
-        }
+      for (int d = 0; d < len[u]; ++d) {
+        const int f = (int)((creators[u] >> (8 * d)) & 0xff);
+        const int node = s.kept_base[f] + (d - s.kept_m[f]);
         if (node >= max_nodes) { leaf = -1; break; }
         if (node < 64) m0 |= 1ull << node; else m1 |= 1ull << (node - 64);
-        if (d >= m) {
-          node_token[node] = s.kept_tok[c][d];
+        if (f == c) {
+          node_token[node] = s.ids[(int)((ck[u] >> (7 * d)) & 0x7f)];
           node_parent[node] = par;
           node_depth[node] = d + 1;
           mask[(size_t)node * W] = m0;
@@ -659,26 +700,39 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
       }
       p.cand_leaf[(size_t)b * beam + c] = leaf;
     }
-    for (int cc = tid; cc < beam; cc += kThreads)
-      if (cc >= n_c) p.cand_leaf[(size_t)b * beam + cc] = -1;
-    for (int i = tid; i < max_nodes; i += kThreads) {
-      if (i == 0) {
-        node_token[0] = p.root_token[b];
-        node_parent[0] = -1;
-        node_depth[0] = 0;
-        mask[0] = 1ull;
-        if (W > 1) mask[1] = 0ull;
-      } else if (i >= n_nodes) {
-        node_token[i] = -1;
-        node_parent[i] = -1;
-        node_depth[i] = -1;
-        mask[(size_t)i * W] = 0ull;
-        if (W > 1) mask[(size_t)i * W + 1] = 0ull;
+  } else {
+    // ---- draft arrays, by the other wavefronts ----------------------------------------------------
+    for (int i = tid - 64; i < beam * 8; i += kThreads - 64) {
+      const int c = i >> 3, d = i & 7;
+      if (d < T) {
+        int tok = -1;
+        if (c < n_c && d < s.kept_len[c]) tok = s.ids[(int)((s.kept_ck[c] >> (7 * d)) & 0x7f)];
+        p.cand_tokens[((size_t)b * beam + c) * T + d] = tok;
       }
     }
-    if (tid == 0) {
-      p.n_cand[b] = n_c;
-      p.n_nodes[b] = n_nodes;
+    for (int c = tid - 64; c < beam; c += kThreads - 64) {
+      p.cand_len[(size_t)b * beam + c] = c < n_c ? s.kept_len[c] : 0;
+      if (c >= n_c) {
+        p.cand_score[(size_t)b * beam + c] = -INFINITY;
+        p.cand_leaf[(size_t)b * beam + c] = -1;
+      }
+    }
+  }
+  __syncthreads();
+  const int n_nodes = s.n_nodes;
+  for (int i = tid; i < max_nodes; i += kThreads) {
+    if (i == 0) {
+      node_token[0] = p.root_token[b];
+      node_parent[0] = -1;
+      node_depth[0] = 0;
+      mask[0] = 1ull;
+      if (W > 1) mask[1] = 0ull;
+    } else if (i >= n_nodes) {
+      node_token[i] = -1;
+      node_parent[i] = -1;
+      node_depth[i] = -1;
+      mask[(size_t)i * W] = 0ull;
+      if (W > 1) mask[(size_t)i * W + 1] = 0ull;
     }
   }
 }
@@ -720,8 +774,10 @@ extern "C" int ctc_collapse_tree(ctcspec_ctx* ctx, const int32_t* topk_id, const
   p.ws = ctx->collapse_ws;
   static_assert(sizeof(CollapseShared) <= 160 * 1024, "collapse LDS footprint");
   static_assert(kHalfMax <= 2 * kThreads, "two sorted first-half entries per thread");
-  static_assert(CTCSPEC_MAX_BEAM * 2 == kThreads, "tree build maps (draft, half) onto the threads");
+  static_assert(CTCSPEC_MAX_BEAM <= 128, "the tree build keeps two drafts per lane of one wavefront");
   static_assert(CTCSPEC_MAX_SLOTS <= 8 && CTCSPEC_MAX_TOPK <= 8, "half combinations have at most four base-k digits");
+  static_assert(CTCSPEC_MAX_SLOTS * CTCSPEC_MAX_TOPK <= 64, "token codes fit 6 bits; the top-k lists fit one wavefront");
+  static_assert(128 * 64 <= 2 * kLdsCap, "direct-address table of (creator, code) pairs");
   const int lds = (int)sizeof(CollapseShared);
   static bool lds_allowed = false;
   if (!lds_allowed) {
