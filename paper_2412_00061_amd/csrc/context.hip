@@ -68,9 +68,11 @@ extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec
   size_t o_psum = carve((size_t)ctx->lm_max_blocks * kMaxCols * sizeof(float));
   size_t o_pkey = carve((size_t)ctx->lm_max_blocks * kMaxCols * kMaxTopk * sizeof(unsigned long long));
   size_t o_coll = carve((size_t)lim->max_batch * kCollapseWsBytesPerSeq);
-  size_t o_po = carve((size_t)ctx->attn_units * lim->max_nodes * lim->max_head_dim * sizeof(float));
-  size_t o_pm = carve((size_t)ctx->attn_units * lim->max_nodes * sizeof(float));
-  size_t o_pl = carve((size_t)ctx->attn_units * lim->max_nodes * sizeof(float));
+  // attention partials are stored per query block of up to 64 rows: round the row count up
+  const size_t attn_rows = (size_t)ctx->attn_units * (((size_t)lim->max_nodes + 63) / 64 * 64);
+  size_t o_po = carve(attn_rows * lim->max_head_dim * sizeof(float));
+  size_t o_pm = carve(attn_rows * sizeof(float));
+  size_t o_pl = carve(attn_rows * sizeof(float));
   ctx->ws_bytes = off;
   e = hipMalloc(&ctx->ws, ctx->ws_bytes);
   if (e != hipSuccess) {

@@ -5,6 +5,8 @@
 //                                softmax, every wavefront streams its own share of the keys
 //   * tree_attn_generic_kernel - any dtype / head dimension within the limits: one workgroup per
 //                                (node, head, sequence), keys in chunks with an online softmax
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace ctcspec {
@@ -119,47 +121,66 @@ __global__ __launch_bounds__(kGenericThreads) void tree_attn_generic_kernel(Attn
 
 
 // ---- bf16, dh = 128 -------------------------------------------------------------------------------
-// Workgroup = kAttnWaves wavefronts = one block of 16 query nodes of one (sequence, head).  The keys
-// (cached context rows first, then the tree nodes) are cut into tiles of 32; wavefront w takes tiles
-// w, w+kAttnWaves, ... and runs its own online softmax over them; the wavefronts' partial results are
-// merged through LDS at the end, so there is no second kernel and no partial result in HBM.
+// Workgroup = kAttnWaves wavefronts = one block of 16*QT query nodes of one (sequence, head) and one
+// of S splits of the keys.  The keys (cached context rows first, then the tree nodes) are cut into
+// tiles of 32; the 4*S wavefronts that share a query block take the tiles round robin, each running
+// its own online softmax; a workgroup's wavefronts are merged through LDS at the end.  With S == 1
+// that is the result; otherwise the workgroup leaves an unnormalised partial (O, max, sum) in the
+// context workspace and tree_attn_merge_kernel combines the S partials.
 //
 // Per tile and wavefront:
 //   S^T[key, q] = K.Q^T   : A = K rows (staged through a private LDS strip to get from coalesced
-//                           256-byte row reads to the MFMA A layout), B = Q^T (resident in VGPRs)
+//                           256-byte row reads to the MFMA A layout), B = Q^T (resident in VGPRs);
+//                           every K fragment is used for all QT query tiles
 //   P = exp2(S^T*c - m)   : in the MFMA C layout a lane holds 8 keys of ONE query column, so the
 //                           running max/sum are per lane plus a 4-lane exchange
 //   O^T[dh, q] += V^T.P   : P stays in registers as the B operand (hi + lo bf16 halves, so that P
 //                           carries 16 mantissa bits); V is read straight from global memory, 16
 //                           bytes (8 consecutive dh of one key) per lane and load, and an 8x8 16-bit
-//                           transpose inside the lane turns that into A operands.  MFMA row r of
-//                           output block db stands for dh = 8*r + db, which makes every V load a
-//                           contiguous 16 bytes; the permutation is undone when O is written.
-// Workgroups of the same (sequence, head) differ only in the query block and are given block
-// indices congruent modulo 8, i.e. the same XCD, so K/V are fetched from HBM once and re-read from
-// that XCD's L2.
+//                           transpose inside the lane turns that into A operands, shared by the QT
+//                           query tiles.  MFMA row r of output block db stands for dh = 8*r + db,
+//                           which makes every V load a contiguous 16 bytes; the permutation is
+//                           undone when O is written.
+// K/V are re-read once per query block; workgroups of the same (sequence, head) are given block
+// indices congruent modulo 8, i.e. the same XCD, so those re-reads are served by that XCD's L2.
 constexpr int kAttnWaves = 4;
 constexpr int kTileKeys = 32;
 constexpr int kStripRow = 256 + 16;                    // bytes per staged K row
 constexpr int kStripBytes = kTileKeys * kStripRow;     // per wavefront
 constexpr int kMergeRow = 128 + 4;                     // floats per query row in the merge buffer
-constexpr int kMergeBytes = 16 * kMergeRow * 4;        // per wavefront
-constexpr int kAttnLdsPerWave = kStripBytes > kMergeBytes ? kStripBytes : kMergeBytes;
 
-__global__ __launch_bounds__(64 * kAttnWaves) void tree_attn_bf16_kernel(AttnParams p, int QB) {
+template <int QT>
+constexpr int attn_lds_per_wave() {
+  return kStripBytes > QT * 16 * kMergeRow * 4 ? kStripBytes : QT * 16 * kMergeRow * 4;
+}
+
+struct AttnSplit {
+  int QB;      // query blocks of 16*QT rows
+  int S;       // key splits
+  float* po;   // [unit][16*QT][128] partial O (unnormalised), unit = ((b*H + h)*QB + qb)*S + s
+  float* pm;   // [unit][16*QT] running max (log2 domain)
+  float* pl;   // [unit][16*QT] running sum
+};
+
+template <int QT>
+__global__ __launch_bounds__(64 * kAttnWaves) void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ float m_sh[kAttnWaves][16];
-  __shared__ float l_sh[kAttnWaves][16];
+  __shared__ float m_sh[kAttnWaves][16 * QT];
+  __shared__ float l_sh[kAttnWaves][16 * QT];
+  constexpr int kLdsPerWave = attn_lds_per_wave<QT>();
+  constexpr int ROWS = 16 * QT;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c = lane & 15, g = lane >> 4;
   int bid = blockIdx.x;
   const int h = bid % p.H;
   bid /= p.H;
-  const int qb = bid % QB;
-  const int b = bid / QB;
+  const int split = bid % sp.S;
+  bid /= sp.S;
+  const int qb = bid % sp.QB;
+  const int b = bid / sp.QB;
   int n = p.n_nodes[b];
   n = n < 1 ? 1 : (n > p.max_nodes ? p.max_nodes : n);
-  if (qb * 16 >= n) return;
+  if (qb * ROWS >= n) return;
   int L = p.ctx_len[b];
   L = L < 0 ? 0 : (L > p.kv_cap ? p.kv_cap : L);
 
@@ -169,31 +190,42 @@ __global__ __launch_bounds__(64 * kAttnWaves) void tree_attn_bf16_kernel(AttnPar
   const unsigned char* kt = (const unsigned char*)p.k_tree + node_base * 256;
   const unsigned char* vt = (const unsigned char*)p.v_tree + node_base * 256;
 
-  // this lane's query column: Q fragments (B operand of K.Q^T) and mask words
-  const int qi = qb * 16 + c;
-  const int qrow = qi < p.max_nodes ? qi : p.max_nodes - 1;
-  bf16x8 qf[4];
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
-    qf[kk] = __builtin_bit_cast(
-        bf16x8, *(const u32x4*)((const unsigned char*)p.q + (node_base + qrow) * 256 + kk * 64 + g * 16));
+  // this lane's query columns (one per query tile): Q fragments (B operand of K.Q^T) and mask words
+  bf16x8 qf[QT][4];
+  unsigned long long mw0[QT], mw1[QT];
   const int W = (p.max_nodes + 63) >> 6;
-  unsigned long long mw0 = 0ull, mw1 = 0ull;
-  if (qi < n) {
-    const unsigned long long* mrow = p.anc_mask + ((size_t)b * p.max_nodes + qi) * W;
-    mw0 = mrow[0];
-    if (W > 1) mw1 = mrow[1];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    const int qi = qb * ROWS + qt * 16 + c;
+    const int qrow = qi < p.max_nodes ? qi : p.max_nodes - 1;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      qf[qt][kk] = __builtin_bit_cast(
+          bf16x8, *(const u32x4*)((const unsigned char*)p.q + (node_base + qrow) * 256 + kk * 64 + g * 16));
+    mw0[qt] = 0ull;
+    mw1[qt] = 0ull;
+    if (qi < n) {
+      const unsigned long long* mrow = p.anc_mask + ((size_t)b * p.max_nodes + qi) * W;
+      mw0[qt] = mrow[0];
+      if (W > 1) mw1[qt] = mrow[1];
+    }
   }
 
   const int ctxT = (L + kTileKeys - 1) / kTileKeys, treeT = (n + kTileKeys - 1) / kTileKeys;
   const int NTL = ctxT + treeT;
+  const int tstep = kAttnWaves * sp.S;
   const float sl2 = p.scale * 1.4426950408889634f;
-  unsigned char* strip = smem + wave * kAttnLdsPerWave;
+  unsigned char* strip = smem + wave * kLdsPerWave;
 
-  f32x4 o[8];
+  f32x4 o[QT][8];
+  float m_run[QT], l_run[QT];
 #pragma unroll
-  for (int db = 0; db < 8; ++db) o[db] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.f;
+  for (int qt = 0; qt < QT; ++qt) {
+    m_run[qt] = -INFINITY;
+    l_run[qt] = 0.f;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) o[qt][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
 
   u32x4 kr[8], vr[8];
   // tile t: rows [row0, row0+32) of `src`, rows >= limit do not exist (clamped for loads, masked later)
@@ -220,64 +252,76 @@ __global__ __launch_bounds__(64 * kAttnWaves) void tree_attn_bf16_kernel(AttnPar
     }
   };
 
-  int t = wave;
+  int t = split * kAttnWaves + wave;
   if (t < NTL) {
     issue_k(t);
     issue_v(t);
   }
-  for (; t < NTL; t += kAttnWaves) {
+  for (; t < NTL; t += tstep) {
     const bool tree = t >= ctxT;
     const int row0 = (tree ? t - ctxT : t) * kTileKeys;
     // K tile -> private strip (row = key, 272-byte pitch), then the next tile's K loads
 #pragma unroll
     for (int j = 0; j < 8; ++j) *(u32x4*)(strip + (4 * j + g) * kStripRow + c * 16) = kr[j];
-    const int tn = t + kAttnWaves;
+    const int tn = t + tstep;
     if (tn < NTL) issue_k(tn);
-    // S^T = K.Q^T for the two blocks of 16 keys
-    f32x4 s[2];
+    // S^T = K.Q^T for the two blocks of 16 keys, all query tiles
+    f32x4 s[QT][2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      s[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(strip + (kb * 16 + c) * kStripRow + kk * 64 + g * 16));
-        s[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[kk], s[kb], 0, 0, 0);
-      }
+    for (int qt = 0; qt < QT; ++qt) {
+      s[qt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+      s[qt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    // visibility, scaling, running max
-    float sv[8];
-    float mx = -INFINITY;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int key = row0 + kb * 16 + 4 * g + i;
-        bool vis;
-        if (tree) vis = (((key < 64 ? mw0 : mw1) >> (key & 63)) & 1ull) != 0ull;
-        else vis = key < L;
-        const float x = vis ? s[kb][i] * sl2 : -INFINITY;
-        sv[kb * 4 + i] = x;
-        mx = fmaxf(mx, x);
+      for (int kk = 0; kk < 4; ++kk) {
+        const bf16x8 a =
+            __builtin_bit_cast(bf16x8, *(const u32x4*)(strip + (kb * 16 + c) * kStripRow + kk * 64 + g * 16));
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt)
+          s[qt][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[qt][kk], s[qt][kb], 0, 0, 0);
       }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_safe = m_new > -INFINITY ? m_new : 0.f;
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-    float psum = 0.f;
-    bf16x8 ph, pl;
+    // visibility, scaling, online softmax per query tile
+    bf16x8 ph[QT], pl[QT];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const float pj = __builtin_amdgcn_exp2f(sv[j] - m_safe);
-      psum += pj;
-      const __bf16 hi = (__bf16)pj;
-      ph[j] = hi;
-      pl[j] = (__bf16)(pj - (float)hi);
+    for (int qt = 0; qt < QT; ++qt) {
+      float sv[8];
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int key = row0 + kb * 16 + 4 * g + i;
+          bool vis;
+          if (tree) vis = (((key < 64 ? mw0[qt] : mw1[qt]) >> (key & 63)) & 1ull) != 0ull;
+          else vis = key < L;
+          const float x = vis ? s[qt][kb][i] * sl2 : -INFINITY;
+          sv[kb * 4 + i] = x;
+          mx = fmaxf(mx, x);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run[qt], mx);
+      const float m_safe = m_new > -INFINITY ? m_new : 0.f;
+      float psum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float pj = __builtin_amdgcn_exp2f(sv[j] - m_safe);
+        psum += pj;
+        const __bf16 hi = (__bf16)pj;
+        ph[qt][j] = hi;
+        pl[qt][j] = (__bf16)(pj - (float)hi);
+      }
+      if (m_new != m_run[qt]) {  // rescaling is needed only when the running max moved
+        const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_safe);
+        l_run[qt] *= alpha;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) o[qt][db] *= alpha;
+        m_run[qt] = m_new;
+      }
+      l_run[qt] += psum;
     }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int db = 0; db < 8; ++db) o[db] *= alpha;
     // O^T += V^T.P; the A operand of output block db is column db of this lane's 8x8 V block
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
@@ -288,35 +332,44 @@ __global__ __launch_bounds__(64 * kAttnWaves) void tree_attn_bf16_kernel(AttnPar
         a4[jp] = __builtin_amdgcn_perm(y, x, (db & 1) ? 0x07060302u : 0x05040100u);
       }
       const bf16x8 a = __builtin_bit_cast(bf16x8, a4);
-      o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ph, o[db], 0, 0, 0);
-      o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl, o[db], 0, 0, 0);
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) {
+        o[qt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ph[qt], o[qt][db], 0, 0, 0);
+        o[qt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl[qt], o[qt][db], 0, 0, 0);
+      }
     }
     if (tn < NTL) issue_v(tn);
   }
 
   // ---- merge the wavefronts' partial results --------------------------------------------------
-  l_run += __shfl_xor(l_run, 16, 64);
-  l_run += __shfl_xor(l_run, 32, 64);
-  if (g == 0) {
-    m_sh[wave][c] = m_run;
-    l_sh[wave][c] = l_run;
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    l_run[qt] += __shfl_xor(l_run[qt], 16, 64);
+    l_run[qt] += __shfl_xor(l_run[qt], 32, 64);
+    if (g == 0) {
+      m_sh[wave][qt * 16 + c] = m_run[qt];
+      l_sh[wave][qt * 16 + c] = l_run[qt];
+    }
   }
   __syncthreads();  // also: every wavefront is done with its strip, which the merge buffer reuses
-  float* ob = (float*)(smem + wave * kAttnLdsPerWave);
+  float* ob = (float*)(smem + wave * kLdsPerWave);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    // lane (c, g) holds O[q = c][dh = 32g + 8i + db], db = 0..7
-    f32x4 lo4 = {o[0][i], o[1][i], o[2][i], o[3][i]};
-    f32x4 hi4 = {o[4][i], o[5][i], o[6][i], o[7][i]};
-    *(f32x4*)(ob + c * kMergeRow + 32 * g + 8 * i) = lo4;
-    *(f32x4*)(ob + c * kMergeRow + 32 * g + 8 * i + 4) = hi4;
-  }
+  for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      // lane (c, g) holds O[q = 16*qt + c][dh = 32g + 8i + db], db = 0..7
+      f32x4 lo4 = {o[qt][0][i], o[qt][1][i], o[qt][2][i], o[qt][3][i]};
+      f32x4 hi4 = {o[qt][4][i], o[qt][5][i], o[qt][6][i], o[qt][7][i]};
+      *(f32x4*)(ob + (qt * 16 + c) * kMergeRow + 32 * g + 8 * i) = lo4;
+      *(f32x4*)(ob + (qt * 16 + c) * kMergeRow + 32 * g + 8 * i + 4) = hi4;
+    }
   __syncthreads();
-  constexpr int kRowsPerWave = 16 / kAttnWaves;
+  constexpr int kRowsPerWave = ROWS / kAttnWaves;
+  const size_t unit = (((size_t)b * p.H + h) * sp.QB + qb) * sp.S + split;
 #pragma unroll
   for (int rr = 0; rr < kRowsPerWave; ++rr) {
     const int qr = wave * kRowsPerWave + rr;
-    const int qg = qb * 16 + qr;
+    const int qg = qb * ROWS + qr;
     if (qg >= n) continue;
     float M = -INFINITY;
 #pragma unroll
@@ -326,16 +379,73 @@ __global__ __launch_bounds__(64 * kAttnWaves) void tree_attn_bf16_kernel(AttnPar
     for (int w = 0; w < kAttnWaves; ++w) {
       const float mw = m_sh[w][qr];
       const float f = mw > -INFINITY ? __builtin_amdgcn_exp2f(mw - M) : 0.f;
-      const float* src = (const float*)(smem + w * kAttnLdsPerWave) + qr * kMergeRow;
+      const float* src = (const float*)(smem + w * kLdsPerWave) + qr * kMergeRow;
       Lt += f * l_sh[w][qr];
       a0 += f * src[lane];
       a1 += f * src[lane + 64];
     }
-    const float inv = 1.0f / Lt;
-    float* dst = p.out + (node_base + qg) * 128;
-    dst[lane] = a0 * inv;
-    dst[lane + 64] = a1 * inv;
+    if (sp.S == 1) {
+      const float inv = 1.0f / Lt;
+      float* dst = p.out + (node_base + qg) * 128;
+      dst[lane] = a0 * inv;
+      dst[lane + 64] = a1 * inv;
+    } else {
+      float* dst = sp.po + (unit * ROWS + qr) * 128;
+      dst[lane] = a0;
+      dst[lane + 64] = a1;
+      if (lane == 0) {
+        sp.pm[unit * ROWS + qr] = M;
+        sp.pl[unit * ROWS + qr] = Lt;
+      }
+    }
   }
+}
+
+// Combine the S key-split partials of every live query row: one wavefront per row.
+__global__ __launch_bounds__(64) void tree_attn_merge_kernel(AttnParams p, AttnSplit sp, int rows_per_block) {
+  const int lane = threadIdx.x;
+  const int row = blockIdx.x % p.max_nodes;
+  const int bh = blockIdx.x / p.max_nodes;
+  const int b = bh / p.H;
+  int n = p.n_nodes[b];
+  n = n < 1 ? 1 : (n > p.max_nodes ? p.max_nodes : n);
+  if (row >= n) return;
+  const int qb = row / rows_per_block, qr = row % rows_per_block;
+  const size_t unit0 = ((size_t)bh * sp.QB + qb) * sp.S;
+  float M = -INFINITY;
+  for (int s = 0; s < sp.S; ++s) M = fmaxf(M, sp.pm[(unit0 + s) * rows_per_block + qr]);
+  float Lt = 0.f, a0 = 0.f, a1 = 0.f;
+  for (int s = 0; s < sp.S; ++s) {
+    const size_t r = (unit0 + s) * rows_per_block + qr;
+    const float ms = sp.pm[r];
+    const float f = ms > -INFINITY ? __builtin_amdgcn_exp2f(ms - M) : 0.f;
+    Lt += f * sp.pl[r];
+    a0 += f * sp.po[r * 128 + lane];
+    a1 += f * sp.po[r * 128 + lane + 64];
+  }
+  const float inv = 1.0f / Lt;
+  float* dst = p.out + ((size_t)bh * p.max_nodes + row) * 128;
+  dst[lane] = a0 * inv;
+  dst[lane + 64] = a1 * inv;
+}
+
+template <int QT>
+static hipError_t launch_attn_bf16(const AttnParams& p, const AttnSplit& sp, hipStream_t stream) {
+  auto kern = tree_attn_bf16_kernel<QT>;
+  const int lds = kAttnWaves * attn_lds_per_wave<QT>();
+  static bool lds_allowed = false;
+  if (!lds_allowed) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    lds_allowed = true;
+  }
+  const long long blocks = (long long)sp.QB * sp.S * p.H * p.B;
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * kAttnWaves), lds, stream, p, sp);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || sp.S == 1) return e;
+  hipLaunchKernelGGL(tree_attn_merge_kernel, dim3((unsigned)((long long)p.B * p.H * p.max_nodes)), dim3(64), 0,
+                     stream, p, sp, 16 * QT);
+  return hipGetLastError();
 }
 
 }  // namespace ctcspec
@@ -369,18 +479,26 @@ extern "C" int tree_verify_attn(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* 
   p.k_tree = k_tree; p.v_tree = v_tree; p.n_nodes = n_nodes; p.anc_mask = (const unsigned long long*)anc_mask;
   p.B = B; p.H = H; p.dh = dh; p.max_nodes = max_nodes; p.scale = scale; p.out = out;
   if (dt == CTCSPEC_BF16 && dh == 128) {
-    const int QB = (max_nodes + 15) / 16;
-    const long long blocks = (long long)QB * H * B;
-    CTCSPEC_REQUIRE(ctx, blocks <= 0x7fffffffLL, CTCSPEC_EUNSUPPORTED, "tree_verify_attn: grid too large");
-    const int lds = kAttnWaves * kAttnLdsPerWave;
-    static int lds_allowed = 0;
-    if (lds > lds_allowed) {
-      CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)tree_attn_bf16_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-      lds_allowed = lds;
-    }
-    hipLaunchKernelGGL(tree_attn_bf16_kernel, dim3((unsigned)blocks), dim3(64 * kAttnWaves), lds, ctx->stream, p, QB);
-    CTCSPEC_HIP(ctx, hipGetLastError());
+    // Launch shape: QT query tiles of 16 rows per wavefront (K/V are re-read once per block of 16*QT
+    // rows) and S key splits (each leaves a partial result).  Few (sequence, head) pairs: big query
+    // blocks and more splits keep all compute units busy; many pairs: no split at all.
+    const long long bh = (long long)B * H;
+    int qt = 1;
+    if (const char* e = getenv("CTCSPEC_ATTN_QT")) qt = atoi(e) == 1 ? 1 : (atoi(e) == 2 ? 2 : 4);
+    AttnSplit sp;
+    sp.QB = (max_nodes + 16 * qt - 1) / (16 * qt);
+    const int key_tiles = (kv_cap + max_nodes + kTileKeys - 1) / kTileKeys;
+    int S = 1;
+    while (S < kMaxKvSplits && bh * sp.QB * S < 512 && key_tiles / (2 * S * kAttnWaves) >= 2) S *= 2;
+    if (const char* e = getenv("CTCSPEC_ATTN_SPLITS")) S = atoi(e) < 1 ? 1 : (atoi(e) > kMaxKvSplits ? kMaxKvSplits : atoi(e));
+    while (S > 1 && bh * S > ctx->attn_units) S /= 2;
+    sp.S = S;
+    sp.po = ctx->attn_po; sp.pm = ctx->attn_pm; sp.pl = ctx->attn_pl;
+    CTCSPEC_REQUIRE(ctx, bh * sp.QB * S <= 0x7fffffffLL && bh * max_nodes <= 0x7fffffffLL, CTCSPEC_EUNSUPPORTED,
+                    "tree_verify_attn: grid too large");
+    hipError_t e = qt == 1 ? launch_attn_bf16<1>(p, sp, ctx->stream)
+                           : (qt == 2 ? launch_attn_bf16<2>(p, sp, ctx->stream) : launch_attn_bf16<4>(p, sp, ctx->stream));
+    CTCSPEC_HIP(ctx, e);
     return CTCSPEC_OK;
   }
   dim3 grid(max_nodes, H, B);
