@@ -43,6 +43,8 @@ def parse_args():
     ap.add_argument("--graph", action="store_true", help="replay the steps from a captured HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=2)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run ten 256 MiB device copies (known traffic, for scaling rocprofv3 HBM counters)")
     return ap.parse_args()
 
 
@@ -274,6 +276,12 @@ def main():
                      "traffic": read_traffic_summary(), "algorithmic_bytes_per_launch": head_b,
                      "launch_us": head_us},
     }
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, x, args.cpu_steps)
     print(json.dumps(result))
