@@ -15,7 +15,7 @@ SOURCES = ["context.hip", "draft_topk.hip", "collapse_tree.hip", "tree_attn.hip"
 LIB = os.path.join(HERE, "libctcspec.so")
 
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    "-O3", "-std=c++20", "--offload-arch=gfx950", "-fPIC", "-shared",
     # keep the compiler from emitting packed fp32 VALU ops
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument",

@@ -100,6 +100,11 @@ __device__ __forceinline__ unsigned int rank_key_index(unsigned long long key) {
   return 0xffffffffu - (unsigned int)(key & 0xffffffffu);
 }
 
+// Workgroup barrier for data exchanged through LDS only.  __syncthreads() also waits for every
+// outstanding global load (vmcnt(0)), which would drain a register prefetch pipeline at each barrier;
+// this one waits for the wavefront's own LDS operations and then joins the barrier.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // ---- wavefront reductions ------------------------------------------------------------------------
 // Inside each row of 16 lanes the partial results travel by DPP row rotations (no LDS round trip);
 // the four row results are then combined through v_readlane.  Every lane returns the full result.

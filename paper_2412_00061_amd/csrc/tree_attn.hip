@@ -7,6 +7,9 @@
 //                                (node, head, sequence), keys in chunks with an online softmax
 #include <stdlib.h>
 
+#include <type_traits>
+#include <utility>
+
 #include "common.h"
 
 namespace ctcspec {
@@ -121,54 +124,49 @@ __global__ __launch_bounds__(kGenericThreads) void tree_attn_generic_kernel(Attn
 
 
 // ---- bf16, dh = 128 -------------------------------------------------------------------------------
-// Workgroup = kAttnWaves wavefronts = one block of 16*QT query nodes of one (sequence, head) and one
-// of S splits of the keys.  The keys (cached context rows first, then the tree nodes) are cut into
-// tiles of 32; the 4*S wavefronts that share a query block take the tiles round robin, each running
-// its own online softmax; a workgroup's wavefronts are merged through LDS at the end.  With S == 1
-// that is the result; otherwise the workgroup leaves an unnormalised partial (O, max, sum) in the
-// context workspace and tree_attn_merge_kernel combines the S partials.
+// Workgroup = NW wavefronts = one block of 16*QT*NW query nodes of one (sequence, head) and one of S
+// splits of the keys; wavefront w owns query rows [16*QT*w, 16*QT*(w+1)) of the block.  The keys
+// (cached context rows first, then the tree nodes) are cut into tiles of 32; split s takes tiles s,
+// s+S, ...  A tile (K and V, 16 KB) is fetched ONCE per workgroup by all threads together (one or two
+// 16-byte loads of K and of V per thread, PF tiles ahead in registers), put into one of two LDS
+// stages and used by every wavefront.  With S == 1 the workgroup writes the result; otherwise it
+// leaves an unnormalised partial (O, max, sum) per row in the context workspace and
+// tree_attn_merge_kernel combines the S partials.
+//
+// LDS tile layout: 32 rows (keys) of 256 bytes, 16-byte slot = chunk ^ (row & 15).  Both access
+// patterns - 16 lanes reading the same chunk of 16 different rows (K as MFMA A operand) and 16 lanes
+// reading the 16 chunks of one row (V) - then touch 16 different slots: conflict-free without padding.
 //
 // Per tile and wavefront:
-//   S^T[key, q] = K.Q^T   : A = K rows (staged through a private LDS strip to get from coalesced
-//                           256-byte row reads to the MFMA A layout), B = Q^T (resident in VGPRs);
-//                           every K fragment is used for all QT query tiles
-//   P = exp2(S^T*c - m)   : in the MFMA C layout a lane holds 8 keys of ONE query column, so the
+//   S^T[key, q] = K.Q^T   : A = K rows from LDS, B = Q^T resident in VGPRs; every K fragment is used
+//                           for all QT query tiles
+//   P = exp2((S^T - m)*c) : in the MFMA C layout a lane holds 8 keys of ONE query column, so the
 //                           running max/sum are per lane plus a 4-lane exchange
 //   O^T[dh, q] += V^T.P   : P stays in registers as the B operand (hi + lo bf16 halves, so that P
-//                           carries 16 mantissa bits); V is read straight from global memory, 16
-//                           bytes (8 consecutive dh of one key) per lane and load, and an 8x8 16-bit
-//                           transpose inside the lane turns that into A operands, shared by the QT
-//                           query tiles.  MFMA row r of output block db stands for dh = 8*r + db,
-//                           which makes every V load a contiguous 16 bytes; the permutation is
-//                           undone when O is written.
-// K/V are re-read once per query block; workgroups of the same (sequence, head) are given block
-// indices congruent modulo 8, i.e. the same XCD, so those re-reads are served by that XCD's L2.
-constexpr int kAttnWaves = 4;
+//                           carries 16 mantissa bits); a lane reads 16 bytes (8 consecutive dh of one
+//                           key) of V per key slot and an 8x8 16-bit transpose inside the lane turns
+//                           that into A operands, shared by the QT query tiles.  MFMA row r of output
+//                           block db stands for dh = 8*r + db; the permutation is undone when O is
+//                           written.
 constexpr int kTileKeys = 32;
-constexpr int kStripRow = 256 + 16;                    // bytes per staged K row
-constexpr int kStripBytes = kTileKeys * kStripRow;     // per wavefront
-constexpr int kMergeRow = 128 + 4;                     // floats per query row in the merge buffer
-
-template <int QT>
-constexpr int attn_lds_per_wave() {
-  return kStripBytes > QT * 16 * kMergeRow * 4 ? kStripBytes : QT * 16 * kMergeRow * 4;
-}
+constexpr int kTileBytes = kTileKeys * 256;        // K or V of one tile
+constexpr int kStageBytes = 2 * kTileBytes;        // K then V
+constexpr int kAttnLdsBytes = 2 * kStageBytes;     // two stages
 
 struct AttnSplit {
-  int QB;      // query blocks of 16*QT rows
+  int QB;      // query blocks of 16*QT*NW rows
   int S;       // key splits
-  float* po;   // [unit][16*QT][128] partial O (unnormalised), unit = ((b*H + h)*QB + qb)*S + s
-  float* pm;   // [unit][16*QT] running max (log2 domain)
-  float* pl;   // [unit][16*QT] running sum
+  float* po;   // [unit][rows][128] partial O (unnormalised), unit = ((b*H + h)*QB + qb)*S + s
+  float* pm;   // [unit][rows] softmax reference, scaled to the log2 domain
+  float* pl;   // [unit][rows] running sum
 };
 
-template <int QT>
-__global__ __launch_bounds__(64 * kAttnWaves) void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
+template <int QT, int NW, int PF>
+__global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ float m_sh[kAttnWaves][16 * QT];
-  __shared__ float l_sh[kAttnWaves][16 * QT];
-  constexpr int kLdsPerWave = attn_lds_per_wave<QT>();
-  constexpr int ROWS = 16 * QT;
+  constexpr int ROWS = 16 * QT * NW;
+  constexpr int kThreadsA = 64 * NW;
+  constexpr int LU = 512 / kThreadsA;  // 16-byte pieces of K (and of V) per thread and tile
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c = lane & 15, g = lane >> 4;
   int bid = blockIdx.x;
@@ -190,13 +188,51 @@ __global__ __launch_bounds__(64 * kAttnWaves) void tree_attn_bf16_kernel(AttnPar
   const unsigned char* kt = (const unsigned char*)p.k_tree + node_base * 256;
   const unsigned char* vt = (const unsigned char*)p.v_tree + node_base * 256;
 
-  // this lane's query columns (one per query tile): Q fragments (B operand of K.Q^T) and mask words
+  const int ctxT = (L + kTileKeys - 1) / kTileKeys, treeT = (n + kTileKeys - 1) / kTileKeys;
+  const int NTL = ctxT + treeT;
+  const int nloc = split < NTL ? (NTL - split + sp.S - 1) / sp.S : 0;  // my tiles: split, split+S, ...
+
+  // ---- tile loader: thread -> (row, chunk) of K and of V, twice ---------------------------------
+  u32x4 ld[PF][2 * LU];
+  auto issue = [&](int j, auto set_tag) __attribute__((always_inline)) {
+    constexpr int SET = decltype(set_tag)::value;
+    // past the last tile the loads are still issued (on the last tile again, an L2 hit): every wait on
+    // an earlier tile can then count on exactly PF-1 younger tiles in flight
+    const int t = split + (j < nloc ? j : nloc - 1) * sp.S;
+    const bool tree = t >= ctxT;
+    const unsigned char* ks = tree ? kt : kc;
+    const unsigned char* vs = tree ? vt : vc;
+    const int row0 = (tree ? t - ctxT : t) * kTileKeys, limit = tree ? n : L;
+#pragma unroll
+    for (int u = 0; u < LU; ++u) {
+      const int q = tid + kThreadsA * u;
+      int row = row0 + (q >> 4);
+      row = row < limit ? row : limit - 1;  // rows past the end re-read the last valid row (masked later)
+      ld[SET][u] = *(const u32x4*)(ks + (size_t)row * 256 + (q & 15) * 16);
+      ld[SET][LU + u] = *(const u32x4*)(vs + (size_t)row * 256 + (q & 15) * 16);
+    }
+  };
+  auto commit = [&](auto set_tag, int stage) __attribute__((always_inline)) {
+    constexpr int SET = decltype(set_tag)::value;
+    unsigned char* base = smem + stage * kStageBytes;
+#pragma unroll
+    for (int u = 0; u < LU; ++u) {
+      const int q = tid + kThreadsA * u;
+      const int row = q >> 4, slot = (q & 15) ^ (row & 15);
+      *(u32x4*)(base + row * 256 + slot * 16) = ld[SET][u];
+      *(u32x4*)(base + kTileBytes + row * 256 + slot * 16) = ld[SET][LU + u];
+    }
+  };
+
+  // ---- this wavefront's query columns: Q fragments (B operand of K.Q^T) and mask words -------------
+  const int qbase = qb * ROWS + wave * 16 * QT;
+  const bool live_wave = qbase < n;
   bf16x8 qf[QT][4];
   unsigned long long mw0[QT], mw1[QT];
   const int W = (p.max_nodes + 63) >> 6;
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
-    const int qi = qb * ROWS + qt * 16 + c;
+    const int qi = qbase + qt * 16 + c;
     const int qrow = qi < p.max_nodes ? qi : p.max_nodes - 1;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
@@ -210,15 +246,10 @@ __global__ __launch_bounds__(64 * kAttnWaves) void tree_attn_bf16_kernel(AttnPar
       if (W > 1) mw1[qt] = mrow[1];
     }
   }
-
-  const int ctxT = (L + kTileKeys - 1) / kTileKeys, treeT = (n + kTileKeys - 1) / kTileKeys;
-  const int NTL = ctxT + treeT;
-  const int tstep = kAttnWaves * sp.S;
   const float sl2 = p.scale * 1.4426950408889634f;
-  unsigned char* strip = smem + wave * kLdsPerWave;
 
   f32x4 o[QT][8];
-  float m_run[QT], l_run[QT];
+  float m_run[QT], l_run[QT];  // m_run: softmax reference in raw (unscaled) score units
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
     m_run[qt] = -INFINITY;
@@ -227,44 +258,13 @@ __global__ __launch_bounds__(64 * kAttnWaves) void tree_attn_bf16_kernel(AttnPar
     for (int db = 0; db < 8; ++db) o[qt][db] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  u32x4 kr[8], vr[8];
-  // tile t: rows [row0, row0+32) of `src`, rows >= limit do not exist (clamped for loads, masked later)
-  auto issue_k = [&](int t) {
-    const bool tree = t >= ctxT;
-    const unsigned char* src = tree ? kt : kc;
-    const int row0 = (tree ? t - ctxT : t) * kTileKeys, limit = tree ? n : L;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      int row = row0 + 4 * j + g;
-      row = row < limit ? row : limit - 1;
-      kr[j] = *(const u32x4*)(src + (size_t)row * 256 + c * 16);
-    }
-  };
-  auto issue_v = [&](int t) {
-    const bool tree = t >= ctxT;
-    const unsigned char* src = tree ? vt : vc;
-    const int row0 = (tree ? t - ctxT : t) * kTileKeys, limit = tree ? n : L;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      int row = row0 + (j >> 2) * 16 + 4 * g + (j & 3);  // key slot (g, j) of the P.V contraction
-      row = row < limit ? row : limit - 1;
-      vr[j] = *(const u32x4*)(src + (size_t)row * 256 + c * 16);
-    }
-  };
-
-  int t = split * kAttnWaves + wave;
-  if (t < NTL) {
-    issue_k(t);
-    issue_v(t);
-  }
-  for (; t < NTL; t += tstep) {
+  auto compute = [&](int j, int stage) __attribute__((always_inline)) {
+    const int t = split + j * sp.S;
     const bool tree = t >= ctxT;
     const int row0 = (tree ? t - ctxT : t) * kTileKeys;
-    // K tile -> private strip (row = key, 272-byte pitch), then the next tile's K loads
-#pragma unroll
-    for (int j = 0; j < 8; ++j) *(u32x4*)(strip + (4 * j + g) * kStripRow + c * 16) = kr[j];
-    const int tn = t + tstep;
-    if (tn < NTL) issue_k(tn);
+    const bool full = !tree && row0 + kTileKeys <= L;  // every key of the tile is visible to every row
+    const unsigned char* kbase = smem + stage * kStageBytes;
+    const unsigned char* vbase = kbase + kTileBytes;
     // S^T = K.Q^T for the two blocks of 16 keys, all query tiles
     f32x4 s[QT][2];
 #pragma unroll
@@ -276,52 +276,69 @@ __global__ __launch_bounds__(64 * kAttnWaves) void tree_attn_bf16_kernel(AttnPar
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        const bf16x8 a =
-            __builtin_bit_cast(bf16x8, *(const u32x4*)(strip + (kb * 16 + c) * kStripRow + kk * 64 + g * 16));
+        // row kb*16 + c, chunk kk*4 + g; (row & 15) == c
+        const bf16x8 a = __builtin_bit_cast(
+            bf16x8, *(const u32x4*)(kbase + (kb * 16 + c) * 256 + (((kk * 4 + g) ^ c) * 16)));
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt)
           s[qt][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[qt][kk], s[qt][kb], 0, 0, 0);
       }
-    // visibility, scaling, online softmax per query tile
-    bf16x8 ph[QT], pl[QT];
+    // V fragments of the tile: key slot (g, j) -> row (j>>2)*16 + 4g + (j&3), chunk c
+    u32x4 vr[8];
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-      float sv[8];
-      float mx = -INFINITY;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int key = row0 + kb * 16 + 4 * g + i;
-          bool vis;
-          if (tree) vis = (((key < 64 ? mw0[qt] : mw1[qt]) >> (key & 63)) & 1ull) != 0ull;
-          else vis = key < L;
-          const float x = vis ? s[qt][kb][i] * sl2 : -INFINITY;
-          sv[kb * 4 + i] = x;
-          mx = fmaxf(mx, x);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run[qt], mx);
-      const float m_safe = m_new > -INFINITY ? m_new : 0.f;
-      float psum = 0.f;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float pj = __builtin_amdgcn_exp2f(sv[j] - m_safe);
-        psum += pj;
-        const __bf16 hi = (__bf16)pj;
-        ph[qt][j] = hi;
-        pl[qt][j] = (__bf16)(pj - (float)hi);
-      }
-      if (m_new != m_run[qt]) {  // rescaling is needed only when the running max moved
-        const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_safe);
-        l_run[qt] *= alpha;
-#pragma unroll
-        for (int db = 0; db < 8; ++db) o[qt][db] *= alpha;
-        m_run[qt] = m_new;
-      }
-      l_run[qt] += psum;
+    for (int jj = 0; jj < 8; ++jj) {
+      const int row = (jj >> 2) * 16 + 4 * g + (jj & 3);
+      vr[jj] = *(const u32x4*)(vbase + row * 256 + ((c ^ (row & 15)) * 16));
     }
+    // online softmax per query tile
+    bf16x8 ph[QT], pl[QT];
+    auto softmax = [&](auto full_tag) __attribute__((always_inline)) {
+      constexpr bool FULL = decltype(full_tag)::value;
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) {
+        float sv[8];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float x = s[qt][kb][i];
+            if (!FULL) {
+              const int key = row0 + kb * 16 + 4 * g + i;
+              const bool vis_tree = (((key < 64 ? mw0[qt] : mw1[qt]) >> (key & 63)) & 1ull) != 0ull;
+              const bool vis = tree ? vis_tree : key < L;
+              x = vis ? x : -INFINITY;
+            }
+            sv[kb * 4 + i] = x;
+          }
+        float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        // The softmax reference m_run only has to be NEAR the running max: it is moved (and O, l
+        // rescaled) when the tile's max exceeds it by more than 2^8 in the exponent domain, so P stays
+        // below 256 and the rescaling of the accumulators - by far the most expensive part of the
+        // step - happens about once per wavefront instead of once per tile.
+        if ((mx - m_run[qt]) * sl2 > 8.0f) {
+          const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - mx) * sl2);  // 0 on first use
+          l_run[qt] *= alpha;
+#pragma unroll
+          for (int db = 0; db < 8; ++db) o[qt][db] *= alpha;
+          m_run[qt] = mx;
+        }
+        const float ms = (m_run[qt] > -INFINITY ? m_run[qt] : 0.f) * sl2;
+        float psum = 0.f;
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+          const float pj = __builtin_amdgcn_exp2f(fmaf(sv[jj], sl2, -ms));
+          psum += pj;
+          const __bf16 hi = (__bf16)pj;
+          ph[qt][jj] = hi;
+          pl[qt][jj] = (__bf16)(pj - (float)hi);
+        }
+        l_run[qt] += psum;
+      }
+    };
+    if (full) softmax(std::true_type{});
+    else softmax(std::false_type{});
     // O^T += V^T.P; the A operand of output block db is column db of this lane's 8x8 V block
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
@@ -338,64 +355,63 @@ __global__ __launch_bounds__(64 * kAttnWaves) void tree_attn_bf16_kernel(AttnPar
         o[qt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl[qt], o[qt][db], 0, 0, 0);
       }
     }
-    if (tn < NTL) issue_v(tn);
-  }
+  };
 
-  // ---- merge the wavefronts' partial results --------------------------------------------------
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    l_run[qt] += __shfl_xor(l_run[qt], 16, 64);
-    l_run[qt] += __shfl_xor(l_run[qt], 32, 64);
-    if (g == 0) {
-      m_sh[wave][qt * 16 + c] = m_run[qt];
-      l_sh[wave][qt * 16 + c] = l_run[qt];
+  // ---- pipeline: loads PF tiles ahead in registers, LDS write one tile ahead -------------------------
+  auto for_each_set = [&](auto&& fn) __attribute__((always_inline)) {
+    [&]<int... I>(std::integer_sequence<int, I...>) { (fn(std::integral_constant<int, I>{}), ...); }
+    (std::make_integer_sequence<int, PF>{});
+  };
+  if (nloc > 0) {
+    for_each_set([&](auto jj_tag) __attribute__((always_inline)) { issue(decltype(jj_tag)::value, jj_tag); });
+    commit(std::integral_constant<int, 0>{}, 0);
+    lds_barrier();
+    // the trip count is rounded up to a multiple of PF; the surplus iterations only move (already
+    // cached) data - keeping loads, LDS writes and barriers free of conditions is what lets the
+    // waits be exact
+    const int nit = (nloc + PF - 1) / PF * PF;
+    for (int j0 = 0; j0 < nit; j0 += PF) {
+      for_each_set([&](auto jj_tag) __attribute__((always_inline)) {
+        constexpr int JJ = decltype(jj_tag)::value;
+        const int j = j0 + JJ;
+        commit(std::integral_constant<int, (JJ + 1) % PF>{}, (JJ + 1) & 1);
+        issue(j + PF, jj_tag);
+        if (live_wave && j < nloc) compute(j, JJ & 1);
+        lds_barrier();  // not __syncthreads(): the prefetched tiles must stay in flight
+      });
     }
   }
-  __syncthreads();  // also: every wavefront is done with its strip, which the merge buffer reuses
-  float* ob = (float*)(smem + wave * kLdsPerWave);
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      // lane (c, g) holds O[q = 16*qt + c][dh = 32g + 8i + db], db = 0..7
-      f32x4 lo4 = {o[qt][0][i], o[qt][1][i], o[qt][2][i], o[qt][3][i]};
-      f32x4 hi4 = {o[qt][4][i], o[qt][5][i], o[qt][6][i], o[qt][7][i]};
-      *(f32x4*)(ob + (qt * 16 + c) * kMergeRow + 32 * g + 8 * i) = lo4;
-      *(f32x4*)(ob + (qt * 16 + c) * kMergeRow + 32 * g + 8 * i + 4) = hi4;
-    }
-  __syncthreads();
-  constexpr int kRowsPerWave = ROWS / kAttnWaves;
+  if (!live_wave) return;
+
+  // ---- results ------------------------------------------------------------------------------------
   const size_t unit = (((size_t)b * p.H + h) * sp.QB + qb) * sp.S + split;
 #pragma unroll
-  for (int rr = 0; rr < kRowsPerWave; ++rr) {
-    const int qr = wave * kRowsPerWave + rr;
+  for (int qt = 0; qt < QT; ++qt) {
+    float l = l_run[qt];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    const int qr = wave * 16 * QT + qt * 16 + c;  // row inside the block
     const int qg = qb * ROWS + qr;
     if (qg >= n) continue;
-    float M = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < kAttnWaves; ++w) M = fmaxf(M, m_sh[w][qr]);
-    float Lt = 0.f, a0 = 0.f, a1 = 0.f;
-#pragma unroll
-    for (int w = 0; w < kAttnWaves; ++w) {
-      const float mw = m_sh[w][qr];
-      const float f = mw > -INFINITY ? __builtin_amdgcn_exp2f(mw - M) : 0.f;
-      const float* src = (const float*)(smem + w * kLdsPerWave) + qr * kMergeRow;
-      Lt += f * l_sh[w][qr];
-      a0 += f * src[lane];
-      a1 += f * src[lane + 64];
-    }
+    // lane (c, g) holds O[q = c][dh = 32g + 8i + db], db = 0..7
     if (sp.S == 1) {
-      const float inv = 1.0f / Lt;
-      float* dst = p.out + (node_base + qg) * 128;
-      dst[lane] = a0 * inv;
-      dst[lane + 64] = a1 * inv;
+      const float inv = 1.0f / l;
+      float* dst = p.out + (node_base + qg) * 128 + 32 * g;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        *(f32x4*)(dst + 8 * i) = f32x4{o[qt][0][i] * inv, o[qt][1][i] * inv, o[qt][2][i] * inv, o[qt][3][i] * inv};
+        *(f32x4*)(dst + 8 * i + 4) = f32x4{o[qt][4][i] * inv, o[qt][5][i] * inv, o[qt][6][i] * inv, o[qt][7][i] * inv};
+      }
     } else {
-      float* dst = sp.po + (unit * ROWS + qr) * 128;
-      dst[lane] = a0;
-      dst[lane + 64] = a1;
-      if (lane == 0) {
-        sp.pm[unit * ROWS + qr] = M;
-        sp.pl[unit * ROWS + qr] = Lt;
+      float* dst = sp.po + (unit * ROWS + qr) * 128 + 32 * g;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        *(f32x4*)(dst + 8 * i) = f32x4{o[qt][0][i], o[qt][1][i], o[qt][2][i], o[qt][3][i]};
+        *(f32x4*)(dst + 8 * i + 4) = f32x4{o[qt][4][i], o[qt][5][i], o[qt][6][i], o[qt][7][i]};
+      }
+      if (g == 0) {
+        sp.pm[unit * ROWS + qr] = m_run[qt] * sl2;  // -inf stays -inf (scale > 0)
+        sp.pl[unit * ROWS + qr] = l;
       }
     }
   }
@@ -429,22 +445,15 @@ __global__ __launch_bounds__(64) void tree_attn_merge_kernel(AttnParams p, AttnS
   dst[lane + 64] = a1 * inv;
 }
 
-template <int QT>
+template <int QT, int NW, int PF>
 static hipError_t launch_attn_bf16(const AttnParams& p, const AttnSplit& sp, hipStream_t stream) {
-  auto kern = tree_attn_bf16_kernel<QT>;
-  const int lds = kAttnWaves * attn_lds_per_wave<QT>();
-  static bool lds_allowed = false;
-  if (!lds_allowed) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    lds_allowed = true;
-  }
+  auto kern = tree_attn_bf16_kernel<QT, NW, PF>;
   const long long blocks = (long long)sp.QB * sp.S * p.H * p.B;
-  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * kAttnWaves), lds, stream, p, sp);
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * NW), kAttnLdsBytes, stream, p, sp);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || sp.S == 1) return e;
   hipLaunchKernelGGL(tree_attn_merge_kernel, dim3((unsigned)((long long)p.B * p.H * p.max_nodes)), dim3(64), 0,
-                     stream, p, sp, 16 * QT);
+                     stream, p, sp, 16 * QT * NW);
   return hipGetLastError();
 }
 
@@ -479,25 +488,30 @@ extern "C" int tree_verify_attn(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* 
   p.k_tree = k_tree; p.v_tree = v_tree; p.n_nodes = n_nodes; p.anc_mask = (const unsigned long long*)anc_mask;
   p.B = B; p.H = H; p.dh = dh; p.max_nodes = max_nodes; p.scale = scale; p.out = out;
   if (dt == CTCSPEC_BF16 && dh == 128) {
-    // Launch shape: QT query tiles of 16 rows per wavefront (K/V are re-read once per block of 16*QT
-    // rows) and S key splits (each leaves a partial result).  Few (sequence, head) pairs: big query
-    // blocks and more splits keep all compute units busy; many pairs: no split at all.
+    CTCSPEC_REQUIRE(ctx, scale > 0.f, CTCSPEC_EINVAL, "tree_verify_attn: scale must be positive");
+    // Launch shape: blocks of 64 (max_nodes <= 64) or 128 query rows; S key splits chosen so that
+    // about 256 workgroups exist and each still has a few tiles of 32 keys to stream.
     const long long bh = (long long)B * H;
-    int qt = 1;
-    if (const char* e = getenv("CTCSPEC_ATTN_QT")) qt = atoi(e) == 1 ? 1 : (atoi(e) == 2 ? 2 : 4);
+    int rows = max_nodes > 64 ? 128 : 64;  // query rows per workgroup: 8 or 4 wavefronts of 16
+    int pf = 4;
+    if (const char* e = getenv("CTCSPEC_ATTN_ROWS")) rows = atoi(e) == 64 ? 64 : 128;
+    if (const char* e = getenv("CTCSPEC_ATTN_PF")) pf = atoi(e);
     AttnSplit sp;
-    sp.QB = (max_nodes + 16 * qt - 1) / (16 * qt);
+    sp.QB = (max_nodes + rows - 1) / rows;
     const int key_tiles = (kv_cap + max_nodes + kTileKeys - 1) / kTileKeys;
-    int S = 1;
-    while (S < kMaxKvSplits && bh * sp.QB * S < 512 && key_tiles / (2 * S * kAttnWaves) >= 2) S *= 2;
-    if (const char* e = getenv("CTCSPEC_ATTN_SPLITS")) S = atoi(e) < 1 ? 1 : (atoi(e) > kMaxKvSplits ? kMaxKvSplits : atoi(e));
-    while (S > 1 && bh * S > ctx->attn_units) S /= 2;
-    sp.S = S;
+    long long S = 256 / (bh * sp.QB);
+    if (S > key_tiles / 4) S = key_tiles / 4;
+    if (S > kMaxKvSplits) S = kMaxKvSplits;
+    if (const char* e = getenv("CTCSPEC_ATTN_SPLITS")) S = atoi(e);
+    while (S > 1 && bh * sp.QB * S * rows > (long long)ctx->attn_units * ((ctx->lim.max_nodes + 63) / 64 * 64)) --S;
+    if (S < 1) S = 1;
+    sp.S = (int)S;
     sp.po = ctx->attn_po; sp.pm = ctx->attn_pm; sp.pl = ctx->attn_pl;
     CTCSPEC_REQUIRE(ctx, bh * sp.QB * S <= 0x7fffffffLL && bh * max_nodes <= 0x7fffffffLL, CTCSPEC_EUNSUPPORTED,
                     "tree_verify_attn: grid too large");
-    hipError_t e = qt == 1 ? launch_attn_bf16<1>(p, sp, ctx->stream)
-                           : (qt == 2 ? launch_attn_bf16<2>(p, sp, ctx->stream) : launch_attn_bf16<4>(p, sp, ctx->stream));
+    hipError_t e;
+    if (rows == 64) e = pf == 2 ? launch_attn_bf16<1, 4, 2>(p, sp, ctx->stream) : (pf == 3 ? launch_attn_bf16<1, 4, 3>(p, sp, ctx->stream) : launch_attn_bf16<1, 4, 4>(p, sp, ctx->stream));
+    else e = pf == 2 ? launch_attn_bf16<1, 8, 2>(p, sp, ctx->stream) : (pf == 3 ? launch_attn_bf16<1, 8, 3>(p, sp, ctx->stream) : launch_attn_bf16<1, 8, 4>(p, sp, ctx->stream));
     CTCSPEC_HIP(ctx, e);
     return CTCSPEC_OK;
   }
