@@ -42,7 +42,7 @@ enum {
   CTCSPEC_EHIP = -3          /* the HIP runtime reported a failure */
 };
 
-/* Compiled limits (also returned by ctcspec_query_limit). */
+/* Compiled limits. */
 #define CTCSPEC_MAX_SLOTS 8        /* T */
 #define CTCSPEC_MAX_TOPK 8         /* k */
 #define CTCSPEC_MAX_ALIGNMENTS 65536 /* k^T */
@@ -80,6 +80,14 @@ const char* ctcspec_last_error(const ctcspec_ctx* ctx);
 
 /* Bytes of device workspace the context holds. */
 size_t ctcspec_workspace_bytes(const ctcspec_ctx* ctx);
+
+/* Measurement aid.  With enable != 0, every following ctc_draft_topk call records a pair of HIP events
+ * on the context's stream directly around its main kernel (the pass over the head weights, not the
+ * small merge kernel).  ctcspec_draft_head_kernel_ms synchronises with the second event of the LAST
+ * such call and returns the elapsed milliseconds in *ms (host pointer).  CTCSPEC_EINVAL when profiling
+ * is off or no call has been made since it was switched on. */
+int ctcspec_profile_draft_head(ctcspec_ctx* ctx, int enable);
+int ctcspec_draft_head_kernel_ms(ctcspec_ctx* ctx, float* ms);
 
 /*
  * Stage 1+2 - draft head.  For every draft slot, project its hidden state through the LM head of

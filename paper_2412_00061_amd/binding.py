@@ -14,7 +14,7 @@ _LIB = None
 
 EXPORTS = (
     "ctcspec_create", "ctcspec_destroy", "ctcspec_set_stream", "ctcspec_last_error",
-    "ctcspec_workspace_bytes", "ctc_draft_topk", "ctc_collapse_tree", "tree_verify_attn",
+    "ctcspec_workspace_bytes", "ctcspec_profile_draft_head", "ctcspec_draft_head_kernel_ms", "ctc_draft_topk", "ctc_collapse_tree", "tree_verify_attn",
     "accept_longest",
 )
 
@@ -55,6 +55,10 @@ def load_library():
     lib.ctcspec_last_error.argtypes = [c_void_p]
     lib.ctcspec_workspace_bytes.restype = c_size_t
     lib.ctcspec_workspace_bytes.argtypes = [c_void_p]
+    lib.ctcspec_profile_draft_head.restype = c_int
+    lib.ctcspec_profile_draft_head.argtypes = [c_void_p, c_int]
+    lib.ctcspec_draft_head_kernel_ms.restype = c_int
+    lib.ctcspec_draft_head_kernel_ms.argtypes = [c_void_p, POINTER(c_float)]
     lib.ctc_draft_topk.restype = c_int
     lib.ctc_draft_topk.argtypes = [c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int,
                                    c_int, c_int, c_void_p, c_void_p, c_void_p, c_void_p]
@@ -117,6 +121,14 @@ class Context:
 
     def workspace_bytes(self) -> int:
         return int(self.lib.ctcspec_workspace_bytes(self.handle))
+
+    def profile_draft_head(self, enable: bool):
+        self._check(self.lib.ctcspec_profile_draft_head(self.handle, 1 if enable else 0), "ctcspec_profile_draft_head")
+
+    def draft_head_kernel_ms(self) -> float:
+        ms = c_float()
+        self._check(self.lib.ctcspec_draft_head_kernel_ms(self.handle, ctypes.byref(ms)), "ctcspec_draft_head_kernel_ms")
+        return float(ms.value)
 
     def last_error(self) -> str:
         return self.lib.ctcspec_last_error(self.handle).decode()

@@ -43,6 +43,10 @@ struct ctcspec_ctx {
   float* lm_pmax;               // [lm_max_blocks][kMaxCols]
   float* lm_psum;               // [lm_max_blocks][kMaxCols]
   unsigned long long* lm_pkey;  // [lm_max_blocks][kMaxCols][kMaxTopk]
+  // optional timing of the draft-head kernel
+  int lm_profile;               // events are recorded around the main kernel when non-zero
+  int lm_profile_valid;
+  hipEvent_t lm_ev0, lm_ev1;
   // collapse / tree
   unsigned char* collapse_ws;   // [max_batch][kCollapseWsBytesPerSeq]
   // attention

@@ -93,8 +93,31 @@ extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec
   return CTCSPEC_OK;
 }
 
+extern "C" int ctcspec_profile_draft_head(ctcspec_ctx* ctx, int enable) {
+  if (!ctx) return CTCSPEC_EINVAL;
+  if (enable && !ctx->lm_ev0) {
+    CTCSPEC_HIP(ctx, hipEventCreate(&ctx->lm_ev0));
+    CTCSPEC_HIP(ctx, hipEventCreate(&ctx->lm_ev1));
+  }
+  ctx->lm_profile = enable ? 1 : 0;
+  ctx->lm_profile_valid = 0;
+  return CTCSPEC_OK;
+}
+
+extern "C" int ctcspec_draft_head_kernel_ms(ctcspec_ctx* ctx, float* ms) {
+  if (!ctx) return CTCSPEC_EINVAL;
+  CTCSPEC_REQUIRE(ctx, ms, CTCSPEC_EINVAL, "ctcspec_draft_head_kernel_ms: null pointer");
+  CTCSPEC_REQUIRE(ctx, ctx->lm_profile && ctx->lm_profile_valid, CTCSPEC_EINVAL,
+                  "ctcspec_draft_head_kernel_ms: profiling is off or no call was recorded");
+  CTCSPEC_HIP(ctx, hipEventSynchronize(ctx->lm_ev1));
+  CTCSPEC_HIP(ctx, hipEventElapsedTime(ms, ctx->lm_ev0, ctx->lm_ev1));
+  return CTCSPEC_OK;
+}
+
 extern "C" void ctcspec_destroy(ctcspec_ctx* ctx) {
   if (!ctx) return;
+  if (ctx->lm_ev0) (void)hipEventDestroy(ctx->lm_ev0);
+  if (ctx->lm_ev1) (void)hipEventDestroy(ctx->lm_ev1);
   if (ctx->ws) (void)hipFree(ctx->ws);
   delete ctx;
 }

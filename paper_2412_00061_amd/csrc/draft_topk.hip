@@ -379,6 +379,7 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
       int lds = p.hs_bytes + kMfmaWaves * kWStageBytes;
       int nt = (p.BT + 15) / 16;
       hipError_t e;
+      if (ctx->lm_profile) CTCSPEC_HIP(ctx, hipEventRecord(ctx->lm_ev0, ctx->stream));
       if (stages == 4) {
         switch (nt) {
           case 1: e = launch_mfma<1, 4, false>(p, lds, ctx->stream); break;
@@ -402,6 +403,10 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
         }
       }
       CTCSPEC_HIP(ctx, e);
+      if (ctx->lm_profile) {
+        CTCSPEC_HIP(ctx, hipEventRecord(ctx->lm_ev1, ctx->stream));
+        ctx->lm_profile_valid = 1;
+      }
       launch_merge(p, ctx->stream);
       CTCSPEC_HIP(ctx, hipGetLastError());
       return CTCSPEC_OK;
