@@ -2,7 +2,8 @@
 //
 // Two kernels:
 //   * tree_attn_bf16_kernel    - bf16 operands, head dimension 128: MFMA for Q.K^T and P.V, online
-//                                softmax, every wavefront streams its own share of the keys
+//                                softmax, K/V tiles shared by the wavefronts of a workgroup through LDS,
+//                                optional key splits combined by tree_attn_merge_kernel
 //   * tree_attn_generic_kernel - any dtype / head dimension within the limits: one workgroup per
 //                                (node, head, sequence), keys in chunks with an online softmax
 #include <stdlib.h>
@@ -133,25 +134,49 @@ __global__ __launch_bounds__(kGenericThreads) void tree_attn_generic_kernel(Attn
 // leaves an unnormalised partial (O, max, sum) per row in the context workspace and
 // tree_attn_merge_kernel combines the S partials.
 //
-// LDS tile layout: 32 rows (keys) of 256 bytes, 16-byte slot = chunk ^ (row & 15).  Both access
-// patterns - 16 lanes reading the same chunk of 16 different rows (K as MFMA A operand) and 16 lanes
-// reading the 16 chunks of one row (V) - then touch 16 different slots: conflict-free without padding.
+// LDS tile layout: 32 rows (keys) of 256 bytes in 16-byte slots.
+//   K: slot = chunk ^ (row & 15).  16 lanes reading the same chunk of 16 different rows (the MFMA A
+//      operand of K.Q^T: lane = key row, 8 consecutive dh) touch 16 different slots.
+//   V: slot = chunk ^ ((row & 7) << 1).  V is read back with ds_read_b64_tr_b16: 16 lanes fetch 8 bytes
+//      each from 4 rows x 32 bytes and the instruction hands every lane four CONSECUTIVE KEYS of one dh
+//      column - the A operand of O^T += V^T.P - without any shuffling in registers.  With this swizzle
+//      the 8 rows x 2 chunks a half wavefront reads lie in 32 different 8-byte bank pairs.
 //
 // Per tile and wavefront:
 //   S^T[key, q] = K.Q^T   : A = K rows from LDS, B = Q^T resident in VGPRs; every K fragment is used
 //                           for all QT query tiles
 //   P = exp2((S^T - m)*c) : in the MFMA C layout a lane holds 8 keys of ONE query column, so the
-//                           running max/sum are per lane plus a 4-lane exchange
-//   O^T[dh, q] += V^T.P   : P stays in registers as the B operand (hi + lo bf16 halves, so that P
-//                           carries 16 mantissa bits); a lane reads 16 bytes (8 consecutive dh of one
-//                           key) of V per key slot and an 8x8 16-bit transpose inside the lane turns
-//                           that into A operands, shared by the QT query tiles.  MFMA row r of output
-//                           block db stands for dh = 8*r + db; the permutation is undone when O is
-//                           written.
+//                           running max/sum are per lane plus an exchange between the 4 row groups
+//   O^T[dh, q] += V^T.P   : P stays in registers as the B operand, as hi + lo bf16 halves so that it
+//                           carries 16 mantissa bits; MFMA row r of output block db is dh = 16*db + r
 constexpr int kTileKeys = 32;
 constexpr int kTileBytes = kTileKeys * 256;        // K or V of one tile
 constexpr int kStageBytes = 2 * kTileBytes;        // K then V
 constexpr int kAttnLdsBytes = 2 * kStageBytes;     // two stages
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+__device__ __forceinline__ float max3_f32(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+// max / sum over the four lanes l, l^16, l^32, l^48 (the lanes that hold the same query column), by
+// row swaps inside the vector ALU
+__device__ __forceinline__ float max_across_row_groups(float x) {
+  u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float sum_across_row_groups(float x) {
+  u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
 
 struct AttnSplit {
   int QB;      // query blocks of 16*QT*NW rows
@@ -167,7 +192,8 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
   constexpr int ROWS = 16 * QT * NW;
   constexpr int kThreadsA = 64 * NW;
   constexpr int LU = 512 / kThreadsA;  // 16-byte pieces of K (and of V) per thread and tile
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c = lane & 15, g = lane >> 4;
   int bid = blockIdx.x;
   const int h = bid % p.H;
@@ -192,7 +218,7 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
   const int NTL = ctxT + treeT;
   const int nloc = split < NTL ? (NTL - split + sp.S - 1) / sp.S : 0;  // my tiles: split, split+S, ...
 
-  // ---- tile loader: thread -> (row, chunk) of K and of V, twice ---------------------------------
+  // ---- tile loader: thread -> (row, chunk) of K and of V, LU times -----------------------------------
   u32x4 ld[PF][2 * LU];
   auto issue = [&](int j, auto set_tag) __attribute__((always_inline)) {
     constexpr int SET = decltype(set_tag)::value;
@@ -212,17 +238,39 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
       ld[SET][LU + u] = *(const u32x4*)(vs + (size_t)row * 256 + (q & 15) * 16);
     }
   };
+  int coff_k[LU], coff_v[LU];
+#pragma unroll
+  for (int u = 0; u < LU; ++u) {
+    const int q = tid + kThreadsA * u;
+    const int row = q >> 4, chunk = q & 15;
+    coff_k[u] = row * 256 + ((chunk ^ (row & 15)) << 4);
+    coff_v[u] = kTileBytes + row * 256 + ((chunk ^ ((row & 7) << 1)) << 4);
+  }
   auto commit = [&](auto set_tag, int stage) __attribute__((always_inline)) {
     constexpr int SET = decltype(set_tag)::value;
     unsigned char* base = smem + stage * kStageBytes;
 #pragma unroll
     for (int u = 0; u < LU; ++u) {
-      const int q = tid + kThreadsA * u;
-      const int row = q >> 4, slot = (q & 15) ^ (row & 15);
-      *(u32x4*)(base + row * 256 + slot * 16) = ld[SET][u];
-      *(u32x4*)(base + kTileBytes + row * 256 + slot * 16) = ld[SET][LU + u];
+      *(u32x4*)(base + coff_k[u]) = ld[SET][u];
+      *(u32x4*)(base + coff_v[u]) = ld[SET][LU + u];
     }
   };
+
+  // ---- LDS read addresses --------------------------------------------------------------------------
+  // K fragment (kb, kk): row kb*16 + c, chunk kk*4 + g; (row & 15) == c
+  int koff[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) koff[kk] = c * 256 + (((kk * 4 + g) ^ c) << 4);
+  // V, transposing read: lane 16g + s fetches 8 bytes of row kb*16 + 4g + (s >> 2), dh 16db + 4(s & 3)..+3;
+  // the 16 lanes of a row group then hold dh 16db + s, keys kb*16 + 4g .. + 3
+  int toff[8];
+  {
+    const int s4 = c >> 2;
+    const int x7 = ((4 * (g & 1) + s4) << 1) << 4;  // swizzle term of that row, in bytes
+    const int rbase = kTileBytes + (4 * g + s4) * 256 + ((c & 2) ? 16 : 0) + ((c & 1) ? 8 : 0);
+#pragma unroll
+    for (int db = 0; db < 8; ++db) toff[db] = rbase + ((db << 5) ^ x7);
+  }
 
   // ---- this wavefront's query columns: Q fragments (B operand of K.Q^T) and mask words -------------
   const int qbase = qb * ROWS + wave * 16 * QT;
@@ -248,7 +296,7 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
   }
   const float sl2 = p.scale * 1.4426950408889634f;
 
-  f32x4 o[QT][8];
+  f32x4 o[QT][8];              // lane (c, g): O[q = c][dh = 16db + 4g + i]
   float m_run[QT], l_run[QT];  // m_run: softmax reference in raw (unscaled) score units
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
@@ -263,8 +311,7 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
     const bool tree = t >= ctxT;
     const int row0 = (tree ? t - ctxT : t) * kTileKeys;
     const bool full = !tree && row0 + kTileKeys <= L;  // every key of the tile is visible to every row
-    const unsigned char* kbase = smem + stage * kStageBytes;
-    const unsigned char* vbase = kbase + kTileBytes;
+    const int sbase = stage * kStageBytes;  // plain integer offsets: they fold into the instructions' offset fields
     // S^T = K.Q^T for the two blocks of 16 keys, all query tiles
     f32x4 s[QT][2];
 #pragma unroll
@@ -273,88 +320,92 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
       s[qt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        // row kb*16 + c, chunk kk*4 + g; (row & 15) == c
-        const bf16x8 a = __builtin_bit_cast(
-            bf16x8, *(const u32x4*)(kbase + (kb * 16 + c) * 256 + (((kk * 4 + g) ^ c) * 16)));
+      for (int kb = 0; kb < 2; ++kb) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(smem + (koff[kk] + sbase + kb * 4096)));
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt)
           s[qt][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[qt][kk], s[qt][kb], 0, 0, 0);
       }
-    // V fragments of the tile: key slot (g, j) -> row (j>>2)*16 + 4g + (j&3), chunk c
-    u32x4 vr[8];
+    // V^T fragments of the tile, one per output block of 16 dh
+    s16x8 va[8];
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
-      const int row = (jj >> 2) * 16 + 4 * g + (jj & 3);
-      vr[jj] = *(const u32x4*)(vbase + row * 256 + ((c ^ (row & 15)) * 16));
+    for (int db = 0; db < 8; ++db) {
+      const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4*)(smem + (toff[db] + sbase)));
+      const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4*)(smem + (toff[db] + sbase + 4096)));
+      va[db] = s16x8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
     }
     // online softmax per query tile
     bf16x8 ph[QT], pl[QT];
-    auto softmax = [&](auto full_tag) __attribute__((always_inline)) {
-      constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
-      for (int qt = 0; qt < QT; ++qt) {
-        float sv[8];
+    for (int qt = 0; qt < QT; ++qt) {
+      float sv[8];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sv[kb * 4 + i] = s[qt][kb][i];
+      if (!full) {
+        // this lane's 8 keys are bits 4g..4g+3 and 16+4g..16+4g+3 of the tile's 32-bit visibility word
+        const int left = (tree ? n : L) - row0;  // >= 1 keys of the tile exist
+        unsigned int vis = left >= 32 ? 0xffffffffu : ((1u << left) - 1u);
+        if (tree) {
+          const unsigned long long w = row0 < 64 ? mw0[qt] : mw1[qt];
+          vis &= (unsigned int)(w >> (row0 & 63));
+        }
+        vis >>= 4 * g;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            float x = s[qt][kb][i];
-            if (!FULL) {
-              const int key = row0 + kb * 16 + 4 * g + i;
-              const bool vis_tree = (((key < 64 ? mw0[qt] : mw1[qt]) >> (key & 63)) & 1ull) != 0ull;
-              const bool vis = tree ? vis_tree : key < L;
-              x = vis ? x : -INFINITY;
-            }
-            sv[kb * 4 + i] = x;
-          }
-        float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        // The softmax reference m_run only has to be NEAR the running max: it is moved (and O, l
-        // rescaled) when the tile's max exceeds it by more than 2^8 in the exponent domain, so P stays
-        // below 256 and the rescaling of the accumulators - by far the most expensive part of the
-        // step - happens about once per wavefront instead of once per tile.
-        if ((mx - m_run[qt]) * sl2 > 8.0f) {
-          const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - mx) * sl2);  // 0 on first use
-          l_run[qt] *= alpha;
-#pragma unroll
-          for (int db = 0; db < 8; ++db) o[qt][db] *= alpha;
-          m_run[qt] = mx;
-        }
-        const float ms = (m_run[qt] > -INFINITY ? m_run[qt] : 0.f) * sl2;
-        float psum = 0.f;
-#pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
-          const float pj = __builtin_amdgcn_exp2f(fmaf(sv[jj], sl2, -ms));
-          psum += pj;
-          const __bf16 hi = (__bf16)pj;
-          ph[qt][jj] = hi;
-          pl[qt][jj] = (__bf16)(pj - (float)hi);
-        }
-        l_run[qt] += psum;
+          for (int i = 0; i < 4; ++i) sv[kb * 4 + i] = ((vis >> (kb * 16 + i)) & 1u) ? sv[kb * 4 + i] : -INFINITY;
       }
-    };
-    if (full) softmax(std::true_type{});
-    else softmax(std::false_type{});
-    // O^T += V^T.P; the A operand of output block db is column db of this lane's 8x8 V block
+      float mx = max3_f32(max3_f32(sv[0], sv[1], sv[2]), max3_f32(sv[3], sv[4], sv[5]), fmaxf(sv[6], sv[7]));
+      mx = max_across_row_groups(mx);
+      // The softmax reference m_run only has to be NEAR the running max: it is moved (and O, l
+      // rescaled) when the tile's max exceeds it by more than 2^8 in the exponent domain, so P stays
+      // below 256 and the rescaling of the accumulators - by far the most expensive part of the
+      // step - happens about once per wavefront instead of once per tile.
+      if ((mx - m_run[qt]) * sl2 > 8.0f) {
+        const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - mx) * sl2);  // 0 on first use
+        l_run[qt] *= alpha;
 #pragma unroll
-    for (int db = 0; db < 8; ++db) {
-      u32x4 a4;
+        for (int db = 0; db < 8; ++db) o[qt][db] *= alpha;
+        m_run[qt] = mx;
+      }
+      const float ms = (m_run[qt] > -INFINITY ? m_run[qt] : 0.f) * sl2;
+      float psum = 0.f;
+      u32x4 hi4, lo4;
 #pragma unroll
       for (int jp = 0; jp < 4; ++jp) {
-        const unsigned int x = vr[2 * jp][db >> 1], y = vr[2 * jp + 1][db >> 1];
-        a4[jp] = __builtin_amdgcn_perm(y, x, (db & 1) ? 0x07060302u : 0x05040100u);
+        // P = hi + lo: hi is P cut to its upper 16 bits (a bf16 by construction), lo the rounded rest
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(sv[2 * jp], sl2, -ms));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(sv[2 * jp + 1], sl2, -ms));
+        psum += p0 + p1;
+        const unsigned int u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
+        hi4[jp] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);
+        const float r0 = p0 - __uint_as_float(u0 & 0xffff0000u);
+        const float r1 = p1 - __uint_as_float(u1 & 0xffff0000u);
+        const bf16x2 lo = bf16x2{(__bf16)r0, (__bf16)r1};
+        lo4[jp] = __builtin_bit_cast(unsigned int, lo);
       }
-      const bf16x8 a = __builtin_bit_cast(bf16x8, a4);
-#pragma unroll
-      for (int qt = 0; qt < QT; ++qt) {
-        o[qt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ph[qt], o[qt][db], 0, 0, 0);
-        o[qt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl[qt], o[qt][db], 0, 0, 0);
-      }
+      ph[qt] = __builtin_bit_cast(bf16x8, hi4);
+      pl[qt] = __builtin_bit_cast(bf16x8, lo4);
+      l_run[qt] += psum;
     }
+    // O^T += V^T.P: the hi products of all dh blocks first, then the lo products, so that consecutive
+    // MFMAs never wait for each other's accumulator
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt)
+        o[qt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va[db]), ph[qt], o[qt][db], 0, 0, 0);
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt)
+        o[qt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va[db]), pl[qt], o[qt][db], 0, 0, 0);
   };
 
   // ---- pipeline: loads PF tiles ahead in registers, LDS write one tile ahead -------------------------
@@ -387,28 +438,19 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
   const size_t unit = (((size_t)b * p.H + h) * sp.QB + qb) * sp.S + split;
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
-    float l = l_run[qt];
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
+    const float l = sum_across_row_groups(l_run[qt]);
     const int qr = wave * 16 * QT + qt * 16 + c;  // row inside the block
     const int qg = qb * ROWS + qr;
     if (qg >= n) continue;
-    // lane (c, g) holds O[q = c][dh = 32g + 8i + db], db = 0..7
     if (sp.S == 1) {
       const float inv = 1.0f / l;
-      float* dst = p.out + (node_base + qg) * 128 + 32 * g;
+      float* dst = p.out + (node_base + qg) * 128 + 4 * g;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        *(f32x4*)(dst + 8 * i) = f32x4{o[qt][0][i] * inv, o[qt][1][i] * inv, o[qt][2][i] * inv, o[qt][3][i] * inv};
-        *(f32x4*)(dst + 8 * i + 4) = f32x4{o[qt][4][i] * inv, o[qt][5][i] * inv, o[qt][6][i] * inv, o[qt][7][i] * inv};
-      }
+      for (int db = 0; db < 8; ++db) *(f32x4*)(dst + 16 * db) = o[qt][db] * inv;
     } else {
-      float* dst = sp.po + (unit * ROWS + qr) * 128 + 32 * g;
+      float* dst = sp.po + (unit * ROWS + qr) * 128 + 4 * g;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        *(f32x4*)(dst + 8 * i) = f32x4{o[qt][0][i], o[qt][1][i], o[qt][2][i], o[qt][3][i]};
-        *(f32x4*)(dst + 8 * i + 4) = f32x4{o[qt][4][i], o[qt][5][i], o[qt][6][i], o[qt][7][i]};
-      }
+      for (int db = 0; db < 8; ++db) *(f32x4*)(dst + 16 * db) = o[qt][db];
       if (g == 0) {
         sp.pm[unit * ROWS + qr] = m_run[qt] * sl2;  // -inf stays -inf (scale > 0)
         sp.pl[unit * ROWS + qr] = l;
@@ -417,32 +459,47 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
   }
 }
 
-// Combine the S key-split partials of every live query row: one wavefront per row.
-__global__ __launch_bounds__(64) void tree_attn_merge_kernel(AttnParams p, AttnSplit sp, int rows_per_block) {
-  const int lane = threadIdx.x;
-  const int row = blockIdx.x % p.max_nodes;
-  const int bh = blockIdx.x / p.max_nodes;
-  const int b = bh / p.H;
+// Combine the S key-split partials of every live query row.  Thread -> (row, 4 consecutive dh), 32
+// threads per row, 8 rows per workgroup; all of a thread's partials are requested before any is used,
+// so the kernel costs about one memory round trip.  (Letting the split that finishes last do the
+// merge inside the attention kernel was measured: one workgroup per query block then pulls all S
+// partials through a single compute unit, which takes longer than this second launch.)
+constexpr int kMergeThreads = 256;
+__global__ __launch_bounds__(kMergeThreads) void tree_attn_merge_kernel(AttnParams p, AttnSplit sp, int rows_per_block) {
+  const int tid = threadIdx.x;
+  const long long grow = (long long)blockIdx.x * (kMergeThreads / 32) + (tid >> 5);  // (b*H + h)*max_nodes + row
+  const int row = (int)(grow % p.max_nodes);
+  const long long bh = grow / p.max_nodes;
+  if (bh >= (long long)p.B * p.H) return;
+  const int b = (int)(bh / p.H);
   int n = p.n_nodes[b];
   n = n < 1 ? 1 : (n > p.max_nodes ? p.max_nodes : n);
   if (row >= n) return;
   const int qb = row / rows_per_block, qr = row % rows_per_block;
   const size_t unit0 = ((size_t)bh * sp.QB + qb) * sp.S;
-  float M = -INFINITY;
-  for (int s = 0; s < sp.S; ++s) M = fmaxf(M, sp.pm[(unit0 + s) * rows_per_block + qr]);
-  float Lt = 0.f, a0 = 0.f, a1 = 0.f;
-  for (int s = 0; s < sp.S; ++s) {
-    const size_t r = (unit0 + s) * rows_per_block + qr;
-    const float ms = sp.pm[r];
-    const float f = ms > -INFINITY ? __builtin_amdgcn_exp2f(ms - M) : 0.f;
-    Lt += f * sp.pl[r];
-    a0 += f * sp.po[r * 128 + lane];
-    a1 += f * sp.po[r * 128 + lane + 64];
+  const int d4 = (tid & 31) * 4;
+  float pmv[kMaxKvSplits], plv[kMaxKvSplits];
+  f32x4 pov[kMaxKvSplits];
+#pragma unroll
+  for (int s = 0; s < kMaxKvSplits; ++s) {
+    const bool on = s < sp.S;
+    const size_t r = (unit0 + (on ? s : 0)) * rows_per_block + qr;
+    pmv[s] = on ? sp.pm[r] : -INFINITY;
+    plv[s] = sp.pl[r];
+    pov[s] = *(const f32x4*)(sp.po + r * 128 + d4);
   }
-  const float inv = 1.0f / Lt;
-  float* dst = p.out + ((size_t)bh * p.max_nodes + row) * 128;
-  dst[lane] = a0 * inv;
-  dst[lane + 64] = a1 * inv;
+  float M = -INFINITY;
+#pragma unroll
+  for (int s = 0; s < kMaxKvSplits; ++s) M = fmaxf(M, pmv[s]);
+  float Lt = 0.f;
+  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < kMaxKvSplits; ++s) {
+    const float f = pmv[s] > -INFINITY ? __builtin_amdgcn_exp2f(pmv[s] - M) : 0.f;
+    Lt += f * plv[s];
+    acc += pov[s] * f;
+  }
+  *(f32x4*)(p.out + ((size_t)bh * p.max_nodes + row) * 128 + d4) = acc * (1.0f / Lt);
 }
 
 template <int QT, int NW, int PF>
@@ -452,8 +509,10 @@ static hipError_t launch_attn_bf16(const AttnParams& p, const AttnSplit& sp, hip
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * NW), kAttnLdsBytes, stream, p, sp);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || sp.S == 1) return e;
-  hipLaunchKernelGGL(tree_attn_merge_kernel, dim3((unsigned)((long long)p.B * p.H * p.max_nodes)), dim3(64), 0,
-                     stream, p, sp, 16 * QT * NW);
+  const long long rows = (long long)p.B * p.H * p.max_nodes;
+  const long long mblocks = (rows + kMergeThreads / 32 - 1) / (kMergeThreads / 32);
+  hipLaunchKernelGGL(tree_attn_merge_kernel, dim3((unsigned)mblocks), dim3(kMergeThreads), 0, stream, p, sp,
+                     16 * QT * NW);
   return hipGetLastError();
 }
 
@@ -493,7 +552,7 @@ extern "C" int tree_verify_attn(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* 
     // about 256 workgroups exist and each still has a few tiles of 32 keys to stream.
     const long long bh = (long long)B * H;
     int rows = max_nodes > 64 ? 128 : 64;  // query rows per workgroup: 8 or 4 wavefronts of 16
-    int pf = 4;
+    int pf = 2;
     if (const char* e = getenv("CTCSPEC_ATTN_ROWS")) rows = atoi(e) == 64 ? 64 : 128;
     if (const char* e = getenv("CTCSPEC_ATTN_PF")) pf = atoi(e);
     AttnSplit sp;
