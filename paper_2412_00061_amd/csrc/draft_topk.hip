@@ -11,6 +11,9 @@
 //   * lmhead_bf16_mfma_kernel  - bf16 operands, v_mfma_f32_16x16x32_bf16, HBM-streaming design
 //   * lmhead_generic_kernel    - any dtype/shape within the limits, plain fp32 FMA
 // Both hand the block over in LDS to the same epilogue.
+#include <type_traits>
+#include <utility>
+
 #include "common.h"
 
 namespace ctcspec {
@@ -27,6 +30,7 @@ struct LmHeadParams {
   int BT, D, Vp1, k;
   int KC;        // mfma kernel: hidden-state chunk held in LDS (elements)
   int hs_bytes;  // mfma kernel: bytes of the LDS hidden-state region
+  unsigned int hs_magic;  // mfma kernel: ceil(2^32 / (KC / 8)), for index / (KC / 8) by multiplication
   int n_blocks;
   float* pmax;
   float* psum;
@@ -178,17 +182,22 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(LmHeadParams p) {
 // two rows x 512 contiguous bytes), parks them in its private LDS strip and reads them back in the
 // MFMA A-operand layout (lane = row, 8 consecutive k).  Loads run STAGES-1 steps ahead in registers.
 // The hidden states (the B operand) sit in LDS for the whole workgroup.
+//
+// Every global load of the streaming path is issued unconditionally and in a fixed number per step
+// (rows past the vocabulary re-read its last row, the tail of the k loop is peeled instead of
+// guarded): the waits can then name the exact number of younger loads that may stay in flight, and
+// the prefetch pipeline never drains.  A load under a condition makes every later wait a full drain.
 template <int NT, int STAGES, bool CHUNKED>
 __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHeadParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c = lane & 15, g = lane >> 4;
   const int lrow = lane >> 5, lch = lane & 31;
   unsigned char* hs = smem;
   const int HSS = p.KC * 2 + 16;
   unsigned char* wst = smem + p.hs_bytes + wave * kWStageBytes;
   const int row0 = blockIdx.x * kRowsPerBlock + wave * 16;
-  const bool active = row0 < p.Vp1;
 
   const unsigned char* wp[8];
 #pragma unroll
@@ -212,74 +221,105 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHea
   const int nchunks = CHUNKED ? p.D / p.KC : 1;  // !CHUNKED: the host guarantees KC == D
   const int total_steps = p.D / 256;
 
-  // Hidden-state chunk staging: every thread carries up to kHsPieces 16-byte pieces of the chunk
-  // through registers.  The loads of chunk ch+1 are issued before chunk ch is consumed, so only the
-  // very first chunk exposes its latency - and that one is requested before the first W loads.
+  // Hidden-state chunk staging: every thread carries kHsPieces 16-byte pieces of the chunk through
+  // registers (pieces past the end of the chunk repeat its last piece and are not written to LDS).
+  // The loads of chunk ch+1 are issued before chunk ch is consumed, so only the very first chunk
+  // exposes its latency - and that one is requested before the first W loads.
   constexpr int kHsPieces = 12;
   const int per_row = p.KC / 8;  // 16-byte pieces per column
   const int hs_total = p.BT * per_row;
   u32x4 hreg[kHsPieces];
-  auto hs_request = [&](int ch) {
+  int hs_dst[kHsPieces];  // LDS offset of piece u, -1: none
+  size_t hs_src[kHsPieces];
+#pragma unroll
+  for (int u = 0; u < kHsPieces; ++u) {
+    const int idx = tid + u * 64 * kMfmaWaves;
+    const int cl = idx < hs_total ? idx : hs_total - 1;
+    const int m = (int)__umulhi((unsigned)cl, p.hs_magic);  // cl / per_row
+    const int q = cl - m * per_row;
+    hs_dst[u] = idx < hs_total ? m * HSS + q * 16 : -1;
+    hs_src[u] = (size_t)m * p.D * 2 + q * 16;
+  }
+  auto hs_request = [&](int ch) __attribute__((always_inline)) {
     const unsigned char* src = (const unsigned char*)p.hidden + (size_t)ch * p.KC * 2;
 #pragma unroll
-    for (int u = 0; u < kHsPieces; ++u) {
-      const int idx = tid + u * 64 * kMfmaWaves;
-      if (idx < hs_total) {
-        const int m = idx / per_row, q = idx % per_row;
-        hreg[u] = *(const u32x4*)(src + (size_t)m * p.D * 2 + q * 16);
-      }
-    }
+    for (int u = 0; u < kHsPieces; ++u) hreg[u] = *(const u32x4*)(src + hs_src[u]);
   };
-  auto hs_commit = [&]() {
+  auto hs_commit = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int u = 0; u < kHsPieces; ++u) {
-      const int idx = tid + u * 64 * kMfmaWaves;
-      if (idx < hs_total) {
-        const int m = idx / per_row, q = idx % per_row;
-        *(u32x4*)(hs + m * HSS + q * 16) = hreg[u];
+    for (int u = 0; u < kHsPieces; ++u)
+      if (hs_dst[u] >= 0) *(u32x4*)(hs + hs_dst[u]) = hreg[u];
+  };
+
+  u32x4 v[STAGES][8];
+  auto w_request = [&](int step, auto stage_tag) __attribute__((always_inline)) {
+    constexpr int ST = decltype(stage_tag)::value;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[ST][j] = __builtin_nontemporal_load((const u32x4*)(wp[j] + (size_t)step * 512));
+    // keep the scheduler from mixing these loads with those of another step: the waits count loads in
+    // issue order, and a stage whose loads are spread among younger ones can only be waited for late
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // one step: W registers of stage ST -> LDS strip -> A fragments; i = step inside the hidden chunk
+  auto consume = [&](int i, auto stage_tag) __attribute__((always_inline)) {
+    constexpr int ST = decltype(stage_tag)::value;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) *(u32x4*)(wst + (2 * j + lrow) * kWRowStride + lch * 16) = v[ST][j];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(wst + c * kWRowStride + kk * 64 + g * 16));
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        bf16x8 b = __builtin_bit_cast(bf16x8, *(const u32x4*)(hs + bcol[nt] + (i * 256 + kk * 32) * 2));
+        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[nt], 0, 0, 0);
       }
     }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto for_each_stage = [&](auto&& fn) __attribute__((always_inline)) {
+    [&]<int... I>(std::integer_sequence<int, I...>) { (fn(std::integral_constant<int, I>{}), ...); }
+    (std::make_integer_sequence<int, STAGES>{});
   };
 
   hs_request(0);
-  u32x4 v[STAGES][8];
-  if (active) {
-#pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        v[s][j] = __builtin_nontemporal_load((const u32x4*)(wp[j] + (size_t)s * 512));
-  }
+  for_each_stage([&](auto st) __attribute__((always_inline)) {
+    if constexpr (decltype(st)::value < STAGES - 1) w_request(decltype(st)::value, st);
+  });
 
-  for (int ch = 0; ch < nchunks; ++ch) {
-    if (ch > 0) __syncthreads();  // every wave is done reading the previous chunk
+  if constexpr (!CHUNKED) {
     hs_commit();
     __syncthreads();
-    if (CHUNKED && ch + 1 < nchunks) hs_request(ch + 1);
-    if (active) {
+    // blocks of STAGES steps; step i refills, with step i + STAGES - 1, the stage that step i - 1 freed
+    const int nblk = total_steps / STAGES;  // the host guarantees total_steps % STAGES == 0
+    for (int blk = 0; blk + 1 < nblk; ++blk) {
+      for_each_stage([&](auto st) __attribute__((always_inline)) {
+        constexpr int SS = decltype(st)::value;
+        const int i = blk * STAGES + SS;
+        w_request(i + STAGES - 1, std::integral_constant<int, (SS + STAGES - 1) % STAGES>{});
+        consume(i, st);
+      });
+    }
+    // last block: only its first step still has something to prefetch
+    for_each_stage([&](auto st) __attribute__((always_inline)) {
+      constexpr int SS = decltype(st)::value;
+      const int i = (nblk - 1) * STAGES + SS;
+      if constexpr (SS == 0) w_request(i + STAGES - 1, std::integral_constant<int, STAGES - 1>{});
+      consume(i, st);
+    });
+  } else {
+    for (int ch = 0; ch < nchunks; ++ch) {
+      if (ch > 0) __syncthreads();  // every wave is done reading the previous chunk
+      hs_commit();
+      __syncthreads();
+      if (ch + 1 < nchunks) hs_request(ch + 1);
       for (int i0 = 0; i0 < SPC; i0 += STAGES) {
-#pragma unroll
-        for (int ss = 0; ss < STAGES; ++ss) {
-          const int i = i0 + ss;
+        for_each_stage([&](auto st) __attribute__((always_inline)) {
+          constexpr int SS = decltype(st)::value;
+          const int i = i0 + SS;
           const int pf = ch * SPC + i + STAGES - 1;
-          if (pf < total_steps) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-              v[(ss + STAGES - 1) % STAGES][j] =
-                  __builtin_nontemporal_load((const u32x4*)(wp[j] + (size_t)pf * 512));
-          }
-#pragma unroll
-          for (int j = 0; j < 8; ++j) *(u32x4*)(wst + (2 * j + lrow) * kWRowStride + lch * 16) = v[ss][j];
-#pragma unroll
-          for (int kk = 0; kk < 8; ++kk) {
-            bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(wst + c * kWRowStride + kk * 64 + g * 16));
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-              bf16x8 b = __builtin_bit_cast(bf16x8, *(const u32x4*)(hs + bcol[nt] + (i * 256 + kk * 32) * 2));
-              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[nt], 0, 0, 0);
-            }
-          }
-        }
+          if (pf < total_steps) w_request(pf, std::integral_constant<int, (SS + STAGES - 1) % STAGES>{});
+          consume(i, st);
+        });
       }
     }
   }
@@ -358,7 +398,7 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
   LmHeadParams p;
   p.hidden = hidden; p.w = w; p.bias = bias;
   p.BT = B * T; p.D = D; p.Vp1 = Vp1; p.k = k;
-  p.KC = 0; p.hs_bytes = 0;
+  p.KC = 0; p.hs_bytes = 0; p.hs_magic = 0;
   p.n_blocks = (Vp1 + kRowsPerBlock - 1) / kRowsPerBlock;
   p.pmax = ctx->lm_pmax; p.psum = ctx->lm_psum; p.pkey = ctx->lm_pkey;
   p.topk_id = topk_id; p.topk_logp = topk_logp; p.lse = lse; p.logits_out = logits_out;
@@ -376,6 +416,7 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
     if (kc > 0) {
       p.KC = kc;
       p.hs_bytes = p.BT * (2 * kc + 16);
+      p.hs_magic = (unsigned int)((0x100000000ull + (unsigned)(kc / 8) - 1) / (unsigned)(kc / 8));
       int lds = p.hs_bytes + kMfmaWaves * kWStageBytes;
       int nt = (p.BT + 15) / 16;
       hipError_t e;
