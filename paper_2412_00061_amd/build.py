@@ -18,9 +18,6 @@ HIPCC_FLAGS = [
     "-O3", "-std=c++20", "--offload-arch=gfx950", "-fPIC", "-shared",
     # keep the compiler from emitting packed fp32 VALU ops
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    # a one-lane atomic must stay a plain atomic: the wave-aggregating rewrite reads the result back at
-    # once, which would drain the load pipeline of the persistent draft-head kernel
-    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument",
 ]
 

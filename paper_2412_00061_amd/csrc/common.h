@@ -33,7 +33,6 @@ constexpr int kMaxKvSplits = 8;
 struct ctcspec_ctx {
   hipStream_t stream;
   int device;
-  int num_cus;
   ctcspec_limits lim;
   char err[256];
   // one device allocation, carved up below
@@ -44,7 +43,6 @@ struct ctcspec_ctx {
   float* lm_pmax;               // [lm_max_blocks][kMaxCols]
   float* lm_psum;               // [lm_max_blocks][kMaxCols]
   unsigned long long* lm_pkey;  // [lm_max_blocks][kMaxCols][kMaxTopk]
-  unsigned int* lm_unit_counter;  // work counter of the persistent draft-head kernel; zero between calls
   // optional timing of the draft-head kernel
   int lm_profile;               // events are recorded around the main kernel when non-zero
   int lm_profile_valid;

@@ -54,14 +54,7 @@ extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec
     return fail(nullptr, CTCSPEC_EHIP, "hipGetDevice failed: %s", hipGetErrorString(e));
   }
 
-  e = hipDeviceGetAttribute(&ctx->num_cus, hipDeviceAttributeMultiprocessorCount, ctx->device);
-  if (e != hipSuccess || ctx->num_cus <= 0) {
-    delete ctx;
-    return fail(nullptr, CTCSPEC_EHIP, "hipDeviceGetAttribute(MultiprocessorCount) failed: %s", hipGetErrorString(e));
-  }
-  // partial results of the draft head: one slot per workgroup, 128-row blocks or one persistent workgroup per CU
   ctx->lm_max_blocks = (lim->max_vocab_rows + kRowsPerBlock - 1) / kRowsPerBlock;
-  if (ctx->lm_max_blocks < ctx->num_cus) ctx->lm_max_blocks = ctx->num_cus;
   long long bh = (long long)lim->max_batch * lim->max_heads;
   ctx->attn_units = (int)(bh > 256 ? bh : 256);
 
@@ -74,7 +67,6 @@ extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec
   size_t o_pmax = carve((size_t)ctx->lm_max_blocks * kMaxCols * sizeof(float));
   size_t o_psum = carve((size_t)ctx->lm_max_blocks * kMaxCols * sizeof(float));
   size_t o_pkey = carve((size_t)ctx->lm_max_blocks * kMaxCols * kMaxTopk * sizeof(unsigned long long));
-  size_t o_cnt = carve(sizeof(unsigned int));
   size_t o_coll = carve((size_t)lim->max_batch * kCollapseWsBytesPerSeq);
   // attention partials are stored per query block of up to 64 rows: round the row count up
   const size_t attn_rows = (size_t)ctx->attn_units * (((size_t)lim->max_nodes + 63) / 64 * 64);
@@ -92,13 +84,6 @@ extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec
   ctx->lm_pmax = (float*)(base + o_pmax);
   ctx->lm_psum = (float*)(base + o_psum);
   ctx->lm_pkey = (unsigned long long*)(base + o_pkey);
-  ctx->lm_unit_counter = (unsigned int*)(base + o_cnt);
-  e = hipMemset(ctx->lm_unit_counter, 0, sizeof(unsigned int));
-  if (e != hipSuccess) {
-    (void)hipFree(ctx->ws);
-    delete ctx;
-    return fail(nullptr, CTCSPEC_EHIP, "hipMemset of the workspace counter failed: %s", hipGetErrorString(e));
-  }
   ctx->collapse_ws = base + o_coll;
   ctx->attn_po = (float*)(base + o_po);
   ctx->attn_pm = (float*)(base + o_pm);

@@ -11,8 +11,6 @@
 //   * lmhead_bf16_mfma_kernel  - bf16 operands, v_mfma_f32_16x16x32_bf16, HBM-streaming design
 //   * lmhead_generic_kernel    - any dtype/shape within the limits, plain fp32 FMA
 // Both hand the block over in LDS to the same epilogue.
-#include <stdlib.h>
-
 #include <type_traits>
 #include <utility>
 
@@ -41,7 +39,6 @@ struct LmHeadParams {
   float* topk_logp;
   float* lse;
   float* logits_out;
-  unsigned int* unit_counter;  // persistent kernel: next unclaimed dynamic unit; the merge kernel zeroes it
 };
 
 // Sorted (descending) register list of the best keys seen by one lane.
@@ -113,7 +110,6 @@ template <int KMAX>
 __global__ __launch_bounds__(64) void lmhead_merge_kernel(LmHeadParams p) {
   const int m = blockIdx.x, lane = threadIdx.x;
   const int nb = p.n_blocks, k = p.k;
-  if (m == 0 && lane == 0 && p.unit_counter) *p.unit_counter = 0u;  // for the next call on this context
   float m_run = -INFINITY, s_run = 0.f;
   KeyList<KMAX> list;
   list.clear();
@@ -348,195 +344,6 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHea
   lmhead_block_epilogue(p, zbuf);
 }
 
-// ---- bf16 MFMA streaming producer, persistent variant for few columns --------------------------------
-// The chip's XCDs do not draw the same bandwidth from HBM, and a static split of the rows leaves the
-// faster ones idle while the slowest finishes.  Here one workgroup per compute unit stays resident and
-// takes UNITS of 16 vocabulary rows until none is left: the first kStaticOrdinals units of a workgroup
-// are fixed (block, block + grid, ...), the rest come from a device-wide counter.  Inside a unit the 8
-// wavefronts split the hidden dimension (wavefront w streams k in [w*NST*256, (w+1)*NST*256) of the 16
-// rows); their partial sums meet in LDS, and 16 threads per column fold the unit's 16 logits into
-// per-thread running softmax / top-k state, which is reduced once at the end.
-//
-// Claims never block: the counter is bumped at the start of a unit and the value is picked up two
-// units later, long after it has returned (and after every load older than it has been consumed, so
-// reading it costs no wait).  With the three-step register prefetch the id of a unit is needed at most
-// two units before the unit starts; an id claimed during unit j is for ordinal j + 6.
-// A load under a condition inside the unit loop (a bias, a logits dump) would blur the compiler's count
-// of loads in flight and turn the waits into drains, so calls that need either use the other kernel.
-// Every wavefront of a workgroup sees the same sequence of unit ids and leaves the loop at the same
-// ordinal - the first whose id is past the last unit - so all workgroup barriers pair up.
-constexpr int kUnitRing = 8;
-constexpr int kStaticOrdinals = 6;
-constexpr int kRedFloats = 2 * kMfmaWaves * 16 * 16;  // two buffers x 8 partial sums x 16 columns x 16 rows
-
-template <int NST>
-__global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_persistent_kernel(LmHeadParams p) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int STAGES = 4;
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int c = lane & 15, g = lane >> 4;
-  const int lrow = lane >> 5, lch = lane & 31;
-  unsigned char* hs = smem;
-  const int HSS = p.D * 2 + 16;
-  unsigned char* wst = smem + p.hs_bytes + wave * kWStageBytes;
-  float* red = (float*)(smem + p.hs_bytes + kMfmaWaves * kWStageBytes);
-  int* uq = (int*)(red + kRedFloats);
-  const int G = gridDim.x, n_units = (p.Vp1 + 15) >> 4;
-  // unit id of an ordinal: the first kStaticOrdinals are fixed, later ones come out of the ring in LDS
-  auto unit_of = [&](int ord) __attribute__((always_inline)) -> int {
-    if (ord < kStaticOrdinals) return (int)blockIdx.x + ord * G;
-    return __builtin_amdgcn_readfirstlane(uq[ord & (kUnitRing - 1)]);
-  };
-
-  // ---- hidden states -> LDS (the whole hidden dimension, once per workgroup) ---------------------------
-  // requested first, so that they arrive first; the first W steps are requested before they are waited for
-  constexpr int kHsPieces = 12;
-  const int per_row = p.D / 8;
-  const int hs_total = p.BT * per_row;
-  u32x4 hreg[kHsPieces];
-  int hs_dst[kHsPieces];
-#pragma unroll
-  for (int u = 0; u < kHsPieces; ++u) {
-    const int idx = tid + u * 64 * kMfmaWaves;
-    const int cl = idx < hs_total ? idx : hs_total - 1;
-    const int m = (int)__umulhi((unsigned)cl, p.hs_magic);  // cl / per_row
-    const int q = cl - m * per_row;
-    hs_dst[u] = idx < hs_total ? m * HSS + q * 16 : -1;
-    hreg[u] = *(const u32x4*)((const unsigned char*)p.hidden + (size_t)m * p.D * 2 + q * 16);
-  }
-  __builtin_amdgcn_sched_barrier(0);
-
-  const int bcol = (c < p.BT ? c : p.BT - 1) * HSS + g * 16 + wave * NST * 512;
-
-  // ---- prefetch stream: unit ordinal pf_ord, step pf_t inside it ----------------------------------------
-  const unsigned char* wp[8];
-  auto set_pf_unit = [&](int U) __attribute__((always_inline)) {
-    // a unit id past the end (no work left) turns into re-reads of the last row: harmless L2 hits
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      int row = U * 16 + 2 * j + lrow;
-      row = row < p.Vp1 ? row : p.Vp1 - 1;
-      wp[j] = (const unsigned char*)p.w + (size_t)row * p.D * 2 + wave * NST * 512 + lch * 16;
-    }
-  };
-  int pf_ord = 0, pf_t = 0;
-  set_pf_unit(unit_of(0));
-  u32x4 v[STAGES][8];
-  auto w_request = [&](auto stage_tag) __attribute__((always_inline)) {
-    constexpr int ST = decltype(stage_tag)::value;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) v[ST][j] = __builtin_nontemporal_load((const u32x4*)(wp[j] + pf_t * 512));
-    __builtin_amdgcn_sched_barrier(0);  // keep the loads of different steps apart (the waits count them in order)
-    if (++pf_t == NST) {
-      pf_t = 0;
-      ++pf_ord;
-      set_pf_unit(unit_of(pf_ord));
-    }
-  };
-  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-  auto consume = [&](int t, auto stage_tag) __attribute__((always_inline)) {
-    constexpr int ST = decltype(stage_tag)::value;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) *(u32x4*)(wst + (2 * j + lrow) * kWRowStride + lch * 16) = v[ST][j];
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(wst + c * kWRowStride + kk * 64 + g * 16));
-      const bf16x8 b = __builtin_bit_cast(bf16x8, *(const u32x4*)(hs + bcol + (t * 256 + kk * 32) * 2));
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  };
-
-  // running state of thread (column tid >> 4, row lane tid & 15), used by threads < 16 * BT
-  float m_run = -INFINITY, s_run = 0.f;
-  KeyList<kMaxTopk> list;
-  list.clear();
-  const bool folds = tid < 16 * p.BT;
-
-  w_request(std::integral_constant<int, 0>{});
-  w_request(std::integral_constant<int, 1>{});
-  w_request(std::integral_constant<int, 2>{});
-#pragma unroll
-  for (int u = 0; u < kHsPieces; ++u)
-    if (hs_dst[u] >= 0) *(u32x4*)(hs + hs_dst[u]) = hreg[u];
-  __builtin_amdgcn_sched_barrier(0);
-  lds_barrier();  // not __syncthreads(): the W steps stay in flight
-
-  unsigned int pend[2] = {0u, 0u};  // thread 0: counter values drawn by the last two units
-  int cj = 0;
-  // one unit: NST steps on stages FIRST..; returns false when no unit is left
-  auto run_unit = [&](auto first_tag, auto parity_tag) __attribute__((always_inline)) -> bool {
-    constexpr int FIRST = decltype(first_tag)::value, PAR = decltype(parity_tag)::value;
-    const int U = unit_of(cj);
-    if (U >= n_units) return false;
-    if (tid == 0) {
-      // claimed two units ago, for ordinal cj + 4 (the raw counter value is only touched here, when it
-      // has long returned)
-      if (cj >= 2) uq[(cj + 4) & (kUnitRing - 1)] = kStaticOrdinals * G + (int)pend[PAR];
-      pend[PAR] = atomicAdd(p.unit_counter, 1u);  // for ordinal cj + 6
-    }
-    [&]<int... T>(std::integer_sequence<int, T...>) {
-      ((w_request(std::integral_constant<int, (FIRST + T + STAGES - 1) % STAGES>{}),
-        consume(T, std::integral_constant<int, (FIRST + T) % STAGES>{})),
-       ...);
-    }(std::make_integer_sequence<int, NST>{});
-    // partial sums of the 8 k slices -> LDS; buffer PAR (the other one may still be read)
-    float* rbuf = red + PAR * (kRedFloats / 2);
-    *(f32x4*)(rbuf + (wave * 16 + c) * 16 + 4 * g) = acc;
-    acc = f32x4{0.f, 0.f, 0.f, 0.f};
-    lds_barrier();  // not __syncthreads(): the prefetched W steps stay in flight
-    if (folds) {
-      const int col = tid >> 4, row = U * 16 + (tid & 15);
-      float z = 0.f;
-#pragma unroll
-      for (int w = 0; w < kMfmaWaves; ++w) z += rbuf[(w * 16 + col) * 16 + (tid & 15)];
-      if (row < p.Vp1) {  // (no bias, no logits output here: the host sends such calls to the other kernel)
-        const float mn = fmaxf(m_run, z);
-        s_run = s_run * __expf(m_run - mn) + __expf(z - mn);
-        m_run = mn;
-        list.insert(rank_key(z, (unsigned)row));
-      }
-    }
-    ++cj;
-    return true;
-  };
-  for (;;) {
-    if (!run_unit(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{})) break;
-    if (!run_unit(std::integral_constant<int, NST % STAGES>{}, std::integral_constant<int, 1>{})) break;
-  }
-
-  // ---- the workgroup's partial result per column ---------------------------------------------------------
-  __syncthreads();  // strips and reduction buffers are done with; the state area overlaps the strips
-  float* fm = (float*)(smem + p.hs_bytes);                       // [16 * BT]
-  float* fs = fm + 16 * kMaxCols;
-  unsigned long long* fk = (unsigned long long*)(fs + 16 * kMaxCols);  // [16 * BT][kMaxTopk]
-  if (folds) {
-    fm[tid] = m_run;
-    fs[tid] = s_run;
-#pragma unroll
-    for (int r = 0; r < kMaxTopk; ++r) fk[tid * kMaxTopk + r] = list.v[r];
-  }
-  __syncthreads();
-  for (int col = wave; col < p.BT; col += kMfmaWaves) {
-    const bool on = lane < 16;
-    const float m = on ? fm[col * 16 + lane] : -INFINITY;
-    const float sv = on ? fs[col * 16 + lane] : 0.f;
-    KeyList<kMaxTopk> mine;
-#pragma unroll
-    for (int r = 0; r < kMaxTopk; ++r) mine.v[r] = on ? fk[(col * 16 + lane) * kMaxTopk + r] : 0ull;
-    const float mx = wave_max_f32(m);
-    const float ssum = wave_sum_f32(m > -INFINITY ? sv * __expf(m - mx) : 0.f);
-    const size_t slot = (size_t)blockIdx.x * kMaxCols + col;
-    for (int r = 0; r < p.k; ++r) {
-      const unsigned long long best = wave_max_u64(mine.v[0]);
-      if (mine.v[0] == best) mine.pop();
-      if (lane == 0) p.pkey[slot * kMaxTopk + r] = best;
-    }
-    if (lane == 0) { p.pmax[slot] = mx; p.psum[slot] = ssum; }
-  }
-}
-
 static void launch_merge(const LmHeadParams& p, hipStream_t stream) {
   if (p.k <= 1) hipLaunchKernelGGL(lmhead_merge_kernel<1>, dim3(p.BT), dim3(64), 0, stream, p);
   else if (p.k <= 2) hipLaunchKernelGGL(lmhead_merge_kernel<2>, dim3(p.BT), dim3(64), 0, stream, p);
@@ -595,41 +402,8 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
   p.n_blocks = (Vp1 + kRowsPerBlock - 1) / kRowsPerBlock;
   p.pmax = ctx->lm_pmax; p.psum = ctx->lm_psum; p.pkey = ctx->lm_pkey;
   p.topk_id = topk_id; p.topk_logp = topk_logp; p.lse = lse; p.logits_out = logits_out;
-  p.unit_counter = nullptr;
 
   if (dt == CTCSPEC_BF16) {
-    // few columns, hidden dimension 4096 or 8192: persistent workgroups that take units of 16 rows dynamically
-    const int nst = D % 2048 == 0 ? D / 2048 : 0;  // steps of 256 per wavefront and unit
-    const long long hs_need = (long long)p.BT * (2LL * D + 16);
-    const long long lds_need = hs_need + kMfmaWaves * kWStageBytes + kRedFloats * 4 + kUnitRing * 4;
-    const bool persistent_ok = (nst == 2 || nst == 4) && p.BT <= 16 && (long long)p.BT * (D / 8) <= 12 * 64 * kMfmaWaves &&
-                               lds_need <= 160 * 1024 && !bias && !logits_out && !getenv("CTCSPEC_LM_STATIC");
-    if (persistent_ok) {
-      p.KC = D;
-      p.hs_bytes = (int)hs_need;
-      p.hs_magic = (unsigned int)((0x100000000ull + (unsigned)(D / 8) - 1) / (unsigned)(D / 8));
-      p.unit_counter = ctx->lm_unit_counter;
-      p.n_blocks = ctx->num_cus;
-      const void* kern = nst == 2 ? (const void*)lmhead_bf16_persistent_kernel<2> : (const void*)lmhead_bf16_persistent_kernel<4>;
-      static int lds_allowed[2] = {0, 0};
-      if ((int)lds_need > lds_allowed[nst == 4]) {
-        CTCSPEC_HIP(ctx, hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_need));
-        lds_allowed[nst == 4] = (int)lds_need;
-      }
-      if (ctx->lm_profile) CTCSPEC_HIP(ctx, hipEventRecord(ctx->lm_ev0, ctx->stream));
-      if (nst == 2)
-        hipLaunchKernelGGL(lmhead_bf16_persistent_kernel<2>, dim3(p.n_blocks), dim3(64 * kMfmaWaves), (int)lds_need, ctx->stream, p);
-      else
-        hipLaunchKernelGGL(lmhead_bf16_persistent_kernel<4>, dim3(p.n_blocks), dim3(64 * kMfmaWaves), (int)lds_need, ctx->stream, p);
-      CTCSPEC_HIP(ctx, hipGetLastError());
-      if (ctx->lm_profile) {
-        CTCSPEC_HIP(ctx, hipEventRecord(ctx->lm_ev1, ctx->stream));
-        ctx->lm_profile_valid = 1;
-      }
-      launch_merge(p, ctx->stream);
-      CTCSPEC_HIP(ctx, hipGetLastError());
-      return CTCSPEC_OK;
-    }
     const int budget = 160 * 1024 - kMfmaWaves * kWStageBytes - 64;
     // deep prefetch (4 stages) when the whole hidden dimension fits in LDS at once; otherwise the
     // hidden states are chunked through LDS and the prefetch is 2 stages deep (register budget)
