@@ -5,40 +5,48 @@ namespace ctcspec {
 
 // Lane l looks at nodes l and l+64.  At each step the lanes whose node is a child of the current
 // node carrying the target token raise a ballot; sibling tokens are distinct, so at most one does.
+// Everything the walk reads is fetched up front in one round of loads (the node count included, so
+// nothing waits for it): the walk itself then runs on registers, lane to lane.
 __global__ __launch_bounds__(64) void accept_longest_kernel(const int32_t* n_nodes, const int32_t* node_token,
                                                             const int32_t* node_parent,
                                                             const int32_t* target, int T, int max_nodes,
                                                             int32_t* accept_len, int32_t* accept_nodes,
                                                             int32_t* accept_tokens, int32_t* next_token) {
   const int b = blockIdx.x, lane = threadIdx.x;
-  int n = n_nodes[b];
-  n = n < 1 ? 1 : (n > max_nodes ? max_nodes : n);
   const int32_t* tok = node_token + (size_t)b * max_nodes;
   const int32_t* par = node_parent + (size_t)b * max_nodes;
   const int32_t* tgt = target + (size_t)b * max_nodes;
   const int j0 = lane, j1 = lane + 64;
-  const int t0 = j0 < n ? tok[j0] : -1, p0 = j0 < n ? par[j0] : -2;
-  const int t1 = j1 < n ? tok[j1] : -1, p1 = j1 < n ? par[j1] : -2;
+  const int c0 = j0 < max_nodes ? j0 : max_nodes - 1, c1 = j1 < max_nodes ? j1 : max_nodes - 1;
+  int n = n_nodes[b];
+  int t0 = tok[c0], p0 = par[c0], g0 = tgt[c0];
+  int t1 = tok[c1], p1 = par[c1], g1 = tgt[c1];
+  n = n < 1 ? 1 : (n > max_nodes ? max_nodes : n);
+  if (j0 >= n) { t0 = -1; p0 = -2; }
+  if (j1 >= n) { t1 = -1; p1 = -2; }
+  const int root_token = __builtin_amdgcn_readfirstlane(t0);
   int cur = 0, len = 0;
-  int32_t* out_nodes = accept_nodes + (size_t)b * (T + 1);
-  int32_t* out_tokens = accept_tokens + (size_t)b * (T + 1);
-  if (lane == 0) { out_nodes[0] = 0; out_tokens[0] = tok[0]; }
+  int want = __builtin_amdgcn_readfirstlane(g0);  // target at the root
+  int my_node = lane == 0 ? 0 : -1, my_token = lane == 0 ? root_token : -1;  // lane i: entry i of the outputs
   while (len < T) {
-    const int want = tgt[cur];
-    unsigned long long hit0 = __ballot(j0 > 0 && p0 == cur && t0 == want);
-    unsigned long long hit1 = __ballot(p1 == cur && t1 == want);
+    const unsigned long long hit0 = __ballot(j0 > 0 && p0 == cur && t0 == want);
+    const unsigned long long hit1 = __ballot(p1 == cur && t1 == want);
     int nxt = -1;
     if (hit0) nxt = __builtin_ctzll(hit0);
     else if (hit1) nxt = 64 + __builtin_ctzll(hit1);
     if (nxt < 0) break;
     cur = nxt;
     ++len;
-    if (lane == 0) { out_nodes[len] = cur; out_tokens[len] = want; }
+    if (lane == len) { my_node = cur; my_token = want; }
+    want = __builtin_amdgcn_readlane(cur < 64 ? g0 : g1, cur & 63);
+  }
+  if (lane <= T) {
+    accept_nodes[(size_t)b * (T + 1) + lane] = my_node;
+    accept_tokens[(size_t)b * (T + 1) + lane] = my_token;
   }
   if (lane == 0) {
-    for (int i = len + 1; i <= T; ++i) { out_nodes[i] = -1; out_tokens[i] = -1; }
     accept_len[b] = len;
-    next_token[b] = tgt[cur];
+    next_token[b] = want;
   }
 }
 
