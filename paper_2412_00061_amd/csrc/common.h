@@ -51,9 +51,9 @@ struct ctcspec_ctx {
   unsigned char* collapse_ws;   // [max_batch][kCollapseWsBytesPerSeq]
   // attention
   int attn_units;               // number of (sequence, head, split) partial slots
-  float* attn_po;               // [attn_units][max_nodes][max_head_dim]
-  float* attn_pm;               // [attn_units][max_nodes]
-  float* attn_pl;               // [attn_units][max_nodes]
+  float* attn_po;               // [attn_units][128][max_head_dim]
+  float* attn_pm;               // [attn_units][128]
+  float* attn_pl;               // [attn_units][128]
 };
 
 namespace ctcspec {

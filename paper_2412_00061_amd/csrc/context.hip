@@ -68,8 +68,8 @@ extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec
   size_t o_psum = carve((size_t)ctx->lm_max_blocks * kMaxCols * sizeof(float));
   size_t o_pkey = carve((size_t)ctx->lm_max_blocks * kMaxCols * kMaxTopk * sizeof(unsigned long long));
   size_t o_coll = carve((size_t)lim->max_batch * kCollapseWsBytesPerSeq);
-  // attention partials are stored per query block of up to 64 rows: round the row count up
-  const size_t attn_rows = (size_t)ctx->attn_units * (((size_t)lim->max_nodes + 63) / 64 * 64);
+  // attention partials: one slot of 128 query rows per (sequence, head, key split)
+  const size_t attn_rows = (size_t)ctx->attn_units * 128;
   size_t o_po = carve(attn_rows * lim->max_head_dim * sizeof(float));
   size_t o_pm = carve(attn_rows * sizeof(float));
   size_t o_pl = carve(attn_rows * sizeof(float));

@@ -6,8 +6,6 @@
 //                                optional key splits combined by tree_attn_merge_kernel
 //   * tree_attn_generic_kernel - any dtype / head dimension within the limits: one workgroup per
 //                                (node, head, sequence), keys in chunks with an online softmax
-#include <stdlib.h>
-
 #include <type_traits>
 #include <utility>
 
@@ -548,29 +546,25 @@ extern "C" int tree_verify_attn(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* 
   p.B = B; p.H = H; p.dh = dh; p.max_nodes = max_nodes; p.scale = scale; p.out = out;
   if (dt == CTCSPEC_BF16 && dh == 128) {
     CTCSPEC_REQUIRE(ctx, scale > 0.f, CTCSPEC_EINVAL, "tree_verify_attn: scale must be positive");
-    // Launch shape: blocks of 64 (max_nodes <= 64) or 128 query rows; S key splits chosen so that
-    // about 256 workgroups exist and each still has a few tiles of 32 keys to stream.
+    // Launch shape: one block of 128 query rows per (sequence, head) - 8 wavefronts of 16 rows; with 64
+    // nodes or fewer the upper four wavefronts only help to fetch the tiles, which still beats a
+    // workgroup of four - and S key splits, chosen so that about 256 workgroups exist and each still
+    // has a few tiles of 32 keys to stream.
+    constexpr int kRows = 128;
     const long long bh = (long long)B * H;
-    int rows = max_nodes > 64 ? 128 : 64;  // query rows per workgroup: 8 or 4 wavefronts of 16
-    int pf = 2;
-    if (const char* e = getenv("CTCSPEC_ATTN_ROWS")) rows = atoi(e) == 64 ? 64 : 128;
-    if (const char* e = getenv("CTCSPEC_ATTN_PF")) pf = atoi(e);
     AttnSplit sp;
-    sp.QB = (max_nodes + rows - 1) / rows;
+    sp.QB = (max_nodes + kRows - 1) / kRows;
     const int key_tiles = (kv_cap + max_nodes + kTileKeys - 1) / kTileKeys;
     long long S = 256 / (bh * sp.QB);
     if (S > key_tiles / 4) S = key_tiles / 4;
     if (S > kMaxKvSplits) S = kMaxKvSplits;
-    if (const char* e = getenv("CTCSPEC_ATTN_SPLITS")) S = atoi(e);
-    while (S > 1 && bh * sp.QB * S * rows > (long long)ctx->attn_units * ((ctx->lim.max_nodes + 63) / 64 * 64)) --S;
+    while (S > 1 && bh * sp.QB * S > (long long)ctx->attn_units) --S;  // partial slots of the workspace
     if (S < 1) S = 1;
     sp.S = (int)S;
     sp.po = ctx->attn_po; sp.pm = ctx->attn_pm; sp.pl = ctx->attn_pl;
     CTCSPEC_REQUIRE(ctx, bh * sp.QB * S <= 0x7fffffffLL && bh * max_nodes <= 0x7fffffffLL, CTCSPEC_EUNSUPPORTED,
                     "tree_verify_attn: grid too large");
-    hipError_t e;
-    if (rows == 64) e = pf == 2 ? launch_attn_bf16<1, 4, 2>(p, sp, ctx->stream) : (pf == 3 ? launch_attn_bf16<1, 4, 3>(p, sp, ctx->stream) : launch_attn_bf16<1, 4, 4>(p, sp, ctx->stream));
-    else e = pf == 2 ? launch_attn_bf16<1, 8, 2>(p, sp, ctx->stream) : (pf == 3 ? launch_attn_bf16<1, 8, 3>(p, sp, ctx->stream) : launch_attn_bf16<1, 8, 4>(p, sp, ctx->stream));
+    const hipError_t e = launch_attn_bf16<1, kRows / 16, 2>(p, sp, ctx->stream);
     CTCSPEC_HIP(ctx, e);
     return CTCSPEC_OK;
   }
