@@ -1,0 +1,207 @@
+"""GPU tests of how the step is launched rather than of what it computes: the prepared-call path that the
+benchmark times, replay from a captured HIP graph, and the draft-head timing hook.
+
+Each compares the library with itself (eager, freshly marshalled calls); the comparison with the oracle is in
+test_gpu_parity.py.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from gpu_harness import cached_inputs
+from workloads.device import dev_f32, dev_i32, dev_i64, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2412_00061_amd as m
+    m.load_library()
+    return m
+
+
+class _Step:
+    """Buffers and prepared calls of one step of a configuration, as bench.py sets them up."""
+
+    def __init__(self, pkg, cfg_index, seed=0, variant="literal"):
+        from paper_2412_00061_amd.binding import CTCSPEC_BF16, CTCSPEC_F32
+        self.pkg = pkg
+        cfg = self.cfg = workloads.get_config(cfg_index)
+        x = self.x = cached_inputs(cfg_index, seed, variant)
+        self.ctx = pkg.Context.for_config(cfg)
+        B, T, k, N, H, dh = cfg.B, cfg.T, cfg.k, cfg.max_nodes, cfg.H, cfg.dh
+        dt = CTCSPEC_BF16 if cfg.dtype == "bf16" else CTCSPEC_F32
+        self.keep = [to_device(x.hidden, cfg.dtype), to_device(x.w, cfg.dtype), dev_f32(x.bias),
+                     dev_i32(x.root_token)]
+        d_hidden, d_w, d_bias, d_root = self.keep
+        q, kt, vt, kc, vc = (to_device(a, cfg.dtype) for a in (x.q, x.k_tree, x.v_tree, x.k_cache, x.v_cache))
+        d_off, d_len = dev_i64(x.kv_off), dev_i32(x.ctx_len)
+        self.keep += [q, kt, vt, kc, vc, d_off, d_len]
+
+        def i32(*shape):
+            return torch.full(shape, -7, dtype=torch.int32, device="cuda")
+
+        def f32(*shape):
+            return torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+
+        words = (N + 63) // 64
+        o = self.out = dict(
+            topk_id=i32(B, T, k), topk_logp=f32(B, T, k), lse=f32(B, T),
+            n_cand=i32(B), cand_tokens=i32(B, cfg.beam, T), cand_len=i32(B, cfg.beam),
+            cand_score=f32(B, cfg.beam), cand_leaf=i32(B, cfg.beam),
+            n_nodes=i32(B), node_token=i32(B, N), node_parent=i32(B, N), node_depth=i32(B, N),
+            anc_mask=torch.zeros((B, N, words), dtype=torch.int64, device="cuda"),
+            attn=f32(B, H, N, dh),
+            accept_len=i32(B), accept_nodes=i32(B, T + 1), accept_tokens=i32(B, T + 1), next_token=i32(B))
+        self.targets = torch.full((B, N), cfg.V + 5, dtype=torch.int32, device="cuda")
+        ctx, scale = self.ctx, 1.0 / math.sqrt(dh)
+        self.calls = (
+            pkg.prepared(ctx, "ctc_draft_topk", dt, d_hidden, d_w, d_bias, B, T, cfg.D, cfg.Vp1, k, o["topk_id"],
+                         o["topk_logp"], o["lse"], None),
+            pkg.prepared(ctx, "ctc_collapse_tree", o["topk_id"], o["topk_logp"], d_root, B, T, k, cfg.blank_id,
+                         cfg.beam, N, o["n_cand"], o["cand_tokens"], o["cand_len"], o["cand_score"],
+                         o["cand_leaf"], o["n_nodes"], o["node_token"], o["node_parent"], o["node_depth"],
+                         o["anc_mask"]),
+            pkg.prepared(ctx, "tree_verify_attn", dt, q, kc, vc, d_off, d_len, cfg.kv_cap, kt, vt, o["n_nodes"],
+                         o["anc_mask"], B, H, dh, N, scale, o["attn"]),
+            pkg.prepared(ctx, "accept_longest", o["n_nodes"], o["node_token"], o["node_parent"], o["node_depth"],
+                         self.targets, B, T, N, o["accept_len"], o["accept_nodes"], o["accept_tokens"],
+                         o["next_token"]),
+        )
+
+    def run(self):
+        for c in self.calls:
+            c()
+
+    def snapshot(self):
+        torch.cuda.synchronize()
+        n = self.out["n_nodes"].cpu().numpy()
+        snap = {}
+        for name, t in self.out.items():
+            a = t.cpu().numpy().copy()
+            if name == "attn":  # rows of nodes that do not exist are not written
+                for b in range(a.shape[0]):
+                    a[b, :, n[b]:] = 0
+            snap[name] = a
+        return snap
+
+    def scrub(self):
+        for name, t in self.out.items():
+            if t.dtype == torch.float32:
+                t.fill_(float("nan"))
+            else:
+                t.fill_(-7 if name != "anc_mask" else 0)
+
+    def plant_targets(self):
+        """Make the acceptance walk follow the deepest path of the tree the step produced."""
+        torch.cuda.synchronize()
+        cfg = self.cfg
+        n = self.out["n_nodes"].cpu().numpy()
+        par, tok, dep = (self.out[k].cpu().numpy() for k in ("node_parent", "node_token", "node_depth"))
+        tgt = np.full((cfg.B, cfg.max_nodes), cfg.V + 5, dtype=np.int32)
+        for b in range(cfg.B):
+            node = int(np.argmax(dep[b, :n[b]]))
+            while node > 0:
+                tgt[b, par[b, node]] = tok[b, node]
+                node = par[b, node]
+        self.targets.copy_(torch.from_numpy(tgt))
+
+
+def _same(a, b):
+    for name in a:
+        assert np.array_equal(a[name], b[name], equal_nan=True), name
+
+
+@pytest.mark.parametrize("cfg_index", [0, 2])
+def test_prepared_calls_match_fresh_calls(pkg, cfg_index):
+    st = _Step(pkg, cfg_index)
+    st.run()
+    st.plant_targets()
+    st.run()
+    got = st.snapshot()
+    cfg, ctx = st.cfg, st.ctx
+    d_hidden, d_w, d_bias, d_root, q, kt, vt, kc, vc, d_off, d_len = st.keep
+    s12 = pkg.ctc_draft_topk(ctx, d_hidden, d_w, d_bias, cfg.k)
+    s3 = pkg.ctc_collapse_tree(ctx, s12["topk_id"], s12["topk_logp"], d_root, cfg.blank_id, cfg.beam,
+                               cfg.max_nodes)
+    attn = pkg.tree_verify_attn(ctx, q, kc, vc, d_off, d_len, cfg.kv_cap, kt, vt, s3["n_nodes"], s3["anc_mask"],
+                                1.0 / math.sqrt(cfg.dh))
+    acc = pkg.accept_longest(ctx, s3["n_nodes"], s3["node_token"], s3["node_parent"], s3["node_depth"],
+                             st.targets, cfg.T)
+    torch.cuda.synchronize()
+    for name in ("topk_id", "topk_logp", "lse"):
+        assert np.array_equal(got[name], s12[name].cpu().numpy()), name
+    for name in ("n_cand", "cand_tokens", "cand_len", "cand_score", "cand_leaf", "n_nodes", "node_token",
+                 "node_parent", "node_depth", "anc_mask"):
+        assert np.array_equal(got[name], s3[name].cpu().numpy()), name
+    n = got["n_nodes"]
+    a = attn.cpu().numpy()
+    for b in range(cfg.B):
+        assert np.array_equal(got["attn"][b, :, :n[b]], a[b, :, :n[b]])
+    for name in ("accept_len", "accept_nodes", "accept_tokens", "next_token"):
+        assert np.array_equal(got[name], acc[name].cpu().numpy()), name
+    assert int(got["accept_len"].max()) >= 1  # the planted path was followed
+    ctx.close()
+
+
+@pytest.mark.parametrize("cfg_index", [0, 2])
+def test_graph_replay_matches_eager(pkg, cfg_index):
+    """The whole step captured into one HIP graph: every replay, with eager work and synchronisation in
+    between, must reproduce the eager results bit for bit."""
+    st = _Step(pkg, cfg_index)
+    st.run()
+    st.plant_targets()
+    st.run()
+    eager = st.snapshot()
+
+    stream = torch.cuda.Stream()
+    st.ctx.set_stream(stream)
+    with torch.cuda.stream(stream):
+        st.run()  # warm-up on the capture stream (one-time function attribute calls happen outside capture)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            st.run()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        st.scrub()
+        torch.cuda.synchronize()
+        graph.replay()
+        _same(eager, st.snapshot())
+        # eager work of the program between the replays
+        st.ctx.set_stream(torch.cuda.current_stream())
+        st.scrub()
+        st.run()
+        _same(eager, st.snapshot())
+        st.ctx.set_stream(stream)
+    st.ctx.set_stream(torch.cuda.current_stream())
+    st.ctx.close()
+
+
+def test_draft_head_timing_hook(pkg):
+    st = _Step(pkg, 2)
+    ctx = st.ctx
+    with pytest.raises(pkg.CtcspecError):
+        ctx.draft_head_kernel_ms()  # profiling is off
+    ctx.profile_draft_head(True)
+    with pytest.raises(pkg.CtcspecError):
+        ctx.draft_head_kernel_ms()  # nothing recorded yet
+    st.calls[0]()
+    ms = ctx.draft_head_kernel_ms()
+    assert 0.005 < ms < 5.0  # 262 MB cannot be read in under 5 us; 5 ms would be 100 times too slow
+    st.calls[0]()
+    torch.cuda.synchronize()
+    t = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t[0].record()
+    st.calls[0]()
+    t[1].record()
+    torch.cuda.synchronize()
+    assert ctx.draft_head_kernel_ms() <= t[0].elapsed_time(t[1]) + 0.02  # the kernel alone vs the whole call
+    ctx.profile_draft_head(False)
+    with pytest.raises(pkg.CtcspecError):
+        ctx.draft_head_kernel_ms()
+    ctx.close()
