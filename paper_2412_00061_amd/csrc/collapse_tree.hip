@@ -41,6 +41,7 @@ struct CollapseParams {
   const int32_t* root_token;
   int T, k, blank_id, beam, max_nodes;
   unsigned int magic;  // ceil(2^32 / k): division by k as a multiply-high
+  unsigned int magic_n2;  // ceil(2^32 / k^(T/2)): division of a candidate index by the number of second halves
   int32_t* n_cand;
   int32_t* cand_tokens;
   int32_t* cand_len;
@@ -73,6 +74,7 @@ struct CollapseShared {
   unsigned long long keys[kLdsCap];
   unsigned long long ckeys[kLdsCap];
   unsigned int table[2 * kLdsCap];
+  unsigned int tree_table[128 * 64];  // (creator of the parent node, token code) -> (level, 127 - draft); zeroed at start
 };
 
 // ---- workgroup / wavefront primitives -------------------------------------------------------------
@@ -111,7 +113,8 @@ __device__ __forceinline__ int search_steps(int n) { return n > 0 ? 32 - __built
 
 // Two independent searches in lockstep: number of leading entries i of [0, n) with pred(i), where pred
 // is true exactly on a prefix.  Both probes of a step are issued before either result is used, so a
-// step costs one LDS round trip.
+// step costs one LDS round trip.  (Cutting the interval to an eighth per step with seven probes was
+// measured: the extra index arithmetic costs more than the saved round trips.)
 template <typename P0, typename P1>
 __device__ __forceinline__ void prefix_count2(int n, P0 pred0, P1 pred1, int& out0, int& out1) {
   int pos0 = 0, len0 = n, pos1 = 0, len1 = n;
@@ -359,9 +362,15 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
   const bool ror4_is_up = dpp_row_ror<4>((unsigned)lane) == (unsigned)(lane ^ 4);
 
   // ---- inputs, local token codes, rounding margin (first wavefront, registers only) -------------
+  // the tree table is cleared by everybody while the first wavefront's loads are in flight
+  int id = -1;
+  float lp = 0.f;
+  if (wave == 0 && lane < TK) {
+    id = p.topk_id[(size_t)b * TK + lane];
+    lp = p.topk_logp[(size_t)b * TK + lane];
+  }
+  for (int i = tid; i < 128 * 64 / 4; i += kThreads) reinterpret_cast<u32x4*>(s.tree_table)[i] = u32x4{0u, 0u, 0u, 0u};
   if (wave == 0) {
-    const int id = lane < TK ? p.topk_id[(size_t)b * TK + lane] : -1;
-    const float lp = lane < TK ? p.topk_logp[(size_t)b * TK + lane] : 0.f;
     int cd = lane;  // code = position of the first entry with the same token id
     for (int j = 0; j < TK; ++j) {
       const int idj = __builtin_amdgcn_readlane(id, j);
@@ -444,12 +453,19 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
       // X_(i) + Y_(j) with (i+1)(j+1) >= M is passed by at least M raw candidates; every wavefront
       // evaluates all i (j = ceil(M/(i+1)) - 1 = floor((M-1)/(i+1))), so no exchange is needed
       float best = -INFINITY;
-      for (int i = lane; i < n1; i += 64) {
+      float xs[kHalfMax / 64], ys[kHalfMax / 64];
+#pragma unroll
+      for (int u = 0; u < kHalfMax / 64; ++u) {  // every probe is requested before the first is used
+        const int i = lane + 64 * u;
         int j = (int)((float)(M - 1) / (float)(i + 1));
         j -= (j * (i + 1) > M - 1) ? 1 : 0;
         j += ((j + 1) * (i + 1) <= M - 1) ? 1 : 0;
-        if (j < n2) best = fmaxf(best, s.Xv[i] + s.Yv[j]);
+        const bool on = i < n1 && j < n2;
+        xs[u] = s.Xv[on ? i : 0];
+        ys[u] = on ? s.Yv[j] : -INFINITY;
       }
+#pragma unroll
+      for (int u = 0; u < kHalfMax / 64; ++u) best = fmaxf(best, xs[u] + ys[u]);
       const float tau = wave_max_f32(best);
       tau_valid = tau - delta;
       tau_f = tau_valid - delta;
@@ -533,7 +549,7 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
       unsigned long long ck = ~0ull;  // ~0: not walked (below tau_valid) or the empty draft
       if (final_level || rank_key_value(key) >= tau_valid) {
         const int idx = (int)rank_key_index(key);
-        const int a = idx / n2, bb = idx - a * n2;
+        const int a = n2 == 1 ? idx : (int)__umulhi((unsigned)idx, p.magic_n2), bb = idx - a * n2;  // idx / n2
         int len;
         const unsigned long long c =
             collapse_key(s, split_digits(a, pad1, k, magic), split_digits(bb, pad2, k, magic), T1, T2, k, &len);
@@ -599,10 +615,7 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
     M *= 4;
     __syncthreads();
   }
-  // the hash table is done with; the tree build below uses it as a zeroed direct-address table
-  __syncthreads();
-  for (int i = tid; i < 2 * kLdsCap; i += kThreads) s.table[i] = 0u;
-  __syncthreads();
+  __syncthreads();  // the kept list is complete
 
   const int n_c = n_d < beam ? n_d : beam;
   const int W = (max_nodes + 63) / 64;
@@ -631,7 +644,7 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         key[u] = ((unsigned)fprev[u] << 6) | (unsigned)((ck[u] >> (7 * (d - 1))) & 0x3f);
-        if (d <= len[u]) atomicMax(&s.table[key[u]], ((unsigned)d << 8) | (unsigned)(127 - (lane + 64 * u)));
+        if (d <= len[u]) atomicMax(&s.tree_table[key[u]], ((unsigned)d << 8) | (unsigned)(127 - (lane + 64 * u)));
       }
       // every lane's announcements must be issued before any lane reads a winner back: keep the
       // compiler from moving the reads up (the hardware executes a wavefront's LDS operations in order)
@@ -640,7 +653,7 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         if (d <= len[u]) {
-          const unsigned int won = __hip_atomic_load(&s.table[key[u]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          const unsigned int won = __hip_atomic_load(&s.tree_table[key[u]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
           fprev[u] = 127 - (int)(won & 0xffu);
           creators[u] |= (unsigned long long)fprev[u] << (8 * (d - 1));
         }
@@ -683,9 +696,18 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
       if (c >= n_c) continue;
       int par = 0, leaf = -1;
       unsigned long long m0 = 1ull, m1 = 0ull;  // ancestors so far: the root
-      for (int d = 0; d < len[u]; ++d) {
+      // node id of every level of my path: all lookups are requested before the first is used
+      int path_node[8];
+#pragma unroll
+      for (int d = 0; d < 8; ++d) {
+        const int f = d < len[u] ? (int)((creators[u] >> (8 * d)) & 0xff) : 0;
+        path_node[d] = s.kept_base[f] + (d - s.kept_m[f]);
+      }
+#pragma unroll
+      for (int d = 0; d < 8; ++d) {
+        if (d >= len[u]) break;
         const int f = (int)((creators[u] >> (8 * d)) & 0xff);
-        const int node = s.kept_base[f] + (d - s.kept_m[f]);
+        const int node = path_node[d];
         if (node >= max_nodes) { leaf = -1; break; }
         if (node < 64) m0 |= 1ull << node; else m1 |= 1ull << (node - 64);
         if (f == c) {
@@ -768,6 +790,11 @@ extern "C" int ctc_collapse_tree(ctcspec_ctx* ctx, const int32_t* topk_id, const
   p.topk_id = topk_id; p.topk_logp = topk_logp; p.root_token = root_token;
   p.T = T; p.k = k; p.blank_id = blank_id; p.beam = beam; p.max_nodes = max_nodes;
   p.magic = (unsigned int)((0x100000000ull + (unsigned)k - 1) / (unsigned)k);
+  {
+    unsigned long long n2 = 1;
+    for (int t = 0; t < T / 2; ++t) n2 *= (unsigned)k;  // T2 = T - ceil(T/2) = floor(T/2)
+    p.magic_n2 = n2 == 1 ? 0u : (unsigned int)((0x100000000ull + n2 - 1) / n2);  // n2 == 1: not used
+  }
   p.n_cand = n_cand; p.cand_tokens = cand_tokens; p.cand_len = cand_len; p.cand_score = cand_score;
   p.cand_leaf = cand_leaf; p.n_nodes = n_nodes; p.node_token = node_token; p.node_parent = node_parent;
   p.node_depth = node_depth; p.anc_mask = (unsigned long long*)anc_mask;
@@ -777,7 +804,7 @@ extern "C" int ctc_collapse_tree(ctcspec_ctx* ctx, const int32_t* topk_id, const
   static_assert(CTCSPEC_MAX_BEAM <= 128, "the tree build keeps two drafts per lane of one wavefront");
   static_assert(CTCSPEC_MAX_SLOTS <= 8 && CTCSPEC_MAX_TOPK <= 8, "half combinations have at most four base-k digits");
   static_assert(CTCSPEC_MAX_SLOTS * CTCSPEC_MAX_TOPK <= 64, "token codes fit 6 bits; the top-k lists fit one wavefront");
-  static_assert(128 * 64 <= 2 * kLdsCap, "direct-address table of (creator, code) pairs");
+  static_assert(CTCSPEC_MAX_BEAM <= 128 && CTCSPEC_MAX_SLOTS * CTCSPEC_MAX_TOPK <= 64, "direct-address table of (creator, code) pairs");
   const int lds = (int)sizeof(CollapseShared);
   static bool lds_allowed = false;
   if (!lds_allowed) {
