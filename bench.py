@@ -42,6 +42,10 @@ def parse_args():
     ap.add_argument("--kv-sets", type=int, default=32)
     ap.add_argument("--graph", action="store_true", help="replay the steps from a captured HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--attn-layers", type=int, default=-1,
+                    help="layers of the full-depth variant line (attention called once per layer on its own "
+                         "K/V/Q buffers); default: heads of the config (32 at 7B, 40 at 13B); 0: skip")
+    ap.add_argument("--full-depth-steps", type=int, default=24)
     ap.add_argument("--cpu-steps", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run ten 256 MiB device copies (known traffic, for scaling rocprofv3 HBM counters)")
@@ -250,7 +254,43 @@ def main():
     torch.cuda.synchronize()
     head_kernel_us = np.array(head_kernel_us)
 
+    # step time from the events of the second pass (first event to last event of each step)
+    step_ev = np.array([e[0].elapsed_time(e[4]) * 1e3 for e in evs])
+
+    # full-depth variant: the same step with the verification attention of EVERY layer of the base model,
+    # each layer on its own K/V cache and Q/K_tree/V_tree (buffer set l for layer l), still one stream
+    n_layers = args.attn_layers if args.attn_layers >= 0 else (H if cfg.dtype == "bf16" else 0)
+    full_depth = None
+    if n_layers > 0:
+        attn_calls = []
+        for q, kt, vt, kc, vc in sets:
+            attn_calls.append(lib.prepared(ctx, "tree_verify_attn", dt, q, kc, vc, d_off, d_len, cfg.kv_cap, kt, vt,
+                                           n_nodes_d, anc_mask, B, H, dh, N, scale, out_attn))
+
+        def full_step(i):
+            c1, c2, _, c4 = slots[i % period]
+            c1(); c2()
+            for l in range(n_layers):
+                attn_calls[(i * n_layers + l) % len(attn_calls)]()
+            c4()
+
+        for i in range(3):
+            full_step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.full_depth_steps):
+            full_step(3 + i)
+        torch.cuda.synchronize()
+        fd_us = (time.perf_counter() - t0) / args.full_depth_steps * 1e6
+
     head_b, attn_b, total_b = algorithmic_bytes(cfg, x.ctx_len, n_nodes)
+    if n_layers > 0:
+        fd_bytes = total_b + (n_layers - 1) * attn_b
+        full_depth = {"attention_layers": n_layers, "distinct_kv_sets": len(sets), "steps": args.full_depth_steps,
+                      "us_per_step": fd_us, "algorithmic_bytes": fd_bytes,
+                      "hbm_gbps": fd_bytes / (fd_us * 1e-6) / 1e9,
+                      "frac_of_hbm_peak": fd_bytes / (fd_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                      "verified_tokens_per_sec": int(n_nodes.sum()) / (fd_us * 1e-6)}
     head_us = float(head_kernel_us.mean())
     achieved = head_b / (head_us * 1e-6) / 1e9
     nodes_total = int(n_nodes.sum())
@@ -280,7 +320,10 @@ def main():
                              "tree_verify_attn": float(call_us[2]), "accept_longest": float(call_us[3])},
         "per_call_us_median": {"ctc_draft_topk": float(call_med[0]), "ctc_collapse_tree": float(call_med[1]),
                                "tree_verify_attn": float(call_med[2]), "accept_longest": float(call_med[3])},
+        "step_us_from_events": {"p10": float(np.percentile(step_ev, 10)), "median": float(np.median(step_ev)),
+                                "p90": float(np.percentile(step_ev, 90)), "n": int(len(step_ev))},
         "attention_hbm_gbps": attn_b / (float(call_us[2]) * 1e-6) / 1e9,
+        "full_depth_variant": full_depth,
         "roofline": {"kernel": "lmhead_bf16_mfma_kernel (ctc_draft_topk)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": read_traffic_summary(), "algorithmic_bytes_per_launch": head_b,

@@ -6,6 +6,8 @@
 //                                optional key splits combined by tree_attn_merge_kernel
 //   * tree_attn_generic_kernel - any dtype / head dimension within the limits: one workgroup per
 //                                (node, head, sequence), keys in chunks with an online softmax
+#include <stdlib.h>
+
 #include <type_traits>
 #include <utility>
 
@@ -184,10 +186,10 @@ struct AttnSplit {
   float* pl;   // [unit][rows] running sum
 };
 
-template <int QT, int NW, int PF>
+template <int QT, int NW, int CW, int PF>
 __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int ROWS = 16 * QT * NW;
+  constexpr int ROWS = 16 * QT * CW;  // the first CW wavefronts own query rows; all NW fetch tiles
   constexpr int kThreadsA = 64 * NW;
   constexpr int LU = 512 / kThreadsA;  // 16-byte pieces of K (and of V) per thread and tile
   const int tid = threadIdx.x, lane = tid & 63;
@@ -272,7 +274,7 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
 
   // ---- this wavefront's query columns: Q fragments (B operand of K.Q^T) and mask words -------------
   const int qbase = qb * ROWS + wave * 16 * QT;
-  const bool live_wave = qbase < n;
+  const bool live_wave = wave < CW && qbase < n;
   bf16x8 qf[QT][4];
   unsigned long long mw0[QT], mw1[QT];
   const int W = (p.max_nodes + 63) >> 6;
@@ -500,9 +502,9 @@ __global__ __launch_bounds__(kMergeThreads) void tree_attn_merge_kernel(AttnPara
   *(f32x4*)(p.out + ((size_t)bh * p.max_nodes + row) * 128 + d4) = acc * (1.0f / Lt);
 }
 
-template <int QT, int NW, int PF>
+template <int QT, int NW, int CW, int PF>
 static hipError_t launch_attn_bf16(const AttnParams& p, const AttnSplit& sp, hipStream_t stream) {
-  auto kern = tree_attn_bf16_kernel<QT, NW, PF>;
+  auto kern = tree_attn_bf16_kernel<QT, NW, CW, PF>;
   const long long blocks = (long long)sp.QB * sp.S * p.H * p.B;
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * NW), kAttnLdsBytes, stream, p, sp);
   hipError_t e = hipGetLastError();
@@ -510,7 +512,7 @@ static hipError_t launch_attn_bf16(const AttnParams& p, const AttnSplit& sp, hip
   const long long rows = (long long)p.B * p.H * p.max_nodes;
   const long long mblocks = (rows + kMergeThreads / 32 - 1) / (kMergeThreads / 32);
   hipLaunchKernelGGL(tree_attn_merge_kernel, dim3((unsigned)mblocks), dim3(kMergeThreads), 0, stream, p, sp,
-                     16 * QT * NW);
+                     16 * QT * CW);
   return hipGetLastError();
 }
 
@@ -550,7 +552,8 @@ extern "C" int tree_verify_attn(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* 
     // nodes or fewer the upper four wavefronts only help to fetch the tiles, which still beats a
     // workgroup of four - and S key splits, chosen so that about 256 workgroups exist and each still
     // has a few tiles of 32 keys to stream.
-    constexpr int kRows = 128;
+    int kRows = 128;
+    if (const char* e = getenv("CTCSPEC_ATTN_CW")) kRows = atoi(e) == 4 ? 64 : 128;
     const long long bh = (long long)B * H;
     AttnSplit sp;
     sp.QB = (max_nodes + kRows - 1) / kRows;
@@ -564,7 +567,7 @@ extern "C" int tree_verify_attn(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* 
     sp.po = ctx->attn_po; sp.pm = ctx->attn_pm; sp.pl = ctx->attn_pl;
     CTCSPEC_REQUIRE(ctx, bh * sp.QB * S <= 0x7fffffffLL && bh * max_nodes <= 0x7fffffffLL, CTCSPEC_EUNSUPPORTED,
                     "tree_verify_attn: grid too large");
-    const hipError_t e = launch_attn_bf16<1, kRows / 16, 2>(p, sp, ctx->stream);
+    const hipError_t e = kRows == 64 ? launch_attn_bf16<1, 8, 4, 2>(p, sp, ctx->stream) : launch_attn_bf16<1, 8, 8, 2>(p, sp, ctx->stream);
     CTCSPEC_HIP(ctx, e);
     return CTCSPEC_OK;
   }
