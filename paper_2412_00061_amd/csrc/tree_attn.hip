@@ -6,8 +6,6 @@
 //                                optional key splits combined by tree_attn_merge_kernel
 //   * tree_attn_generic_kernel - any dtype / head dimension within the limits: one workgroup per
 //                                (node, head, sequence), keys in chunks with an online softmax
-#include <stdlib.h>
-
 #include <type_traits>
 #include <utility>
 
@@ -125,8 +123,9 @@ __global__ __launch_bounds__(kGenericThreads) void tree_attn_generic_kernel(Attn
 
 
 // ---- bf16, dh = 128 -------------------------------------------------------------------------------
-// Workgroup = NW wavefronts = one block of 16*QT*NW query nodes of one (sequence, head) and one of S
-// splits of the keys; wavefront w owns query rows [16*QT*w, 16*QT*(w+1)) of the block.  The keys
+// Workgroup = NW wavefronts = one block of 16*QT*CW query nodes of one (sequence, head) and one of S
+// splits of the keys; wavefront w < CW owns query rows [16*QT*w, 16*QT*(w+1)) of the block (wavefronts
+// CW..NW-1 only help to fetch tiles).  The keys
 // (cached context rows first, then the tree nodes) are cut into tiles of 32; split s takes tiles s,
 // s+S, ...  A tile (K and V, 16 KB) is fetched ONCE per workgroup by all threads together (one or two
 // 16-byte loads of K and of V per thread, PF tiles ahead in registers), put into one of two LDS
@@ -146,7 +145,7 @@ __global__ __launch_bounds__(kGenericThreads) void tree_attn_generic_kernel(Attn
 //   S^T[key, q] = K.Q^T   : A = K rows from LDS, B = Q^T resident in VGPRs; every K fragment is used
 //                           for all QT query tiles
 //   P = exp2((S^T - m)*c) : in the MFMA C layout a lane holds 8 keys of ONE query column, so the
-//                           running max/sum are per lane plus an exchange between the 4 row groups
+//                           running max/sum are per lane plus an exchange between the 4 row groups (ds_bpermute)
 //   O^T[dh, q] += V^T.P   : P stays in registers as the B operand, as hi + lo bf16 halves so that it
 //                           carries 16 mantissa bits; MFMA row r of output block db is dh = 16*db + r
 constexpr int kTileKeys = 32;
@@ -163,23 +162,21 @@ __device__ __forceinline__ float max3_f32(float a, float b, float c) {
   asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
   return r;
 }
-// max / sum over the four lanes l, l^16, l^32, l^48 (the lanes that hold the same query column), by
-// row swaps inside the vector ALU
+// max / sum over the four lanes l, l^16, l^32, l^48 (the lanes that hold the same query column).
+// (v_permlane16_swap / v_permlane32_swap would do this inside the vector ALU, and did in an earlier
+// version - with results that changed from run to run in the last bits: the value read right after a
+// swap was not always the swapped one.  The exchange goes through ds_bpermute instead.)
 __device__ __forceinline__ float max_across_row_groups(float x) {
-  u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
-  u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+  x = fmaxf(x, __shfl_xor(x, 16, 64));
+  return fmaxf(x, __shfl_xor(x, 32, 64));
 }
 __device__ __forceinline__ float sum_across_row_groups(float x) {
-  u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
-  u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+  x += __shfl_xor(x, 16, 64);
+  return x + __shfl_xor(x, 32, 64);
 }
 
 struct AttnSplit {
-  int QB;      // query blocks of 16*QT*NW rows
+  int QB;      // query blocks of 16*QT*CW rows
   int S;       // key splits
   float* po;   // [unit][rows][128] partial O (unnormalised), unit = ((b*H + h)*QB + qb)*S + s
   float* pm;   // [unit][rows] softmax reference, scaled to the log2 domain
@@ -548,26 +545,31 @@ extern "C" int tree_verify_attn(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* 
   p.B = B; p.H = H; p.dh = dh; p.max_nodes = max_nodes; p.scale = scale; p.out = out;
   if (dt == CTCSPEC_BF16 && dh == 128) {
     CTCSPEC_REQUIRE(ctx, scale > 0.f, CTCSPEC_EINVAL, "tree_verify_attn: scale must be positive");
-    // Launch shape: one block of 128 query rows per (sequence, head) - 8 wavefronts of 16 rows; with 64
-    // nodes or fewer the upper four wavefronts only help to fetch the tiles, which still beats a
-    // workgroup of four - and S key splits, chosen so that about 256 workgroups exist and each still
-    // has a few tiles of 32 keys to stream.
-    int kRows = 128;
-    if (const char* e = getenv("CTCSPEC_ATTN_CW")) kRows = atoi(e) == 4 ? 64 : 128;
+    // Launch shape.  A workgroup has 8 wavefronts that all fetch tiles; 8 or 4 of them own 16 query rows
+    // each (blocks of 128 or 64 rows per (sequence, head)); S key splits, so that about 256 workgroups
+    // exist and each still has a few tiles of 32 keys to stream.  64-row blocks halve the partial results
+    // (fewer splits) at the price of a second pass over K/V through L2; they are taken when they fill
+    // more compute units, or as many with at least 4 splits.  Trees of 64 nodes or fewer use one block,
+    // its upper wavefronts only fetching.
     const long long bh = (long long)B * H;
-    AttnSplit sp;
-    sp.QB = (max_nodes + kRows - 1) / kRows;
     const int key_tiles = (kv_cap + max_nodes + kTileKeys - 1) / kTileKeys;
-    long long S = 256 / (bh * sp.QB);
-    if (S > key_tiles / 4) S = key_tiles / 4;
-    if (S > kMaxKvSplits) S = kMaxKvSplits;
-    while (S > 1 && bh * sp.QB * S > (long long)ctx->attn_units) --S;  // partial slots of the workspace
-    if (S < 1) S = 1;
-    sp.S = (int)S;
+    auto splits_for = [&](long long qblocks) {
+      long long S = 256 / (bh * qblocks);
+      if (S > key_tiles / 4) S = key_tiles / 4;
+      if (S > kMaxKvSplits) S = kMaxKvSplits;
+      while (S > 1 && bh * qblocks * S > (long long)ctx->attn_units) --S;  // partial slots of the workspace
+      return S < 1 ? 1LL : S;
+    };
+    const long long s128 = splits_for(1), s64 = splits_for(2);
+    const bool rows64 = max_nodes > 64 && (2 * s64 > s128 || (2 * s64 == s128 && s64 >= 4));
+    AttnSplit sp;
+    sp.QB = rows64 ? 2 : 1;
+    sp.S = (int)(rows64 ? s64 : s128);
     sp.po = ctx->attn_po; sp.pm = ctx->attn_pm; sp.pl = ctx->attn_pl;
-    CTCSPEC_REQUIRE(ctx, bh * sp.QB * S <= 0x7fffffffLL && bh * max_nodes <= 0x7fffffffLL, CTCSPEC_EUNSUPPORTED,
+    CTCSPEC_REQUIRE(ctx, bh * sp.QB * sp.S <= 0x7fffffffLL && bh * max_nodes <= 0x7fffffffLL, CTCSPEC_EUNSUPPORTED,
                     "tree_verify_attn: grid too large");
-    const hipError_t e = kRows == 64 ? launch_attn_bf16<1, 8, 4, 2>(p, sp, ctx->stream) : launch_attn_bf16<1, 8, 8, 2>(p, sp, ctx->stream);
+    const hipError_t e = rows64 ? launch_attn_bf16<1, 8, 4, 2>(p, sp, ctx->stream)
+                                : launch_attn_bf16<1, 8, 8, 2>(p, sp, ctx->stream);
     CTCSPEC_HIP(ctx, e);
     return CTCSPEC_OK;
   }
