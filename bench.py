@@ -46,6 +46,7 @@ def parse_args():
                     help="layers of the full-depth variant line (attention called once per layer on its own "
                          "K/V/Q buffers); default: heads of the config (32 at 7B, 40 at 13B); 0: skip")
     ap.add_argument("--full-depth-steps", type=int, default=24)
+    ap.add_argument("--no-closed-step", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run ten 256 MiB device copies (known traffic, for scaling rocprofv3 HBM counters)")
@@ -283,6 +284,58 @@ def main():
         torch.cuda.synchronize()
         fd_us = (time.perf_counter() - t0) / args.full_depth_steps * 1e6
 
+    # closed-step variant: the step plus the two calls that close it - the base model's LM head over the tree
+    # nodes' hidden states (greedy token per node, another pass over a [V, D] matrix) between attention and
+    # acceptance, and the history update afterwards
+    closed = None
+    if not args.no_closed_step and cfg.dtype == "bf16":
+        g = torch.Generator(device="cuda").manual_seed(args.seed + 1)
+        node_hidden = torch.randn((B, N, cfg.D), generator=g, device="cuda", dtype=torch.float32)
+        node_hidden = (node_hidden / node_hidden.pow(2).mean(-1, keepdim=True).sqrt()).to(torch.bfloat16)
+        wb0 = (torch.randn((cfg.V, cfg.D), generator=g, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+        w_base = [wb0] + [wb0.clone() for _ in range(max(1, args.w_copies // 2) - 1)]
+        vh_targets, new_len = i32(B, N), i32(B)
+        vh_calls = [lib.prepared(ctx, "verify_head_argmax", dt, node_hidden, wb, n_nodes_d, B, N, cfg.D, cfg.V,
+                                 vh_targets, None) for wb in w_base]
+        acc_call = lib.prepared(ctx, "accept_longest", n_nodes_d, node_token, node_parent, node_depth, vh_targets,
+                                B, T, N, accept_len, accept_nodes, accept_tokens, next_token)
+        commit_calls = [lib.prepared(ctx, "kv_commit", dt, kt, vt, accept_len, accept_nodes, T, d_off, d_len,
+                                     cfg.kv_cap, B, H, dh, N, kc, vc, new_len) for (q, kt, vt, kc, vc) in sets]
+
+        def closed_step(i):
+            c1, c2, c3, _ = slots[i % period]
+            c1(); c2(); c3()
+            vh_calls[i % len(vh_calls)]()
+            acc_call()
+            commit_calls[i % len(sets)]()
+
+        for i in range(5):
+            closed_step(i)
+        torch.cuda.synchronize()
+        n_cs = max(24, min(args.steps, 96))
+        t0 = time.perf_counter()
+        for i in range(n_cs):
+            closed_step(5 + i)
+        torch.cuda.synchronize()
+        cs_us = (time.perf_counter() - t0) / n_cs * 1e6
+        cs_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * n_cs)]
+        for i in range(n_cs):
+            c1, c2, c3, _ = slots[i % period]
+            c1(); c2(); c3()
+            cs_ev[2 * i].record()
+            vh_calls[i % len(vh_calls)]()
+            cs_ev[2 * i + 1].record()
+            acc_call()
+            commit_calls[i % len(sets)]()
+        torch.cuda.synchronize()
+        vh_us = float(np.median([cs_ev[2 * i].elapsed_time(cs_ev[2 * i + 1]) * 1e3 for i in range(n_cs)]))
+        vh_bytes = cfg.V * cfg.D * 2 * ((B * N + 127) // 128) + B * N * cfg.D * 2 + B * N * 4
+        closed = {"calls": "ctc_draft_topk, ctc_collapse_tree, tree_verify_attn, verify_head_argmax, accept_longest, "
+                           "kv_commit", "steps": n_cs, "us_per_step": cs_us,
+                  "verify_head_argmax_us_median": vh_us, "verify_head_algorithmic_bytes": vh_bytes,
+                  "verify_head_hbm_gbps": vh_bytes / (vh_us * 1e-6) / 1e9,
+                  "verified_tokens_per_sec": int(n_nodes.sum()) / (cs_us * 1e-6)}
+
     head_b, attn_b, total_b = algorithmic_bytes(cfg, x.ctx_len, n_nodes)
     if n_layers > 0:
         fd_bytes = total_b + (n_layers - 1) * attn_b
@@ -324,6 +377,7 @@ def main():
                                 "p90": float(np.percentile(step_ev, 90)), "n": int(len(step_ev))},
         "attention_hbm_gbps": attn_b / (float(call_us[2]) * 1e-6) / 1e9,
         "full_depth_variant": full_depth,
+        "closed_step_variant": closed,
         "roofline": {"kernel": "lmhead_bf16_mfma_kernel (ctc_draft_topk)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": read_traffic_summary(), "algorithmic_bytes_per_launch": head_b,

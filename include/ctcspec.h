@@ -200,6 +200,54 @@ int accept_longest(ctcspec_ctx* ctx, const int32_t* n_nodes, const int32_t* node
                    const int32_t* target_argmax, int B, int T, int max_nodes, int32_t* accept_len,
                    int32_t* accept_nodes, int32_t* accept_tokens, int32_t* next_token);
 
+/*
+ * Closing the step, part 1 - the base model's greedy token after every tree node (paper Sec. 3.1: the
+ * base model ends in an LM head that maps hidden states to the vocabulary; Sec. 2.1 / 3.3: candidates
+ * are verified against the base model's greedy output).  For sequence b and node i < n_nodes[b]:
+ *
+ *   z[v] = sum_d node_hidden[b,i,d] * w_base[v,d]          (fp32 accumulation)
+ *   target_argmax[b,i] = argmax_v z[v], the smaller id among equal logits
+ *
+ * This produces the target_argmax input of accept_longest; rows i >= n_nodes[b] receive -1.
+ *
+ * dt            element type of node_hidden and w_base
+ * node_hidden   [B,max_nodes,D]    16-byte aligned: the base model's last hidden state at every tree node
+ *               (rows >= n_nodes[b] are read and must be readable; their results are discarded)
+ * w_base        [V,D] row-major    16-byte aligned: the base model's LM head (no blank row)
+ * n_nodes       [B] int32 device
+ * target_argmax [B,max_nodes] int32 out
+ * logits_out    [B,max_nodes,V] float out, may be NULL; when given, receives exactly the z values the
+ *               argmax used (for parity checks; costs extra HBM writes)
+ * The weights are streamed once per 128 nodes (B*max_nodes / 128 passes, rounded up).
+ * Limits: B, max_nodes, V within the context's limits (V <= max_vocab_rows).
+ */
+int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* node_hidden, const void* w_base,
+                       const int32_t* n_nodes, int B, int max_nodes, int D, int V,
+                       int32_t* target_argmax, float* logits_out);
+
+/*
+ * Closing the step, part 2 - history update (paper Sec. 3.3: "the decoding history is updated according
+ * to the output").  The keys and values of the accepted path - the root, which is the base model's own
+ * token, then the accept_len[b] accepted draft tokens, in path order - are appended to sequence b's cached
+ * context in one attention layer:
+ *
+ *   for j = 0..accept_len[b]:  cache row ctx_len[b] + j of every head  <-  tree row accept_nodes[b,j]
+ *   ctx_len_out[b] = min(ctx_len[b] + accept_len[b] + 1, kv_cap)
+ *
+ * Rows that would fall beyond kv_cap are dropped.  One call per layer; layers share accept_* and ctx_len, so
+ * pass ctx_len_out only with the last layer (NULL otherwise).
+ *
+ * dt            element type of the K/V buffers
+ * k_tree, v_tree  [B,H,max_nodes,dh]  in (as given to tree_verify_attn)
+ * accept_len    [B] int32, accept_nodes [B,T+1] int32   as written by accept_longest
+ * kv_off, ctx_len, kv_cap, k_cache, v_cache   as for tree_verify_attn; the caches are written
+ * ctx_len_out   [B] int32 out or NULL; must not be the ctx_len buffer itself
+ */
+int kv_commit(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* k_tree, const void* v_tree,
+              const int32_t* accept_len, const int32_t* accept_nodes, int T, const int64_t* kv_off,
+              const int32_t* ctx_len, int kv_cap, int B, int H, int dh, int max_nodes, void* k_cache,
+              void* v_cache, int32_t* ctx_len_out);
+
 #ifdef __cplusplus
 }
 #endif

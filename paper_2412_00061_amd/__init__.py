@@ -11,8 +11,10 @@ from .binding import (  # noqa: F401
     accept_longest,
     ctc_collapse_tree,
     ctc_draft_topk,
+    kv_commit,
     library_path,
     load_library,
     prepared,
     tree_verify_attn,
+    verify_head_argmax,
 )

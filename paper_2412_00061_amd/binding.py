@@ -15,7 +15,7 @@ _LIB = None
 EXPORTS = (
     "ctcspec_create", "ctcspec_destroy", "ctcspec_set_stream", "ctcspec_last_error",
     "ctcspec_workspace_bytes", "ctcspec_profile_draft_head", "ctcspec_draft_head_kernel_ms", "ctc_draft_topk", "ctc_collapse_tree", "tree_verify_attn",
-    "accept_longest",
+    "accept_longest", "verify_head_argmax", "kv_commit",
 )
 
 CTCSPEC_F32, CTCSPEC_BF16 = 0, 1
@@ -71,6 +71,12 @@ def load_library():
                                      c_int, c_float, c_void_p]
     lib.accept_longest.restype = c_int
     lib.accept_longest.argtypes = [c_void_p] * 6 + [c_int, c_int, c_int] + [c_void_p] * 4
+    lib.verify_head_argmax.restype = c_int
+    lib.verify_head_argmax.argtypes = [c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int,
+                                       c_void_p, c_void_p]
+    lib.kv_commit.restype = c_int
+    lib.kv_commit.argtypes = [c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_void_p,
+                              c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p]
     _LIB = lib
     return lib
 
@@ -261,3 +267,31 @@ def accept_longest(ctx, n_nodes, node_token, node_parent, node_depth, target_arg
         _ptr(res["accept_len"]), _ptr(res["accept_nodes"]), _ptr(res["accept_tokens"]), _ptr(res["next_token"]))
     ctx._check(rc, "accept_longest")
     return res
+
+
+def verify_head_argmax(ctx, node_hidden, w_base, n_nodes, *, want_logits=False, out=None):
+    """node_hidden [B,max_nodes,D], w_base [V,D] (same dtype) -> dict(target_argmax [B,max_nodes][, logits])."""
+    B, max_nodes, D = node_hidden.shape
+    V = w_base.shape[0]
+    dev = node_hidden.device
+    res = {"target_argmax": _out(out, "target_argmax", (B, max_nodes), torch.int32, dev)}
+    if want_logits:
+        res["logits"] = _out(out, "logits", (B, max_nodes, V), torch.float32, dev)
+    rc = ctx.lib.verify_head_argmax(ctx.handle, _dtype_code(node_hidden), _ptr(node_hidden),
+                                    _ptr(w_base, node_hidden.dtype), _ptr(n_nodes, torch.int32), B, max_nodes, D, V,
+                                    _ptr(res["target_argmax"]), _ptr(res.get("logits")))
+    ctx._check(rc, "verify_head_argmax")
+    return res
+
+
+def kv_commit(ctx, k_tree, v_tree, accept_len, accept_nodes, kv_off, ctx_len, kv_cap, k_cache, v_cache, *,
+              ctx_len_out=None):
+    """Append the accepted path's K/V rows to the caches in place; ctx_len_out [B] int32 receives the new lengths."""
+    B, H, max_nodes, dh = k_tree.shape
+    T = accept_nodes.shape[1] - 1
+    rc = ctx.lib.kv_commit(ctx.handle, _dtype_code(k_tree), _ptr(k_tree), _ptr(v_tree, k_tree.dtype),
+                           _ptr(accept_len, torch.int32), _ptr(accept_nodes, torch.int32), T,
+                           _ptr(kv_off, torch.int64), _ptr(ctx_len, torch.int32), kv_cap, B, H, dh, max_nodes,
+                           _ptr(k_cache, k_tree.dtype), _ptr(v_cache, k_tree.dtype),
+                           _ptr(ctx_len_out, torch.int32) if ctx_len_out is not None else None)
+    ctx._check(rc, "kv_commit")

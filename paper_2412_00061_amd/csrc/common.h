@@ -25,6 +25,9 @@ constexpr int kMaxAlign = CTCSPEC_MAX_ALIGNMENTS;
 // sort keys, collapsed-sequence keys (8 B each) and a hash table of 2*kMaxAlign 4-byte slots.
 constexpr size_t kCollapseWsBytesPerSeq = (size_t)kMaxAlign * 8 * 2 + (size_t)kMaxAlign * 2 * 4;
 
+// ---- verifier head workspace geometry ---------------------------------------------------------
+constexpr int kVerifyCols = 128;  // columns (tree nodes) per pass over the base model's head weights
+
 // ---- attention workspace geometry --------------------------------------------------------------
 constexpr int kMaxKvSplits = 8;
 
@@ -47,6 +50,8 @@ struct ctcspec_ctx {
   int lm_profile;               // events are recorded around the main kernel when non-zero
   int lm_profile_valid;
   hipEvent_t lm_ev0, lm_ev1;
+  // verifier head
+  unsigned long long* vh_pkey;  // [lm_max_blocks][kVerifyCols] best (logit, id) key per row block and column
   // collapse / tree
   unsigned char* collapse_ws;   // [max_batch][kCollapseWsBytesPerSeq]
   // attention

@@ -1,0 +1,338 @@
+// verify_head_argmax: the base model's LM head over the hidden states of the tree nodes, reduced to the
+// greedy token per node.  kv_commit: append the accepted path's keys and values to the cached context.
+//
+// The head is the same stream over a [V, D] weight matrix as the draft head, but with up to 128 columns
+// (one per tree node) instead of 8, and all that is kept of a column is its best (logit, id) key:
+//   * verify_head_bf16_kernel    - bf16, D a multiple of 1024: MFMA, 128 vocabulary rows x 128 columns
+//                                  per workgroup, weights read once per block of 128 columns
+//   * verify_head_generic_kernel - any dtype/shape: plain fp32 FMA, one atomic max per (row block, column)
+//   * verify_head_merge_kernel   - best key over the row blocks -> token id, -1 for rows without a node
+#include <type_traits>
+#include <utility>
+
+#include "common.h"
+
+namespace ctcspec {
+
+constexpr int kVhCols = kVerifyCols;            // columns (tree nodes) per pass over the weights
+constexpr int kVhWaves = 8;
+constexpr int kVhRowPitch = 512 + 16;           // bytes per staged row: 256 bf16 + pad (conflict-free b128 reads)
+constexpr int kVhStripBytes = 16 * kVhRowPitch; // W strip of one wavefront: 16 rows x 256 k
+constexpr int kVhHsBytes = kVhCols * kVhRowPitch;  // hidden-state chunk: 128 columns x 256 k
+constexpr int kVhZStride = kRowsPerBlock + 4;   // floats per column of the logit block
+static_assert(kVhCols * kVhZStride * 4 <= kVhHsBytes + kVhWaves * kVhStripBytes, "logit block fits the staging area");
+
+struct VerifyHeadParams {
+  const void* hidden;   // [cols_total][D], this pass starts at column col0
+  const void* w;        // [V][D]
+  int col0, cols;       // columns of this pass (cols <= kVhCols)
+  int D, V;
+  int n_blocks;         // row blocks of 128
+  unsigned long long* pkey;  // [n_blocks][kVhCols] best key per (row block, column of the pass)
+  float* logits_out;    // [cols_total][V] or null
+  const int32_t* n_nodes;  // [B]
+  int max_nodes;
+  int32_t* target;      // [cols_total]
+};
+
+// ---- bf16 MFMA kernel -----------------------------------------------------------------------------------
+// 8 wavefronts; wavefront w owns vocabulary rows [block*128 + 16w, +16) against all 128 columns (8 MFMA
+// column tiles).  Per step of 256 hidden elements: the wavefront's W slice (8 coalesced 16-byte loads, 3
+// steps ahead in registers, nontemporal) goes through its private LDS strip into A fragments as in the
+// draft head; the hidden states of the step (128 columns x 256 k = 64 KB, the B operand of every
+// wavefront) are staged through LDS by all threads together, the next step's in registers meanwhile.
+// All loads are unconditional and counted (tail of the k loop peeled, indices clamped), so the waits name
+// the loads that may stay in flight.
+__global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyHeadParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int STAGES = 4, NT = kVhCols / 16;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int c = lane & 15, g = lane >> 4;
+  const int lrow = lane >> 5, lch = lane & 31;
+  unsigned char* hs = smem;
+  unsigned char* wst = smem + kVhHsBytes + wave * kVhStripBytes;
+  const int row0 = blockIdx.x * kRowsPerBlock + wave * 16;
+  const int total_steps = p.D / 256;  // the host guarantees D % (256 * STAGES) == 0
+
+  // byte offsets (32 bits: the host checks that the matrices are smaller than 4 GB) from two base pointers
+  const unsigned char* wbase = (const unsigned char*)p.w + lch * 16;
+  unsigned int woff[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    int row = row0 + 2 * j + lrow;
+    row = row < p.V ? row : p.V - 1;  // the ragged last block re-reads the last row
+    woff[j] = (unsigned int)row * (unsigned int)(p.D * 2);
+  }
+  // hidden-state staging: thread -> 8 pieces of 16 bytes; piece idx = tid + 512u: column idx >> 5, chunk idx & 31
+  const unsigned char* hbase = (const unsigned char*)p.hidden + (size_t)p.col0 * p.D * 2 + (tid & 31) * 16;
+  unsigned int hoff[8];
+  const int hdst0 = (tid >> 5) * kVhRowPitch + (tid & 31) * 16;  // piece u lands 16 columns further: + u * 16 * pitch
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int m = (tid >> 5) + 16 * u;
+    const int col = m < p.cols ? m : p.cols - 1;  // columns past the end repeat the last one (never read back)
+    hoff[u] = (unsigned int)col * (unsigned int)(p.D * 2);
+  }
+  u32x4 hreg[8];
+  auto hs_request = [&](int step) __attribute__((always_inline)) {
+    const int st = step < total_steps ? step : total_steps - 1;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) hreg[u] = *(const u32x4*)(hbase + hoff[u] + (unsigned int)st * 512u);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  u32x4 v[STAGES][8];
+  auto w_request = [&](int step, auto stage_tag) __attribute__((always_inline)) {
+    constexpr int ST = decltype(stage_tag)::value;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      v[ST][j] = __builtin_nontemporal_load((const u32x4*)(wbase + woff[j] + (unsigned int)step * 512u));
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  f32x4 acc[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  auto consume = [&](auto stage_tag) __attribute__((always_inline)) {
+    constexpr int ST = decltype(stage_tag)::value;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) *(u32x4*)(wst + (2 * j + lrow) * kVhRowPitch + lch * 16) = v[ST][j];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(wst + c * kVhRowPitch + kk * 64 + g * 16));
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const bf16x8 b = __builtin_bit_cast(bf16x8, *(const u32x4*)(hs + (nt * 16 + c) * kVhRowPitch + kk * 64 + g * 16));
+        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[nt], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // one step: publish its hidden states, request the next step's, refill the W stage freed last step
+  auto step_fn = [&](int i, auto stage_tag, auto refill_tag) __attribute__((always_inline)) {
+    constexpr int ST = decltype(stage_tag)::value;
+    constexpr bool REFILL = decltype(refill_tag)::value;
+    lds_barrier();  // every wavefront is done with the previous step's hidden states
+#pragma unroll
+    for (int u = 0; u < 8; ++u) *(u32x4*)(hs + (hdst0 + u * 16 * kVhRowPitch)) = hreg[u];
+    lds_barrier();
+    hs_request(i + 1);
+    if constexpr (REFILL) w_request(i + STAGES - 1, std::integral_constant<int, (ST + STAGES - 1) % STAGES>{});
+    consume(stage_tag);
+  };
+
+  hs_request(0);
+  w_request(0, std::integral_constant<int, 0>{});
+  w_request(1, std::integral_constant<int, 1>{});
+  w_request(2, std::integral_constant<int, 2>{});
+  const int nblk = total_steps / STAGES;
+  for (int blk = 0; blk + 1 < nblk; ++blk) {
+    [&]<int... SS>(std::integer_sequence<int, SS...>) {
+      (step_fn(blk * STAGES + SS, std::integral_constant<int, SS>{}, std::true_type{}), ...);
+    }(std::make_integer_sequence<int, STAGES>{});
+  }
+  {
+    const int i0 = (nblk - 1) * STAGES;  // last block: only its first step still has something to prefetch
+    step_fn(i0 + 0, std::integral_constant<int, 0>{}, std::true_type{});
+    step_fn(i0 + 1, std::integral_constant<int, 1>{}, std::false_type{});
+    step_fn(i0 + 2, std::integral_constant<int, 2>{}, std::false_type{});
+    step_fn(i0 + 3, std::integral_constant<int, 3>{}, std::false_type{});
+  }
+
+  // ---- logit block -> LDS (over the staging area), best key per column ------------------------------------
+  __syncthreads();
+  float* zbuf = (float*)smem;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    f32x4 z;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) z[i] = (row0 + g * 4 + i) < p.V ? acc[nt][i] : -INFINITY;
+    *(f32x4*)(zbuf + (nt * 16 + c) * kVhZStride + wave * 16 + g * 4) = z;
+  }
+  __syncthreads();
+  const int row_base = blockIdx.x * kRowsPerBlock;
+  if (p.logits_out) {
+    for (int idx = tid; idx < p.cols * kRowsPerBlock; idx += 64 * kVhWaves) {
+      const int m = idx / kRowsPerBlock, r = idx % kRowsPerBlock;
+      if (row_base + r < p.V) p.logits_out[(size_t)(p.col0 + m) * p.V + row_base + r] = zbuf[m * kVhZStride + r];
+    }
+  }
+  for (int m = wave; m < p.cols; m += kVhWaves) {
+    const float z0 = zbuf[m * kVhZStride + lane], z1 = zbuf[m * kVhZStride + lane + 64];
+    const int id0 = row_base + lane, id1 = row_base + lane + 64;
+    const unsigned long long a = id0 < p.V ? rank_key(z0, (unsigned)id0) : 0ull;
+    const unsigned long long b = id1 < p.V ? rank_key(z1, (unsigned)id1) : 0ull;
+    const unsigned long long best = wave_max_u64(a > b ? a : b);
+    if (lane == 0) p.pkey[(size_t)blockIdx.x * kVhCols + m] = best;
+  }
+}
+
+// ---- generic kernel: thread -> (row, column), the row block's best key per column by atomic max -----------
+__global__ __launch_bounds__(256) void verify_head_clear_kernel(VerifyHeadParams p) {
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < p.n_blocks * kVhCols; i += gridDim.x * 256) p.pkey[i] = 0ull;
+}
+template <typename T>
+__global__ __launch_bounds__(256) void verify_head_generic_kernel(VerifyHeadParams p) {
+  const int row_base = blockIdx.x * kRowsPerBlock;
+  const T* hidden = (const T*)p.hidden;
+  const T* w = (const T*)p.w;
+  for (int idx = threadIdx.x; idx < p.cols * kRowsPerBlock; idx += 256) {
+    const int m = idx / kRowsPerBlock, row = row_base + idx % kRowsPerBlock;
+    if (row >= p.V) continue;
+    const T* hp = hidden + (size_t)(p.col0 + m) * p.D;
+    const T* wr = w + (size_t)row * p.D;
+    float z = 0.f;
+    for (int d = 0; d < p.D; ++d) z = fmaf(load_as_float(hp + d), load_as_float(wr + d), z);
+    if (p.logits_out) p.logits_out[(size_t)(p.col0 + m) * p.V + row] = z;
+    atomicMax(&p.pkey[(size_t)blockIdx.x * kVhCols + m], rank_key(z, (unsigned)row));
+  }
+}
+
+// best key over the row blocks: one wavefront per column; rows of the node table without a node get -1
+__global__ __launch_bounds__(64) void verify_head_merge_kernel(VerifyHeadParams p) {
+  const int m = blockIdx.x, lane = threadIdx.x;
+  unsigned long long best = 0ull;
+  for (int b0 = 0; b0 < p.n_blocks; b0 += 256) {
+    unsigned long long x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int b = b0 + u * 64 + lane;
+      x[u] = b < p.n_blocks ? p.pkey[(size_t)b * kVhCols + m] : 0ull;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) best = x[u] > best ? x[u] : best;
+  }
+  best = wave_max_u64(best);
+  if (lane == 0) {
+    const int col = p.col0 + m;
+    const int b = col / p.max_nodes, i = col - b * p.max_nodes;
+    int n = p.n_nodes[b];
+    n = n < 0 ? 0 : (n > p.max_nodes ? p.max_nodes : n);
+    p.target[col] = i < n ? (int32_t)rank_key_index(best) : -1;
+  }
+}
+
+// ---- kv_commit ------------------------------------------------------------------------------------------------
+struct KvCommitParams {
+  const unsigned char* k_tree;
+  const unsigned char* v_tree;
+  const int32_t* accept_len;
+  const int32_t* accept_nodes;
+  const int64_t* kv_off;
+  const int32_t* ctx_len;
+  unsigned char* k_cache;
+  unsigned char* v_cache;
+  int32_t* ctx_len_out;
+  int T, kv_cap, H, max_nodes;
+  int row_bytes;  // dh * element size
+  int elem_bytes;
+};
+// one workgroup per (head, sequence); the path has at most T + 1 rows of row_bytes each
+__global__ __launch_bounds__(256) void kv_commit_kernel(KvCommitParams p) {
+  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  int len = p.accept_len[b];
+  len = len < 0 ? 0 : (len > p.T ? p.T : len);
+  int L = p.ctx_len[b];
+  L = L < 0 ? 0 : (L > p.kv_cap ? p.kv_cap : L);
+  const size_t cache_head = ((size_t)p.kv_off[b] * p.elem_bytes) + (size_t)h * p.kv_cap * p.row_bytes;
+  const size_t tree_head = ((size_t)b * p.H + h) * p.max_nodes * (size_t)p.row_bytes;
+  const bool vec = (p.row_bytes & 15) == 0 && (cache_head & 15) == 0;
+  for (int j = 0; j <= len; ++j) {
+    const int node = p.accept_nodes[(size_t)b * (p.T + 1) + j];
+    const int pos = L + j;
+    if (node < 0 || node >= p.max_nodes || pos >= p.kv_cap) continue;
+    const size_t src = tree_head + (size_t)node * p.row_bytes, dst = cache_head + (size_t)pos * p.row_bytes;
+    if (vec) {
+      for (int q = tid; q < p.row_bytes / 16; q += 256) {
+        *(u32x4*)(p.k_cache + dst + q * 16) = *(const u32x4*)(p.k_tree + src + q * 16);
+        *(u32x4*)(p.v_cache + dst + q * 16) = *(const u32x4*)(p.v_tree + src + q * 16);
+      }
+    } else {
+      for (int q = tid; q < p.row_bytes; q += 256) {
+        p.k_cache[dst + q] = p.k_tree[src + q];
+        p.v_cache[dst + q] = p.v_tree[src + q];
+      }
+    }
+  }
+  if (h == 0 && tid == 0 && p.ctx_len_out) {
+    const int grown = L + len + 1;
+    p.ctx_len_out[b] = grown > p.kv_cap ? p.kv_cap : grown;
+  }
+}
+
+}  // namespace ctcspec
+
+using namespace ctcspec;
+
+extern "C" int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* node_hidden, const void* w_base,
+                                  const int32_t* n_nodes, int B, int max_nodes, int D, int V,
+                                  int32_t* target_argmax, float* logits_out) {
+  if (!ctx) return CTCSPEC_EINVAL;
+  CTCSPEC_REQUIRE(ctx, node_hidden && w_base && n_nodes && target_argmax, CTCSPEC_EINVAL,
+                  "verify_head_argmax: null pointer");
+  CTCSPEC_REQUIRE(ctx, dt == CTCSPEC_F32 || dt == CTCSPEC_BF16, CTCSPEC_EINVAL, "verify_head_argmax: bad dtype");
+  CTCSPEC_REQUIRE(ctx, B > 0 && max_nodes > 0 && D > 0 && V > 0, CTCSPEC_EINVAL,
+                  "verify_head_argmax: sizes must be positive");
+  CTCSPEC_REQUIRE(ctx, aligned16(node_hidden) && aligned16(w_base), CTCSPEC_EINVAL,
+                  "verify_head_argmax: node_hidden and w_base must be 16-byte aligned");
+  CTCSPEC_REQUIRE(ctx, B <= ctx->lim.max_batch && max_nodes <= ctx->lim.max_nodes && V <= ctx->lim.max_vocab_rows,
+                  CTCSPEC_EUNSUPPORTED, "verify_head_argmax: shape exceeds the context's limits");
+  VerifyHeadParams p;
+  p.hidden = node_hidden; p.w = w_base; p.D = D; p.V = V;
+  p.n_blocks = (V + kRowsPerBlock - 1) / kRowsPerBlock;
+  p.pkey = ctx->vh_pkey; p.logits_out = logits_out; p.n_nodes = n_nodes; p.max_nodes = max_nodes;
+  p.target = target_argmax;
+  const long long cols_total = (long long)B * max_nodes;
+  const bool wide = dt == CTCSPEC_BF16 && D % 1024 == 0 && (long long)V * D * 2 < (1LL << 32) &&
+                    cols_total * D * 2 < (1LL << 32);
+  const int lds = kVhHsBytes + kVhWaves * kVhStripBytes;
+  if (wide) {
+    static bool lds_allowed = false;  // raising the limit is needed once per process
+    if (!lds_allowed) {
+      CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)verify_head_bf16_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+      lds_allowed = true;
+    }
+  }
+  for (long long col0 = 0; col0 < cols_total; col0 += kVhCols) {
+    p.col0 = (int)col0;
+    p.cols = (int)(cols_total - col0 < kVhCols ? cols_total - col0 : kVhCols);
+    if (wide) {
+      hipLaunchKernelGGL(verify_head_bf16_kernel, dim3(p.n_blocks), dim3(64 * kVhWaves), lds, ctx->stream, p);
+    } else {
+      hipLaunchKernelGGL(verify_head_clear_kernel, dim3(64), dim3(256), 0, ctx->stream, p);
+      if (dt == CTCSPEC_BF16)
+        hipLaunchKernelGGL(verify_head_generic_kernel<unsigned short>, dim3(p.n_blocks), dim3(256), 0, ctx->stream, p);
+      else
+        hipLaunchKernelGGL(verify_head_generic_kernel<float>, dim3(p.n_blocks), dim3(256), 0, ctx->stream, p);
+    }
+    CTCSPEC_HIP(ctx, hipGetLastError());
+    hipLaunchKernelGGL(verify_head_merge_kernel, dim3(p.cols), dim3(64), 0, ctx->stream, p);
+    CTCSPEC_HIP(ctx, hipGetLastError());
+  }
+  return CTCSPEC_OK;
+}
+
+extern "C" int kv_commit(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* k_tree, const void* v_tree,
+                         const int32_t* accept_len, const int32_t* accept_nodes, int T, const int64_t* kv_off,
+                         const int32_t* ctx_len, int kv_cap, int B, int H, int dh, int max_nodes, void* k_cache,
+                         void* v_cache, int32_t* ctx_len_out) {
+  if (!ctx) return CTCSPEC_EINVAL;
+  CTCSPEC_REQUIRE(ctx, k_tree && v_tree && accept_len && accept_nodes && kv_off && ctx_len && k_cache && v_cache,
+                  CTCSPEC_EINVAL, "kv_commit: null pointer");
+  CTCSPEC_REQUIRE(ctx, dt == CTCSPEC_F32 || dt == CTCSPEC_BF16, CTCSPEC_EINVAL, "kv_commit: bad dtype");
+  CTCSPEC_REQUIRE(ctx, B > 0 && H > 0 && dh > 0 && max_nodes > 0 && T > 0 && kv_cap >= 0, CTCSPEC_EINVAL,
+                  "kv_commit: sizes must be positive");
+  CTCSPEC_REQUIRE(ctx, ctx_len_out != ctx_len, CTCSPEC_EINVAL,
+                  "kv_commit: ctx_len_out must not be ctx_len (every head's workgroup reads the old length)");
+  CTCSPEC_REQUIRE(ctx, B <= 65535 && T <= CTCSPEC_MAX_SLOTS, CTCSPEC_EUNSUPPORTED,
+                  "kv_commit: B <= 65535 and T <= %d required", CTCSPEC_MAX_SLOTS);
+  KvCommitParams p;
+  p.elem_bytes = dt == CTCSPEC_BF16 ? 2 : 4;
+  p.k_tree = (const unsigned char*)k_tree; p.v_tree = (const unsigned char*)v_tree;
+  p.accept_len = accept_len; p.accept_nodes = accept_nodes; p.kv_off = kv_off; p.ctx_len = ctx_len;
+  p.k_cache = (unsigned char*)k_cache; p.v_cache = (unsigned char*)v_cache; p.ctx_len_out = ctx_len_out;
+  p.T = T; p.kv_cap = kv_cap; p.H = H; p.max_nodes = max_nodes; p.row_bytes = dh * p.elem_bytes;
+  hipLaunchKernelGGL(kv_commit_kernel, dim3(H, B), dim3(256), 0, ctx->stream, p);
+  CTCSPEC_HIP(ctx, hipGetLastError());
+  return CTCSPEC_OK;
+}
