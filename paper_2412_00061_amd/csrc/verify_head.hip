@@ -3,7 +3,7 @@
 //
 // The head is the same stream over a [V, D] weight matrix as the draft head, but with up to 128 columns
 // (one per tree node) instead of 8, and all that is kept of a column is its best (logit, id) key:
-//   * verify_head_bf16_kernel    - bf16, D a multiple of 1024: MFMA, 128 vocabulary rows x 128 columns
+//   * verify_head_bf16_kernel    - bf16, D a multiple of 512: MFMA, 128 vocabulary rows x 128 columns
 //                                  per workgroup, weights read once per block of 128 columns
 //   * verify_head_generic_kernel - any dtype/shape: plain fp32 FMA, one atomic max per (row block, column)
 //   * verify_head_merge_kernel   - best key over the row blocks -> token id, -1 for rows without a node
@@ -15,7 +15,9 @@
 namespace ctcspec {
 
 constexpr int kVhCols = kVerifyCols;            // columns (tree nodes) per pass over the weights
-constexpr int kVhWaves = 8;
+constexpr int kVhWaves = 8;                     // 16-row tiles per workgroup
+constexpr int kVhRowTiles = 1;                  // of them per wavefront
+constexpr int kVhStages = 2;                    // W register stages (prefetch distance + 1)
 constexpr int kVhRowPitch = 512 + 16;           // bytes per staged row: 256 bf16 + pad (conflict-free b128 reads)
 constexpr int kVhStripBytes = 16 * kVhRowPitch; // W strip of one wavefront: 16 rows x 256 k
 constexpr int kVhHsBytes = kVhCols * kVhRowPitch;  // hidden-state chunk: 128 columns x 256 k
@@ -36,73 +38,86 @@ struct VerifyHeadParams {
 };
 
 // ---- bf16 MFMA kernel -----------------------------------------------------------------------------------
-// 8 wavefronts; wavefront w owns vocabulary rows [block*128 + 16w, +16) against all 128 columns (8 MFMA
-// column tiles).  Per step of 256 hidden elements: the wavefront's W slice (8 coalesced 16-byte loads, 3
-// steps ahead in registers, nontemporal) goes through its private LDS strip into A fragments as in the
-// draft head; the hidden states of the step (128 columns x 256 k = 64 KB, the B operand of every
-// wavefront) are staged through LDS by all threads together, the next step's in registers meanwhile.
+// 128 vocabulary rows x 128 columns per workgroup.  A wavefront owns RT MFMA row tiles (16 * RT rows)
+// against all 128 columns (8 column tiles): 8 / RT wavefronts per workgroup.  Per step of 256 hidden
+// elements: the wavefront's W slice (8 * RT coalesced 16-byte loads, STAGES - 1 steps ahead in registers,
+// nontemporal) goes through its private LDS strip into A fragments as in the draft head; the hidden states
+// of the step (128 columns x 256 k = 64 KB, the B operand of every wavefront) are staged through LDS by all
+// threads together, the next step's in registers meanwhile.  The kernel is bound by LDS traffic, most of it
+// B fragments (512 KB per step and workgroup with 8 wavefronts).  Measured at V=32000, D=4096, 128 columns:
+// (RT, STAGES) = (1, 2) 75 us, (1, 4) 84 us (spills), (2, 2) 86 us (half the B reads, but one wavefront per
+// SIMD serialises its LDS reads and MFMAs).
 // All loads are unconditional and counted (tail of the k loop peeled, indices clamped), so the waits name
 // the loads that may stay in flight.
-__global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyHeadParams p) {
+template <int RT, int STAGES>
+__global__ __launch_bounds__(64 * kVhWaves / RT) void verify_head_bf16_kernel(VerifyHeadParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int STAGES = 4, NT = kVhCols / 16;
+  constexpr int NT = kVhCols / 16, NW = kVhWaves / RT, NTHREADS = 64 * NW;
+  constexpr int WL = 8 * RT;                       // W loads per step and lane
+  constexpr int HL = kVhCols * 32 / NTHREADS;      // hidden-state pieces per step and thread
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c = lane & 15, g = lane >> 4;
   const int lrow = lane >> 5, lch = lane & 31;
   unsigned char* hs = smem;
-  unsigned char* wst = smem + kVhHsBytes + wave * kVhStripBytes;
-  const int row0 = blockIdx.x * kRowsPerBlock + wave * 16;
+  unsigned char* wst = smem + kVhHsBytes + wave * (RT * kVhStripBytes);
+  const int row0 = blockIdx.x * kRowsPerBlock + wave * 16 * RT;
   const int total_steps = p.D / 256;  // the host guarantees D % (256 * STAGES) == 0
 
   // byte offsets (32 bits: the host checks that the matrices are smaller than 4 GB) from two base pointers
   const unsigned char* wbase = (const unsigned char*)p.w + lch * 16;
-  unsigned int woff[8];
+  unsigned int woff[WL];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
+  for (int j = 0; j < WL; ++j) {
     int row = row0 + 2 * j + lrow;
     row = row < p.V ? row : p.V - 1;  // the ragged last block re-reads the last row
     woff[j] = (unsigned int)row * (unsigned int)(p.D * 2);
   }
-  // hidden-state staging: thread -> 8 pieces of 16 bytes; piece idx = tid + 512u: column idx >> 5, chunk idx & 31
+  // hidden-state staging: piece idx = tid + NTHREADS * u: column idx >> 5, 16-byte chunk idx & 31
   const unsigned char* hbase = (const unsigned char*)p.hidden + (size_t)p.col0 * p.D * 2 + (tid & 31) * 16;
-  unsigned int hoff[8];
-  const int hdst0 = (tid >> 5) * kVhRowPitch + (tid & 31) * 16;  // piece u lands 16 columns further: + u * 16 * pitch
+  unsigned int hoff[HL];
+  const int hdst0 = (tid >> 5) * kVhRowPitch + (tid & 31) * 16;  // piece u lands NTHREADS / 32 columns further
 #pragma unroll
-  for (int u = 0; u < 8; ++u) {
-    const int m = (tid >> 5) + 16 * u;
+  for (int u = 0; u < HL; ++u) {
+    const int m = (tid >> 5) + (NTHREADS / 32) * u;
     const int col = m < p.cols ? m : p.cols - 1;  // columns past the end repeat the last one (never read back)
     hoff[u] = (unsigned int)col * (unsigned int)(p.D * 2);
   }
-  u32x4 hreg[8];
+  u32x4 hreg[HL];
   auto hs_request = [&](int step) __attribute__((always_inline)) {
     const int st = step < total_steps ? step : total_steps - 1;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) hreg[u] = *(const u32x4*)(hbase + hoff[u] + (unsigned int)st * 512u);
+    for (int u = 0; u < HL; ++u) hreg[u] = *(const u32x4*)(hbase + hoff[u] + (unsigned int)st * 512u);
     __builtin_amdgcn_sched_barrier(0);
   };
-  u32x4 v[STAGES][8];
+  u32x4 v[STAGES][WL];
   auto w_request = [&](int step, auto stage_tag) __attribute__((always_inline)) {
     constexpr int ST = decltype(stage_tag)::value;
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < WL; ++j)
       v[ST][j] = __builtin_nontemporal_load((const u32x4*)(wbase + woff[j] + (unsigned int)step * 512u));
     __builtin_amdgcn_sched_barrier(0);
   };
-  f32x4 acc[NT];
+  f32x4 acc[RT][NT];
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[rt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
   auto consume = [&](auto stage_tag) __attribute__((always_inline)) {
     constexpr int ST = decltype(stage_tag)::value;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) *(u32x4*)(wst + (2 * j + lrow) * kVhRowPitch + lch * 16) = v[ST][j];
+    for (int j = 0; j < WL; ++j) *(u32x4*)(wst + (2 * j + lrow) * kVhRowPitch + lch * 16) = v[ST][j];
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-      const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(wst + c * kVhRowPitch + kk * 64 + g * 16));
+      bf16x8 a[RT];
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+        a[rt] = __builtin_bit_cast(bf16x8, *(const u32x4*)(wst + (rt * 16 + c) * kVhRowPitch + kk * 64 + g * 16));
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         const bf16x8 b = __builtin_bit_cast(bf16x8, *(const u32x4*)(hs + (nt * 16 + c) * kVhRowPitch + kk * 64 + g * 16));
-        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[nt], 0, 0, 0);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) acc[rt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt], b, acc[rt][nt], 0, 0, 0);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -113,7 +128,7 @@ __global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyH
     constexpr bool REFILL = decltype(refill_tag)::value;
     lds_barrier();  // every wavefront is done with the previous step's hidden states
 #pragma unroll
-    for (int u = 0; u < 8; ++u) *(u32x4*)(hs + (hdst0 + u * 16 * kVhRowPitch)) = hreg[u];
+    for (int u = 0; u < HL; ++u) *(u32x4*)(hs + (hdst0 + u * (NTHREADS / 32) * kVhRowPitch)) = hreg[u];
     lds_barrier();
     hs_request(i + 1);
     if constexpr (REFILL) w_request(i + STAGES - 1, std::integral_constant<int, (ST + STAGES - 1) % STAGES>{});
@@ -121,9 +136,9 @@ __global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyH
   };
 
   hs_request(0);
-  w_request(0, std::integral_constant<int, 0>{});
-  w_request(1, std::integral_constant<int, 1>{});
-  w_request(2, std::integral_constant<int, 2>{});
+  [&]<int... SS>(std::integer_sequence<int, SS...>) {
+    (w_request(SS, std::integral_constant<int, SS>{}), ...);
+  }(std::make_integer_sequence<int, STAGES - 1>{});
   const int nblk = total_steps / STAGES;
   for (int blk = 0; blk + 1 < nblk; ++blk) {
     [&]<int... SS>(std::integer_sequence<int, SS...>) {
@@ -132,31 +147,32 @@ __global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyH
   }
   {
     const int i0 = (nblk - 1) * STAGES;  // last block: only its first step still has something to prefetch
-    step_fn(i0 + 0, std::integral_constant<int, 0>{}, std::true_type{});
-    step_fn(i0 + 1, std::integral_constant<int, 1>{}, std::false_type{});
-    step_fn(i0 + 2, std::integral_constant<int, 2>{}, std::false_type{});
-    step_fn(i0 + 3, std::integral_constant<int, 3>{}, std::false_type{});
+    [&]<int... SS>(std::integer_sequence<int, SS...>) {
+      (step_fn(i0 + SS, std::integral_constant<int, SS>{}, std::integral_constant<bool, SS == 0>{}), ...);
+    }(std::make_integer_sequence<int, STAGES>{});
   }
 
   // ---- logit block -> LDS (over the staging area), best key per column ------------------------------------
   __syncthreads();
   float* zbuf = (float*)smem;
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    f32x4 z;
+  for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) z[i] = (row0 + g * 4 + i) < p.V ? acc[nt][i] : -INFINITY;
-    *(f32x4*)(zbuf + (nt * 16 + c) * kVhZStride + wave * 16 + g * 4) = z;
-  }
+    for (int nt = 0; nt < NT; ++nt) {
+      f32x4 z;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) z[i] = (row0 + rt * 16 + g * 4 + i) < p.V ? acc[rt][nt][i] : -INFINITY;
+      *(f32x4*)(zbuf + (nt * 16 + c) * kVhZStride + wave * 16 * RT + rt * 16 + g * 4) = z;
+    }
   __syncthreads();
   const int row_base = blockIdx.x * kRowsPerBlock;
   if (p.logits_out) {
-    for (int idx = tid; idx < p.cols * kRowsPerBlock; idx += 64 * kVhWaves) {
+    for (int idx = tid; idx < p.cols * kRowsPerBlock; idx += NTHREADS) {
       const int m = idx / kRowsPerBlock, r = idx % kRowsPerBlock;
       if (row_base + r < p.V) p.logits_out[(size_t)(p.col0 + m) * p.V + row_base + r] = zbuf[m * kVhZStride + r];
     }
   }
-  for (int m = wave; m < p.cols; m += kVhWaves) {
+  for (int m = wave; m < p.cols; m += NW) {
     const float z0 = zbuf[m * kVhZStride + lane], z1 = zbuf[m * kVhZStride + lane + 64];
     const int id0 = row_base + lane, id1 = row_base + lane + 64;
     const unsigned long long a = id0 < p.V ? rank_key(z0, (unsigned)id0) : 0ull;
@@ -282,13 +298,13 @@ extern "C" int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void
   p.pkey = ctx->vh_pkey; p.logits_out = logits_out; p.n_nodes = n_nodes; p.max_nodes = max_nodes;
   p.target = target_argmax;
   const long long cols_total = (long long)B * max_nodes;
-  const bool wide = dt == CTCSPEC_BF16 && D % 1024 == 0 && (long long)V * D * 2 < (1LL << 32) &&
+  const bool wide = dt == CTCSPEC_BF16 && D % (256 * kVhStages) == 0 && (long long)V * D * 2 < (1LL << 32) &&
                     cols_total * D * 2 < (1LL << 32);
   const int lds = kVhHsBytes + kVhWaves * kVhStripBytes;
   if (wide) {
     static bool lds_allowed = false;  // raising the limit is needed once per process
     if (!lds_allowed) {
-      CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)verify_head_bf16_kernel,
+      CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)verify_head_bf16_kernel<kVhRowTiles, kVhStages>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds));
       lds_allowed = true;
     }
@@ -297,7 +313,8 @@ extern "C" int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void
     p.col0 = (int)col0;
     p.cols = (int)(cols_total - col0 < kVhCols ? cols_total - col0 : kVhCols);
     if (wide) {
-      hipLaunchKernelGGL(verify_head_bf16_kernel, dim3(p.n_blocks), dim3(64 * kVhWaves), lds, ctx->stream, p);
+      hipLaunchKernelGGL((verify_head_bf16_kernel<kVhRowTiles, kVhStages>), dim3(p.n_blocks), dim3(64 * kVhWaves / kVhRowTiles), lds,
+                         ctx->stream, p);
     } else {
       hipLaunchKernelGGL(verify_head_clear_kernel, dim3(64), dim3(256), 0, ctx->stream, p);
       if (dt == CTCSPEC_BF16)
