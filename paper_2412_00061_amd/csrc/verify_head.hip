@@ -3,7 +3,7 @@
 //
 // The head is the same stream over a [V, D] weight matrix as the draft head, but with up to 128 columns
 // (one per tree node) instead of 8, and all that is kept of a column is its best (logit, id) key:
-//   * verify_head_bf16_kernel    - bf16, D a multiple of 512: MFMA, 128 vocabulary rows x 128 columns
+//   * verify_head_bf16_kernel    - bf16, D a multiple of 256: MFMA, 128 vocabulary rows x 128 columns
 //                                  per workgroup, weights read once per block of 128 columns
 //   * verify_head_generic_kernel - any dtype/shape: plain fp32 FMA, one atomic max per (row block, column)
 //   * verify_head_merge_kernel   - best key over the row blocks -> token id, -1 for rows without a node
@@ -15,14 +15,14 @@
 namespace ctcspec {
 
 constexpr int kVhCols = kVerifyCols;            // columns (tree nodes) per pass over the weights
-constexpr int kVhWaves = 8;                     // 16-row tiles per workgroup
-constexpr int kVhRowTiles = 1;                  // of them per wavefront
-constexpr int kVhStages = 2;                    // W register stages (prefetch distance + 1)
-constexpr int kVhRowPitch = 512 + 16;           // bytes per staged row: 256 bf16 + pad (conflict-free b128 reads)
-constexpr int kVhStripBytes = 16 * kVhRowPitch; // W strip of one wavefront: 16 rows x 256 k
-constexpr int kVhHsBytes = kVhCols * kVhRowPitch;  // hidden-state chunk: 128 columns x 256 k
+constexpr int kVhWaves = 8;
+constexpr int kVhStages = 3;                    // W register stages: prefetch distance + 1
+constexpr int kVhRowPitch = 512 + 32;           // bytes per staged row: 256 bf16 + pad; fragment reads (16 rows x 4
+                                                // chunks per instruction) measure conflict-free at this pitch, 12% slower at +16
+constexpr int kVhHsBytes = kVhCols * kVhRowPitch;       // hidden states of a step: 128 columns x 256 k
+constexpr int kVhWsBytes = kRowsPerBlock * kVhRowPitch; // W tile of a step: 128 rows x 256 k
 constexpr int kVhZStride = kRowsPerBlock + 4;   // floats per column of the logit block
-static_assert(kVhCols * kVhZStride * 4 <= kVhHsBytes + kVhWaves * kVhStripBytes, "logit block fits the staging area");
+static_assert(kVhCols * kVhZStride * 4 <= kVhHsBytes + kVhWsBytes, "logit block fits the staging area");
 
 struct VerifyHeadParams {
   const void* hidden;   // [cols_total][D], this pass starts at column col0
@@ -38,141 +38,157 @@ struct VerifyHeadParams {
 };
 
 // ---- bf16 MFMA kernel -----------------------------------------------------------------------------------
-// 128 vocabulary rows x 128 columns per workgroup.  A wavefront owns RT MFMA row tiles (16 * RT rows)
-// against all 128 columns (8 column tiles): 8 / RT wavefronts per workgroup.  Per step of 256 hidden
-// elements: the wavefront's W slice (8 * RT coalesced 16-byte loads, STAGES - 1 steps ahead in registers,
-// nontemporal) goes through its private LDS strip into A fragments as in the draft head; the hidden states
-// of the step (128 columns x 256 k = 64 KB, the B operand of every wavefront) are staged through LDS by all
-// threads together, the next step's in registers meanwhile.  The kernel is bound by LDS traffic, most of it
-// B fragments (512 KB per step and workgroup with 8 wavefronts).  Measured at V=32000, D=4096, 128 columns:
-// (RT, STAGES) = (1, 2) 75 us, (1, 4) 84 us (spills), (2, 2) 86 us (half the B reads, but one wavefront per
-// SIMD serialises its LDS reads and MFMAs).
-// All loads are unconditional and counted (tail of the k loop peeled, indices clamped), so the waits name
-// the loads that may stay in flight.
-template <int RT, int STAGES>
-__global__ __launch_bounds__(64 * kVhWaves / RT) void verify_head_bf16_kernel(VerifyHeadParams p) {
+// 128 vocabulary rows x 128 columns per workgroup, 8 wavefronts in a 2 x 4 grid: wavefront (wr, wc) owns
+// rows [64 wr, +64) x columns [32 wc, +32) - 4 x 2 MFMA tiles.  Per step of 256 hidden elements both
+// operands go through LDS: the W tile (128 rows x 512 B, nontemporal, the A operand) and the hidden states
+// of the step (128 columns x 512 B, the B operand) are fetched by all threads together with coalesced
+// 16-byte loads, held in registers until the previous step is done with, and written to LDS; a wavefront then
+// reads 4 A and 2 B fragments per 32 k for 8 MFMAs.  LDS bandwidth bounds this kernel (b128 reads sustain
+// about 70 B per clock and CU): the 2 x 4 grid reads 384 KB per step and workgroup where one row tile x all
+// columns per wavefront (the first version) read 576 KB - 75 us then, 128 columns at V=32000, D=4096.
+// All loads are unconditional and counted (indices clamped), so the waits name the loads that stay in flight.
+template <int WS>
+__global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyHeadParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int NT = kVhCols / 16, NW = kVhWaves / RT, NTHREADS = 64 * NW;
-  constexpr int WL = 8 * RT;                       // W loads per step and lane
-  constexpr int HL = kVhCols * 32 / NTHREADS;      // hidden-state pieces per step and thread
+  constexpr int NTHREADS = 64 * kVhWaves, PIECES = kVhCols * 32 / NTHREADS;  // 16-byte pieces per thread and tile
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wr = wave >> 2, wc = wave & 3;
   const int c = lane & 15, g = lane >> 4;
-  const int lrow = lane >> 5, lch = lane & 31;
-  unsigned char* hs = smem;
-  unsigned char* wst = smem + kVhHsBytes + wave * (RT * kVhStripBytes);
-  const int row0 = blockIdx.x * kRowsPerBlock + wave * 16 * RT;
-  const int total_steps = p.D / 256;  // the host guarantees D % (256 * STAGES) == 0
+  unsigned char* hs = smem;                 // [128 columns][pitch]
+  unsigned char* ws = smem + kVhHsBytes;    // [128 rows][pitch]
+  const int row_base = blockIdx.x * kRowsPerBlock;
+  const int total_steps = p.D / 256;
 
-  // byte offsets (32 bits: the host checks that the matrices are smaller than 4 GB) from two base pointers
-  const unsigned char* wbase = (const unsigned char*)p.w + lch * 16;
-  unsigned int woff[WL];
-#pragma unroll
-  for (int j = 0; j < WL; ++j) {
-    int row = row0 + 2 * j + lrow;
-    row = row < p.V ? row : p.V - 1;  // the ragged last block re-reads the last row
-    woff[j] = (unsigned int)row * (unsigned int)(p.D * 2);
-  }
-  // hidden-state staging: piece idx = tid + NTHREADS * u: column idx >> 5, 16-byte chunk idx & 31
+  // piece u of a thread: tile row (tid >> 5) + 16 u, 16-byte chunk tid & 31; byte offsets in 32 bits (the host
+  // checks that the matrices are smaller than 4 GB)
+  const unsigned char* wbase = (const unsigned char*)p.w + (tid & 31) * 16;
   const unsigned char* hbase = (const unsigned char*)p.hidden + (size_t)p.col0 * p.D * 2 + (tid & 31) * 16;
-  unsigned int hoff[HL];
-  const int hdst0 = (tid >> 5) * kVhRowPitch + (tid & 31) * 16;  // piece u lands NTHREADS / 32 columns further
+  unsigned int woff[PIECES], hoff[PIECES];
+  const int dst0 = (tid >> 5) * kVhRowPitch + (tid & 31) * 16;
 #pragma unroll
-  for (int u = 0; u < HL; ++u) {
-    const int m = (tid >> 5) + (NTHREADS / 32) * u;
-    const int col = m < p.cols ? m : p.cols - 1;  // columns past the end repeat the last one (never read back)
+  for (int u = 0; u < PIECES; ++u) {
+    const int r = (tid >> 5) + (NTHREADS / 32) * u;
+    int row = row_base + r;
+    row = row < p.V ? row : p.V - 1;            // the ragged last block re-reads the last row
+    const int col = r < p.cols ? r : p.cols - 1;  // columns past the end repeat the last one (never read back)
+    woff[u] = (unsigned int)row * (unsigned int)(p.D * 2);
     hoff[u] = (unsigned int)col * (unsigned int)(p.D * 2);
   }
-  u32x4 hreg[HL];
-  auto hs_request = [&](int step) __attribute__((always_inline)) {
-    const int st = step < total_steps ? step : total_steps - 1;
+  // The hidden states are fetched one step ahead, W is fetched WS - 1 steps ahead into rotating register
+  // stages.  A request past the last step still issues its loads, so that every wait counts the same loads: it
+  // re-reads the hidden states of the last step (in L2, no HBM traffic) and nothing consumes the result.
+  u32x4 wreg[WS][PIECES], hreg[PIECES];
+  auto request_h = [&](int step) __attribute__((always_inline)) {
+    const unsigned int st = (unsigned int)(step < total_steps ? step : total_steps - 1) * 512u;
 #pragma unroll
-    for (int u = 0; u < HL; ++u) hreg[u] = *(const u32x4*)(hbase + hoff[u] + (unsigned int)st * 512u);
-    __builtin_amdgcn_sched_barrier(0);
+    for (int u = 0; u < PIECES; ++u) hreg[u] = *(const u32x4*)(hbase + hoff[u] + st);
   };
-  u32x4 v[STAGES][WL];
-  auto w_request = [&](int step, auto stage_tag) __attribute__((always_inline)) {
-    constexpr int ST = decltype(stage_tag)::value;
+  auto request_w = [&](int step, auto stage) __attribute__((always_inline)) {
+    constexpr int S = decltype(stage)::value;
+    const bool valid = step < total_steps;
+    const unsigned char* base = valid ? wbase : hbase;
+    const unsigned int st = (unsigned int)(valid ? step : total_steps - 1) * 512u;
 #pragma unroll
-    for (int j = 0; j < WL; ++j)
-      v[ST][j] = __builtin_nontemporal_load((const u32x4*)(wbase + woff[j] + (unsigned int)step * 512u));
-    __builtin_amdgcn_sched_barrier(0);
+    for (int u = 0; u < PIECES; ++u)
+      wreg[S][u] = __builtin_nontemporal_load((const u32x4*)(base + (valid ? woff[u] : hoff[u]) + st));
   };
-  f32x4 acc[RT][NT];
+  f32x4 acc[4][2];
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt)
+  for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) acc[rt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  auto consume = [&](auto stage_tag) __attribute__((always_inline)) {
-    constexpr int ST = decltype(stage_tag)::value;
+    for (int ct = 0; ct < 2; ++ct) acc[rt][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int aoff = (wr * 64 + c) * kVhRowPitch + g * 16, boff = (wc * 32 + c) * kVhRowPitch + g * 16;
+
+  auto commit = [&](auto stage) __attribute__((always_inline)) {
+    constexpr int S = decltype(stage)::value;
 #pragma unroll
-    for (int j = 0; j < WL; ++j) *(u32x4*)(wst + (2 * j + lrow) * kVhRowPitch + lch * 16) = v[ST][j];
+    for (int u = 0; u < PIECES; ++u) {
+      *(u32x4*)(hs + (dst0 + u * (NTHREADS / 32) * kVhRowPitch)) = hreg[u];
+      *(u32x4*)(ws + (dst0 + u * (NTHREADS / 32) * kVhRowPitch)) = wreg[S][u];
+    }
+  };
+  auto compute = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-      bf16x8 a[RT];
+      bf16x8 a[4], b[2];
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
-        a[rt] = __builtin_bit_cast(bf16x8, *(const u32x4*)(wst + (rt * 16 + c) * kVhRowPitch + kk * 64 + g * 16));
+      for (int rt = 0; rt < 4; ++rt)
+        a[rt] = __builtin_bit_cast(bf16x8, *(const u32x4*)(ws + (aoff + rt * 16 * kVhRowPitch + kk * 64)));
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const bf16x8 b = __builtin_bit_cast(bf16x8, *(const u32x4*)(hs + (nt * 16 + c) * kVhRowPitch + kk * 64 + g * 16));
+      for (int ct = 0; ct < 2; ++ct)
+        b[ct] = __builtin_bit_cast(bf16x8, *(const u32x4*)(hs + (boff + ct * 16 * kVhRowPitch + kk * 64)));
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) acc[rt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt], b, acc[rt][nt], 0, 0, 0);
-      }
+      for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+          acc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt], b[ct], acc[rt][ct], 0, 0, 0);
     }
+  };
+  auto do_step = [&](int step, auto stage) __attribute__((always_inline)) {
+    constexpr int S = decltype(stage)::value;
+    if (step > 0) lds_barrier();  // every wavefront is done with the previous step's tiles
+    commit(stage);
+    lds_barrier();
+    request_h(step + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    request_w(step + WS - 1, std::integral_constant<int, (S + WS - 1) % WS>{});
+    __builtin_amdgcn_sched_barrier(0);
+    compute();
     __builtin_amdgcn_sched_barrier(0);
   };
-  // one step: publish its hidden states, request the next step's, refill the W stage freed last step
-  auto step_fn = [&](int i, auto stage_tag, auto refill_tag) __attribute__((always_inline)) {
-    constexpr int ST = decltype(stage_tag)::value;
-    constexpr bool REFILL = decltype(refill_tag)::value;
-    lds_barrier();  // every wavefront is done with the previous step's hidden states
-#pragma unroll
-    for (int u = 0; u < HL; ++u) *(u32x4*)(hs + (hdst0 + u * (NTHREADS / 32) * kVhRowPitch)) = hreg[u];
-    lds_barrier();
-    hs_request(i + 1);
-    if constexpr (REFILL) w_request(i + STAGES - 1, std::integral_constant<int, (ST + STAGES - 1) % STAGES>{});
-    consume(stage_tag);
-  };
 
-  hs_request(0);
-  [&]<int... SS>(std::integer_sequence<int, SS...>) {
-    (w_request(SS, std::integral_constant<int, SS>{}), ...);
-  }(std::make_integer_sequence<int, STAGES - 1>{});
-  const int nblk = total_steps / STAGES;
-  for (int blk = 0; blk + 1 < nblk; ++blk) {
-    [&]<int... SS>(std::integer_sequence<int, SS...>) {
-      (step_fn(blk * STAGES + SS, std::integral_constant<int, SS>{}, std::true_type{}), ...);
-    }(std::make_integer_sequence<int, STAGES>{});
+  // The pipelined loop takes WS steps per trip with no exit in between (an exit inside the trip gives the loop
+  // head a second, differently ordered set of loads in flight and the waits there fall back to draining
+  // everything), so the total_steps % WS steps that do not fill a trip run first, unpipelined.
+  const int lead = total_steps % WS;
+  for (int i = 0; i < lead; ++i) {
+    request_w(i, std::integral_constant<int, 0>{});
+    request_h(i);
+    if (i > 0) lds_barrier();
+    commit(std::integral_constant<int, 0>{});
+    lds_barrier();
+    compute();
   }
-  {
-    const int i0 = (nblk - 1) * STAGES;  // last block: only its first step still has something to prefetch
-    [&]<int... SS>(std::integer_sequence<int, SS...>) {
-      (step_fn(i0 + SS, std::integral_constant<int, SS>{}, std::integral_constant<bool, SS == 0>{}), ...);
-    }(std::make_integer_sequence<int, STAGES>{});
+  if (lead < total_steps) {
+    // same issue order as in the loop (W of a step before its hidden states), kept by the scheduling fences
+    __builtin_amdgcn_sched_barrier(0);
+    request_w(lead, std::integral_constant<int, 0>{});
+    __builtin_amdgcn_sched_barrier(0);
+    request_h(lead);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (WS > 2) request_w(lead + 1, std::integral_constant<int, 1>{});
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (WS > 3) request_w(lead + 2, std::integral_constant<int, 2>{});
+    __builtin_amdgcn_sched_barrier(0);
+    for (int i = lead; i < total_steps; i += WS) {
+      do_step(i, std::integral_constant<int, 0>{});
+      do_step(i + 1, std::integral_constant<int, 1 % WS>{});
+      if constexpr (WS > 2) do_step(i + 2, std::integral_constant<int, 2 % WS>{});
+      if constexpr (WS > 3) do_step(i + 3, std::integral_constant<int, 3 % WS>{});
+    }
   }
 
   // ---- logit block -> LDS (over the staging area), best key per column ------------------------------------
   __syncthreads();
   float* zbuf = (float*)smem;
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt)
+  for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
+    for (int ct = 0; ct < 2; ++ct) {
       f32x4 z;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) z[i] = (row0 + rt * 16 + g * 4 + i) < p.V ? acc[rt][nt][i] : -INFINITY;
-      *(f32x4*)(zbuf + (nt * 16 + c) * kVhZStride + wave * 16 * RT + rt * 16 + g * 4) = z;
+      for (int i = 0; i < 4; ++i) z[i] = (row_base + wr * 64 + rt * 16 + g * 4 + i) < p.V ? acc[rt][ct][i] : -INFINITY;
+      *(f32x4*)(zbuf + (wc * 32 + ct * 16 + c) * kVhZStride + wr * 64 + rt * 16 + g * 4) = z;
     }
   __syncthreads();
-  const int row_base = blockIdx.x * kRowsPerBlock;
   if (p.logits_out) {
     for (int idx = tid; idx < p.cols * kRowsPerBlock; idx += NTHREADS) {
       const int m = idx / kRowsPerBlock, r = idx % kRowsPerBlock;
       if (row_base + r < p.V) p.logits_out[(size_t)(p.col0 + m) * p.V + row_base + r] = zbuf[m * kVhZStride + r];
     }
   }
-  for (int m = wave; m < p.cols; m += NW) {
+  for (int m = wave; m < p.cols; m += kVhWaves) {
     const float z0 = zbuf[m * kVhZStride + lane], z1 = zbuf[m * kVhZStride + lane + 64];
     const int id0 = row_base + lane, id1 = row_base + lane + 64;
     const unsigned long long a = id0 < p.V ? rank_key(z0, (unsigned)id0) : 0ull;
@@ -298,13 +314,13 @@ extern "C" int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void
   p.pkey = ctx->vh_pkey; p.logits_out = logits_out; p.n_nodes = n_nodes; p.max_nodes = max_nodes;
   p.target = target_argmax;
   const long long cols_total = (long long)B * max_nodes;
-  const bool wide = dt == CTCSPEC_BF16 && D % (256 * kVhStages) == 0 && (long long)V * D * 2 < (1LL << 32) &&
+  const bool wide = dt == CTCSPEC_BF16 && D % 256 == 0 && (long long)V * D * 2 < (1LL << 32) &&
                     cols_total * D * 2 < (1LL << 32);
-  const int lds = kVhHsBytes + kVhWaves * kVhStripBytes;
+  const int lds = kVhHsBytes + kVhWsBytes;
   if (wide) {
     static bool lds_allowed = false;  // raising the limit is needed once per process
     if (!lds_allowed) {
-      CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)verify_head_bf16_kernel<kVhRowTiles, kVhStages>,
+      CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)verify_head_bf16_kernel<kVhStages>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds));
       lds_allowed = true;
     }
@@ -313,8 +329,7 @@ extern "C" int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void
     p.col0 = (int)col0;
     p.cols = (int)(cols_total - col0 < kVhCols ? cols_total - col0 : kVhCols);
     if (wide) {
-      hipLaunchKernelGGL((verify_head_bf16_kernel<kVhRowTiles, kVhStages>), dim3(p.n_blocks), dim3(64 * kVhWaves / kVhRowTiles), lds,
-                         ctx->stream, p);
+      hipLaunchKernelGGL(verify_head_bf16_kernel<kVhStages>, dim3(p.n_blocks), dim3(64 * kVhWaves), lds, ctx->stream, p);
     } else {
       hipLaunchKernelGGL(verify_head_clear_kernel, dim3(64), dim3(256), 0, ctx->stream, p);
       if (dt == CTCSPEC_BF16)
