@@ -51,6 +51,7 @@ struct ctcspec_ctx {
   int lm_profile_valid;
   hipEvent_t lm_ev0, lm_ev1;
   // verifier head
+  const void* zeros;            // 256 bytes of zeros
   unsigned long long* vh_pkey;  // [lm_max_blocks][kVerifyCols] best (logit, id) key per row block and column
   // collapse / tree
   unsigned char* collapse_ws;   // [max_batch][kCollapseWsBytesPerSeq]

@@ -68,6 +68,7 @@ extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec
   size_t o_psum = carve((size_t)ctx->lm_max_blocks * kMaxCols * sizeof(float));
   size_t o_pkey = carve((size_t)ctx->lm_max_blocks * kMaxCols * kMaxTopk * sizeof(unsigned long long));
   size_t o_vh = carve((size_t)ctx->lm_max_blocks * kVerifyCols * sizeof(unsigned long long));
+  size_t o_zero = carve(256);
   size_t o_coll = carve((size_t)lim->max_batch * kCollapseWsBytesPerSeq);
   // attention partials: one slot of 128 query rows per (sequence, head, key split)
   const size_t attn_rows = (size_t)ctx->attn_units * 128;
@@ -82,10 +83,17 @@ extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec
                 hipGetErrorString(e));
   }
   unsigned char* base = (unsigned char*)ctx->ws;
+  e = hipMemset(base + o_zero, 0, 256);  // read by loads that must fetch something harmless
+  if (e != hipSuccess) {
+    hipFree(ctx->ws);
+    delete ctx;
+    return fail(nullptr, CTCSPEC_EHIP, "hipMemset failed: %s", hipGetErrorString(e));
+  }
   ctx->lm_pmax = (float*)(base + o_pmax);
   ctx->lm_psum = (float*)(base + o_psum);
   ctx->lm_pkey = (unsigned long long*)(base + o_pkey);
   ctx->vh_pkey = (unsigned long long*)(base + o_vh);
+  ctx->zeros = base + o_zero;
   ctx->collapse_ws = base + o_coll;
   ctx->attn_po = (float*)(base + o_po);
   ctx->attn_pm = (float*)(base + o_pm);

@@ -3,7 +3,7 @@
 //
 // The head is the same stream over a [V, D] weight matrix as the draft head, but with up to 128 columns
 // (one per tree node) instead of 8, and all that is kept of a column is its best (logit, id) key:
-//   * verify_head_bf16_kernel    - bf16, D a multiple of 256: MFMA, 128 vocabulary rows x 128 columns
+//   * verify_head_bf16_kernel    - bf16, D a multiple of 128: MFMA, 128 vocabulary rows x 128 columns
 //                                  per workgroup, weights read once per block of 128 columns
 //   * verify_head_generic_kernel - any dtype/shape: plain fp32 FMA, one atomic max per (row block, column)
 //   * verify_head_merge_kernel   - best key over the row blocks -> token id, -1 for rows without a node
@@ -16,13 +16,15 @@ namespace ctcspec {
 
 constexpr int kVhCols = kVerifyCols;            // columns (tree nodes) per pass over the weights
 constexpr int kVhWaves = 8;
-constexpr int kVhStages = 3;                    // W register stages: prefetch distance + 1
-constexpr int kVhRowPitch = 512 + 32;           // bytes per staged row: 256 bf16 + pad; fragment reads (16 rows x 4
-                                                // chunks per instruction) measure conflict-free at this pitch, 12% slower at +16
-constexpr int kVhHsBytes = kVhCols * kVhRowPitch;       // hidden states of a step: 128 columns x 256 k
-constexpr int kVhWsBytes = kRowsPerBlock * kVhRowPitch; // W tile of a step: 128 rows x 256 k
+constexpr int kVhDist = 4;                      // prefetch distance in steps = register stages per operand
+constexpr int kVhStepK = 128;                   // hidden elements per step
+constexpr int kVhRowPitch = 2 * kVhStepK + 32;  // bytes per staged row: 128 bf16 + pad; fragment reads (16 rows x 4
+                                                // chunks per instruction) measure conflict-free at this pitch
+constexpr int kVhTileBytes = 128 * kVhRowPitch; // one operand of one step: 128 rows (or columns) x 128 k
+constexpr int kVhLdsBytes = 4 * kVhTileBytes;   // W and hidden-state tile, double-buffered
 constexpr int kVhZStride = kRowsPerBlock + 4;   // floats per column of the logit block
-static_assert(kVhCols * kVhZStride * 4 <= kVhHsBytes + kVhWsBytes, "logit block fits the staging area");
+static_assert(kVhCols == 128 && kRowsPerBlock == 128, "tile shape");
+static_assert(kVhCols * kVhZStride * 4 <= kVhLdsBytes, "logit block fits the staging area");
 
 struct VerifyHeadParams {
   const void* hidden;   // [cols_total][D], this pass starts at column col0
@@ -32,6 +34,7 @@ struct VerifyHeadParams {
   int n_blocks;         // row blocks of 128
   unsigned long long* pkey;  // [n_blocks][kVhCols] best key per (row block, column of the pass)
   float* logits_out;    // [cols_total][V] or null
+  const void* zeros;    // 256 bytes of zeros
   const int32_t* n_nodes;  // [B]
   int max_nodes;
   int32_t* target;      // [cols_total]
@@ -39,59 +42,76 @@ struct VerifyHeadParams {
 
 // ---- bf16 MFMA kernel -----------------------------------------------------------------------------------
 // 128 vocabulary rows x 128 columns per workgroup, 8 wavefronts in a 2 x 4 grid: wavefront (wr, wc) owns
-// rows [64 wr, +64) x columns [32 wc, +32) - 4 x 2 MFMA tiles.  Per step of 256 hidden elements both
-// operands go through LDS: the W tile (128 rows x 512 B, nontemporal, the A operand) and the hidden states
-// of the step (128 columns x 512 B, the B operand) are fetched by all threads together with coalesced
-// 16-byte loads, held in registers until the previous step is done with, and written to LDS; a wavefront then
-// reads 4 A and 2 B fragments per 32 k for 8 MFMAs.  LDS bandwidth bounds this kernel (b128 reads sustain
-// about 70 B per clock and CU): the 2 x 4 grid reads 384 KB per step and workgroup where one row tile x all
-// columns per wavefront (the first version) read 576 KB - 75 us then, 128 columns at V=32000, D=4096.
+// rows [64 wr, +64) x columns [32 wc, +32) - 4 x 2 MFMA tiles.  Per step of 128 hidden elements both
+// operands go through LDS: the W tile (128 rows x 256 B, nontemporal, the A operand) and the hidden states
+// of the step (128 columns x 256 B, the B operand) are fetched by all threads together with coalesced
+// 16-byte loads, DIST steps ahead, into rotating register stages, and written to one of two LDS buffers
+// while the other one is computed from: one barrier per step.  A wavefront reads 4 A and 2 B fragments per
+// 32 k for 8 MFMAs; the fragments of the next 32 k are read, and the tiles of the next step are written,
+// between the MFMAs of the current 32 k (the instruction order is pinned with scheduling groups).
+// What bounds it (measured, one CU): b128 fragment reads at 128 B per clock, b128 writes at 79 B per clock -
+// per step 192 KB read + 64 KB written = 2300 clocks against 1024 clocks of MFMA and 1.35 us (3200 clocks)
+// for the 32 KB of W at the HBM rate, so the LDS work fits under the stream only if nothing serialises.
 // All loads are unconditional and counted (indices clamped), so the waits name the loads that stay in flight.
-template <int WS>
+typedef __attribute__((address_space(1))) u32x4 GlobalU32x4;  // a pointer made from an integer is generic otherwise
+template <int DIST>
 __global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyHeadParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int NTHREADS = 64 * kVhWaves, PIECES = kVhCols * 32 / NTHREADS;  // 16-byte pieces per thread and tile
+  constexpr int NTHREADS = 64 * kVhWaves;
+  constexpr int PIECES = 128 * (2 * kVhStepK / 16) / NTHREADS;  // 16-byte pieces per thread and tile: 4
+  constexpr int ROWS_PER_PIECE = NTHREADS / 16;                 // 32
+  constexpr int KK = kVhStepK / 32;                             // MFMA k-blocks per step
+  constexpr int TRIP = DIST % 2 == 0 ? DIST : 2 * DIST;         // steps per loop trip: stage and buffer static
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wr = wave >> 2, wc = wave & 3;
   const int c = lane & 15, g = lane >> 4;
-  unsigned char* hs = smem;                 // [128 columns][pitch]
-  unsigned char* ws = smem + kVhHsBytes;    // [128 rows][pitch]
   const int row_base = blockIdx.x * kRowsPerBlock;
-  const int total_steps = p.D / 256;
+  const int total_steps = p.D / kVhStepK;
+  // LDS: buffer b holds the hidden-state tile at 2 b and the W tile at 2 b + 1 (in tiles)
 
-  // piece u of a thread: tile row (tid >> 5) + 16 u, 16-byte chunk tid & 31; byte offsets in 32 bits (the host
+  // piece u of a thread: tile row (tid >> 4) + 32 u, 16-byte chunk tid & 15; byte offsets in 32 bits (the host
   // checks that the matrices are smaller than 4 GB)
-  const unsigned char* wbase = (const unsigned char*)p.w + (tid & 31) * 16;
-  const unsigned char* hbase = (const unsigned char*)p.hidden + (size_t)p.col0 * p.D * 2 + (tid & 31) * 16;
+  const unsigned int lane_off = (tid & 15) * 16;
+  const uintptr_t w_addr = (uintptr_t)p.w, h_addr = (uintptr_t)p.hidden + (size_t)p.col0 * p.D * 2;
+  const uintptr_t z_addr = (uintptr_t)p.zeros;
   unsigned int woff[PIECES], hoff[PIECES];
-  const int dst0 = (tid >> 5) * kVhRowPitch + (tid & 31) * 16;
+  const int dst0 = (tid >> 4) * kVhRowPitch + (tid & 15) * 16;
 #pragma unroll
   for (int u = 0; u < PIECES; ++u) {
-    const int r = (tid >> 5) + (NTHREADS / 32) * u;
+    const int r = (tid >> 4) + ROWS_PER_PIECE * u;
     int row = row_base + r;
     row = row < p.V ? row : p.V - 1;            // the ragged last block re-reads the last row
     const int col = r < p.cols ? r : p.cols - 1;  // columns past the end repeat the last one (never read back)
     woff[u] = (unsigned int)row * (unsigned int)(p.D * 2);
     hoff[u] = (unsigned int)col * (unsigned int)(p.D * 2);
   }
-  // The hidden states are fetched one step ahead, W is fetched WS - 1 steps ahead into rotating register
-  // stages.  A request past the last step still issues its loads, so that every wait counts the same loads: it
-  // re-reads the hidden states of the last step (in L2, no HBM traffic) and nothing consumes the result.
-  u32x4 wreg[WS][PIECES], hreg[PIECES];
-  auto request_h = [&](int step) __attribute__((always_inline)) {
-    const unsigned int st = (unsigned int)(step < total_steps ? step : total_steps - 1) * 512u;
-#pragma unroll
-    for (int u = 0; u < PIECES; ++u) hreg[u] = *(const u32x4*)(hbase + hoff[u] + st);
-  };
-  auto request_w = [&](int step, auto stage) __attribute__((always_inline)) {
+  // A request past the last step still issues its loads, so that every wait counts the same loads: it reads
+  // a 256-byte block of zeros (in L2, no HBM traffic) and nothing computes from the result.
+  u32x4 wreg[DIST][PIECES], hreg[DIST][PIECES];
+  auto request = [&](int step, auto stage) __attribute__((always_inline)) {
     constexpr int S = decltype(stage)::value;
+    // address arithmetic in integers: a select between pointers would become a branch around each load
     const bool valid = step < total_steps;
-    const unsigned char* base = valid ? wbase : hbase;
-    const unsigned int st = (unsigned int)(valid ? step : total_steps - 1) * 512u;
+    const unsigned int mask = valid ? ~0u : 0u;
+    const unsigned int st = ((unsigned int)step * (unsigned int)(2 * kVhStepK)) & mask;
+    const uintptr_t hb = (valid ? h_addr : z_addr) + st, wb = (valid ? w_addr : z_addr) + st;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < PIECES; ++u) hreg[S][u] = *(const GlobalU32x4*)(hb + ((hoff[u] & mask) + lane_off));
 #pragma unroll
     for (int u = 0; u < PIECES; ++u)
-      wreg[S][u] = __builtin_nontemporal_load((const u32x4*)(base + (valid ? woff[u] : hoff[u]) + st));
+      wreg[S][u] = __builtin_nontemporal_load((const GlobalU32x4*)(wb + ((woff[u] & mask) + lane_off)));
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto commit = [&](auto stage, auto buffer) __attribute__((always_inline)) {
+    constexpr int S = decltype(stage)::value, BUF = decltype(buffer)::value;
+    unsigned char* hs = smem + (2 * BUF) * kVhTileBytes;
+    unsigned char* ws = smem + (2 * BUF + 1) * kVhTileBytes;
+#pragma unroll
+    for (int u = 0; u < PIECES; ++u) *(u32x4*)(hs + (dst0 + u * ROWS_PER_PIECE * kVhRowPitch)) = hreg[S][u];
+#pragma unroll
+    for (int u = 0; u < PIECES; ++u) *(u32x4*)(ws + (dst0 + u * ROWS_PER_PIECE * kVhRowPitch)) = wreg[S][u];
   };
   f32x4 acc[4][2];
 #pragma unroll
@@ -99,102 +119,118 @@ __global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyH
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct) acc[rt][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
   const int aoff = (wr * 64 + c) * kVhRowPitch + g * 16, boff = (wc * 32 + c) * kVhRowPitch + g * 16;
-
-  auto commit = [&](auto stage) __attribute__((always_inline)) {
-    constexpr int S = decltype(stage)::value;
-#pragma unroll
-    for (int u = 0; u < PIECES; ++u) {
-      *(u32x4*)(hs + (dst0 + u * (NTHREADS / 32) * kVhRowPitch)) = hreg[u];
-      *(u32x4*)(ws + (dst0 + u * (NTHREADS / 32) * kVhRowPitch)) = wreg[S][u];
-    }
-  };
-  auto compute = [&]() __attribute__((always_inline)) {
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      bf16x8 a[4], b[2];
+  // compute one step from LDS buffer BUF; with COMMIT, also write stage S of the registers to the other buffer.
+  // Per 32 k: the next fragments' reads and two of the tile writes are issued, then the eight MFMAs of the
+  // current fragments, under which those LDS operations run.
+  auto compute = [&](auto buffer, auto with_commit, auto stage) __attribute__((always_inline)) {
+    constexpr int BUF = decltype(buffer)::value, S = decltype(stage)::value;
+    constexpr bool COMMIT = decltype(with_commit)::value;
+    const unsigned char* hs = smem + (2 * BUF) * kVhTileBytes;
+    const unsigned char* ws = smem + (2 * BUF + 1) * kVhTileBytes;
+    unsigned char* hs_next = smem + (2 * (1 - BUF)) * kVhTileBytes;
+    unsigned char* ws_next = smem + (2 * (1 - BUF) + 1) * kVhTileBytes;
+    bf16x8 a[2][4], b[2][2];
+    auto read_fragments = [&](int kk, int slot) __attribute__((always_inline)) {
 #pragma unroll
       for (int rt = 0; rt < 4; ++rt)
-        a[rt] = __builtin_bit_cast(bf16x8, *(const u32x4*)(ws + (aoff + rt * 16 * kVhRowPitch + kk * 64)));
+        a[slot][rt] = __builtin_bit_cast(bf16x8, *(const u32x4*)(ws + (aoff + rt * 16 * kVhRowPitch + kk * 64)));
 #pragma unroll
       for (int ct = 0; ct < 2; ++ct)
-        b[ct] = __builtin_bit_cast(bf16x8, *(const u32x4*)(hs + (boff + ct * 16 * kVhRowPitch + kk * 64)));
+        b[slot][ct] = __builtin_bit_cast(bf16x8, *(const u32x4*)(hs + (boff + ct * 16 * kVhRowPitch + kk * 64)));
+    };
+    static_assert(PIECES == KK, "one hidden-state and one W piece are written per 32 k");
+    __builtin_amdgcn_sched_barrier(0);
+    read_fragments(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (kk + 1 < KK) read_fragments(kk + 1, (kk + 1) & 1);
+      if constexpr (COMMIT) {
+        *(u32x4*)(hs_next + (dst0 + kk * ROWS_PER_PIECE * kVhRowPitch)) = hreg[S][kk];
+        *(u32x4*)(ws_next + (dst0 + kk * ROWS_PER_PIECE * kVhRowPitch)) = wreg[S][kk];
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct)
-          acc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt], b[ct], acc[rt][ct], 0, 0, 0);
+          acc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kk & 1][rt], b[kk & 1][ct], acc[rt][ct], 0, 0, 0);
     }
-  };
-  auto do_step = [&](int step, auto stage) __attribute__((always_inline)) {
-    constexpr int S = decltype(stage)::value;
-    if (step > 0) lds_barrier();  // every wavefront is done with the previous step's tiles
-    commit(stage);
-    lds_barrier();
-    request_h(step + 1);
-    __builtin_amdgcn_sched_barrier(0);
-    request_w(step + WS - 1, std::integral_constant<int, (S + WS - 1) % WS>{});
-    __builtin_amdgcn_sched_barrier(0);
-    compute();
     __builtin_amdgcn_sched_barrier(0);
   };
+  using I0 = std::integral_constant<int, 0>;
 
-  // The pipelined loop takes WS steps per trip with no exit in between (an exit inside the trip gives the loop
-  // head a second, differently ordered set of loads in flight and the waits there fall back to draining
-  // everything), so the total_steps % WS steps that do not fill a trip run first, unpipelined.
-  const int lead = total_steps % WS;
+  // The pipelined loop takes TRIP steps per trip with no exit in between (an exit inside the trip gives the
+  // loop head a second, differently ordered set of loads in flight and the waits there fall back to draining
+  // everything), so the total_steps % TRIP steps that do not fill a trip run first, unpipelined.
+  const int lead = total_steps % TRIP;
   for (int i = 0; i < lead; ++i) {
-    request_w(i, std::integral_constant<int, 0>{});
-    request_h(i);
+    request(i, I0{});
     if (i > 0) lds_barrier();
-    commit(std::integral_constant<int, 0>{});
+    commit(I0{}, I0{});
     lds_barrier();
-    compute();
+    compute(I0{}, std::false_type{}, I0{});
   }
   if (lead < total_steps) {
-    // same issue order as in the loop (W of a step before its hidden states), kept by the scheduling fences
-    __builtin_amdgcn_sched_barrier(0);
-    request_w(lead, std::integral_constant<int, 0>{});
-    __builtin_amdgcn_sched_barrier(0);
-    request_h(lead);
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (WS > 2) request_w(lead + 1, std::integral_constant<int, 1>{});
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (WS > 3) request_w(lead + 2, std::integral_constant<int, 2>{});
-    __builtin_amdgcn_sched_barrier(0);
-    for (int i = lead; i < total_steps; i += WS) {
-      do_step(i, std::integral_constant<int, 0>{});
-      do_step(i + 1, std::integral_constant<int, 1 % WS>{});
-      if constexpr (WS > 2) do_step(i + 2, std::integral_constant<int, 2 % WS>{});
-      if constexpr (WS > 3) do_step(i + 3, std::integral_constant<int, 3 % WS>{});
+    // local step t = step - lead uses register stage t % DIST and LDS buffer t & 1
+    [&]<int... U>(std::integer_sequence<int, U...>) __attribute__((always_inline)) {
+      (request(lead + U, std::integral_constant<int, U>{}), ...);
+    }(std::make_integer_sequence<int, DIST>{});
+    if (lead > 0) lds_barrier();
+    commit(I0{}, I0{});
+    request(lead + DIST, I0{});
+    lds_barrier();
+    for (int t = lead; t < total_steps; t += TRIP) {
+      [&]<int... U>(std::integer_sequence<int, U...>) __attribute__((always_inline)) {
+        // step t + U: write step t + U + 1 (after the last step: zeros into the idle buffer), refill its stage
+        ((compute(std::integral_constant<int, U & 1>{}, std::true_type{}, std::integral_constant<int, (U + 1) % DIST>{}),
+          request(t + U + 1 + DIST, std::integral_constant<int, (U + 1) % DIST>{}), lds_barrier()),
+         ...);
+      }(std::make_integer_sequence<int, TRIP>{});
     }
   }
 
-  // ---- logit block -> LDS (over the staging area), best key per column ------------------------------------
-  __syncthreads();
-  float* zbuf = (float*)smem;
-#pragma unroll
-  for (int rt = 0; rt < 4; ++rt)
-#pragma unroll
-    for (int ct = 0; ct < 2; ++ct) {
-      f32x4 z;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) z[i] = (row_base + wr * 64 + rt * 16 + g * 4 + i) < p.V ? acc[rt][ct][i] : -INFINITY;
-      *(f32x4*)(zbuf + (wc * 32 + ct * 16 + c) * kVhZStride + wr * 64 + rt * 16 + g * 4) = z;
-    }
-  __syncthreads();
+  // ---- best (logit, id) key per column ---------------------------------------------------------------------
+  // (the loop's last barrier has every wavefront done with the LDS tiles)
   if (p.logits_out) {
+    // the logit block goes through LDS so that it leaves in rows of the output
+    float* zbuf = (float*)smem;
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct)
+        *(f32x4*)(zbuf + (wc * 32 + ct * 16 + c) * kVhZStride + wr * 64 + rt * 16 + g * 4) = acc[rt][ct];
+    __syncthreads();
     for (int idx = tid; idx < p.cols * kRowsPerBlock; idx += NTHREADS) {
       const int m = idx / kRowsPerBlock, r = idx % kRowsPerBlock;
       if (row_base + r < p.V) p.logits_out[(size_t)(p.col0 + m) * p.V + row_base + r] = zbuf[m * kVhZStride + r];
     }
+    __syncthreads();
   }
-  for (int m = wave; m < p.cols; m += kVhWaves) {
-    const float z0 = zbuf[m * kVhZStride + lane], z1 = zbuf[m * kVhZStride + lane + 64];
-    const int id0 = row_base + lane, id1 = row_base + lane + 64;
-    const unsigned long long a = id0 < p.V ? rank_key(z0, (unsigned)id0) : 0ull;
-    const unsigned long long b = id1 < p.V ? rank_key(z1, (unsigned)id1) : 0ull;
-    const unsigned long long best = wave_max_u64(a > b ? a : b);
-    if (lane == 0) p.pkey[(size_t)blockIdx.x * kVhCols + m] = best;
+  // a lane holds 16 rows of two columns: best of those, then over the 4 lane groups (64 rows), then over the
+  // two wavefronts that share the columns
+  unsigned long long* kbuf = (unsigned long long*)smem;  // [2][128]
+#pragma unroll
+  for (int ct = 0; ct < 2; ++ct) {
+    unsigned long long best = 0ull;
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = row_base + wr * 64 + rt * 16 + g * 4 + i;
+        const unsigned long long key = row < p.V ? rank_key(acc[rt][ct][i], (unsigned)row) : 0ull;
+        best = key > best ? key : best;
+      }
+    unsigned long long o = __shfl_xor(best, 16);
+    best = o > best ? o : best;
+    o = __shfl_xor(best, 32);
+    best = o > best ? o : best;
+    if (g == 0) kbuf[wr * kVhCols + wc * 32 + ct * 16 + c] = best;
+  }
+  __syncthreads();
+  if (tid < p.cols) {
+    const unsigned long long k0 = kbuf[tid], k1 = kbuf[kVhCols + tid];
+    p.pkey[(size_t)blockIdx.x * kVhCols + tid] = k0 > k1 ? k0 : k1;
   }
 }
 
@@ -311,16 +347,16 @@ extern "C" int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void
   VerifyHeadParams p;
   p.hidden = node_hidden; p.w = w_base; p.D = D; p.V = V;
   p.n_blocks = (V + kRowsPerBlock - 1) / kRowsPerBlock;
-  p.pkey = ctx->vh_pkey; p.logits_out = logits_out; p.n_nodes = n_nodes; p.max_nodes = max_nodes;
+  p.zeros = ctx->zeros; p.pkey = ctx->vh_pkey; p.logits_out = logits_out; p.n_nodes = n_nodes; p.max_nodes = max_nodes;
   p.target = target_argmax;
   const long long cols_total = (long long)B * max_nodes;
-  const bool wide = dt == CTCSPEC_BF16 && D % 256 == 0 && (long long)V * D * 2 < (1LL << 32) &&
+  const bool wide = dt == CTCSPEC_BF16 && D % kVhStepK == 0 && (long long)V * D * 2 < (1LL << 32) &&
                     cols_total * D * 2 < (1LL << 32);
-  const int lds = kVhHsBytes + kVhWsBytes;
+  const int lds = kVhLdsBytes;
   if (wide) {
     static bool lds_allowed = false;  // raising the limit is needed once per process
     if (!lds_allowed) {
-      CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)verify_head_bf16_kernel<kVhStages>,
+      CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)verify_head_bf16_kernel<kVhDist>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds));
       lds_allowed = true;
     }
@@ -329,7 +365,7 @@ extern "C" int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void
     p.col0 = (int)col0;
     p.cols = (int)(cols_total - col0 < kVhCols ? cols_total - col0 : kVhCols);
     if (wide) {
-      hipLaunchKernelGGL(verify_head_bf16_kernel<kVhStages>, dim3(p.n_blocks), dim3(64 * kVhWaves), lds, ctx->stream, p);
+      hipLaunchKernelGGL(verify_head_bf16_kernel<kVhDist>, dim3(p.n_blocks), dim3(64 * kVhWaves), lds, ctx->stream, p);
     } else {
       hipLaunchKernelGGL(verify_head_clear_kernel, dim3(64), dim3(256), 0, ctx->stream, p);
       if (dt == CTCSPEC_BF16)
