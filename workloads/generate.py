@@ -186,3 +186,56 @@ def make_topk_case(seed: int, B: int, T: int, k: int, blank_id: int, *, vocab: i
                 lp = -np.sort(-lp)
             logp[b, t] = lp
     return ids, logp
+
+
+@dataclass
+class DraftLayerCase:
+    """Inputs of one call of the draft module's transformer layer (storage-rounded float32 arrays)."""
+    B: int
+    T: int
+    D: int
+    H: int
+    F: int
+    kv_cap: int
+    eps: float
+    theta: float
+    dtype: str
+    x: np.ndarray          # [B,T,D] base-model hidden states of the T draft positions
+    weights: dict          # ln1 [D], wq wk wv wo [D,D], ln2 [D], wg wu [F,D], wd [D,F]
+    pos0: np.ndarray       # [B] i32 position of the first of the T tokens
+    ctx_len: np.ndarray    # [B] i32 cached positions of the layer's own history
+    kv_off: np.ndarray     # [B] i64 element offset of sequence b in the cache buffers
+    k_cache: np.ndarray    # [B,H,kv_cap,dh]; rows >= ctx_len[b] are NaN
+    v_cache: np.ndarray    # [B,H,kv_cap,dh]
+
+
+def make_draft_layer_case(seed: int, B: int, T: int, D: int, H: int, F: int, ctx_len, kv_cap: int,
+                          dtype: str = "bf16", eps: float = 1e-6, theta: float = 10000.0) -> DraftLayerCase:
+    """Random decoder-layer weights at the scale of a trained LLaMA layer (projection entries about
+    1/sqrt(fan_in), norm gains around 1), hidden states with a few large channels as the base model's last
+    layer has, and a cache of unit-scale keys and values.  pos0 = ctx_len (the new tokens follow the history)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    dh = D // H
+    ctx_len = np.broadcast_to(np.asarray(ctx_len, dtype=np.int32), (B,)).copy()
+
+    def mat(rows, cols):
+        return round_to_storage(rng.standard_normal((rows, cols), dtype=np.float32) / np.float32(np.sqrt(cols)), dtype)
+
+    weights = {
+        "ln1": round_to_storage(1.0 + 0.1 * rng.standard_normal(D, dtype=np.float32), dtype),
+        "wq": mat(D, D), "wk": mat(D, D), "wv": mat(D, D), "wo": mat(D, D),
+        "ln2": round_to_storage(1.0 + 0.1 * rng.standard_normal(D, dtype=np.float32), dtype),
+        "wg": mat(F, D), "wu": mat(F, D), "wd": mat(D, F),
+    }
+    x = rng.standard_normal((B, T, D), dtype=np.float32)
+    x[..., rng.integers(0, D, size=max(1, D // 256))] *= np.float32(8.0)  # a few outlier channels
+    x = round_to_storage(x, dtype)
+    k_cache = round_to_storage(rng.standard_normal((B, H, kv_cap, dh), dtype=np.float32), dtype)
+    v_cache = round_to_storage(rng.standard_normal((B, H, kv_cap, dh), dtype=np.float32), dtype)
+    for b in range(B):
+        k_cache[b, :, ctx_len[b]:, :] = np.nan
+        v_cache[b, :, ctx_len[b]:, :] = np.nan
+    kv_off = (np.arange(B, dtype=np.int64) * H * kv_cap * dh)
+    return DraftLayerCase(B=B, T=T, D=D, H=H, F=F, kv_cap=kv_cap, eps=eps, theta=theta, dtype=dtype, x=x,
+                          weights=weights, pos0=ctx_len.copy(), ctx_len=ctx_len, kv_off=kv_off,
+                          k_cache=k_cache, v_cache=v_cache)
