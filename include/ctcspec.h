@@ -248,6 +248,55 @@ int kv_commit(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* k_tree, const void
               const int32_t* ctx_len, int kv_cap, int B, int H, int dh, int max_nodes, void* k_cache,
               void* v_cache, int32_t* ctx_len_out);
 
+/*
+ * draft_layer_forward - the transformer layer of the attention draft module (Sec. 3.1 "Model Structure": one
+ * transformer layer of the base model's construction over the base model's last hidden states, predicting all
+ * draft positions in parallel; its output goes to the LM head, i.e. to ctc_draft_topk).
+ *
+ * The layer is the base family's decoder layer (Vicuna/LLaMA), for column (b, t), t = 0..T-1, at position
+ * pos0[b] + t:
+ *   h   = RMSNorm(x; ln1)                      y / sqrt(mean(y^2) + rms_eps) * gain
+ *   q, k, v = h Wq^T, h Wk^T, h Wv^T           head i owns output rows i*dh .. i*dh+dh-1, dh = D / H
+ *   q, k <- rotary embedding                   pair (j, j + dh/2) turned by (pos0[b] + t) * rope_theta^(-2j/dh)
+ *   a   = softmax(q K^T / sqrt(dh)) V          over the ctx_len[b] cached positions and the new positions <= t
+ *   h1  = x + a Wo^T
+ *   out = h1 + (silu(m Wg^T) * (m Wu^T)) Wd^T  with m = RMSNorm(h1; ln2)
+ * The cache is read only; k_new (rotated) and v_new are returned so that the caller appends what it keeps
+ * (kv_commit takes them as k_tree / v_tree with max_nodes = T).
+ *
+ * All pointers are device pointers, 16-byte aligned, bf16 (dt must be CTCSPEC_BF16) unless stated:
+ * x         [B,T,D] in
+ * w         host struct of device pointers: ln1 [D], wqkv [3D,D] (rows: Wq, then Wk, then Wv), wo [D,D],
+ *           ln2 [D], wgu [2F,D] (rows: Wg, then Wu), wd [D,F]; row-major, row = output feature
+ * pos0      [B] int32 in
+ * k_cache, v_cache, kv_off [B] int64, ctx_len [B] int32, kv_cap: the layer's cache, laid out as for
+ *           tree_verify_attn ([H, kv_cap, dh] per sequence at element offset kv_off[b]); not modified
+ * workspace device scratch of at least draft_layer_workspace_bytes(B, T, D, H, F) bytes, owned by the
+ *           caller, contents undefined afterwards; calls that share it must not overlap
+ * q_out     [B,H,T,dh] out or NULL: the rotated queries the attention step used (otherwise kept in the workspace)
+ * k_new, v_new [B,H,T,dh] out
+ * out       [B,T,D] out;  out_f32 [B,T,D] float out or NULL: the same values before rounding to bf16
+ * Limits: D % 256 == 0, F % 256 == 0, dh % 8 == 0, dh <= CTCSPEC_MAX_HEAD_DIM, T <= 64 and T <= limits.max_nodes,
+ * B, H, dh within the context's limits.  Returns CTCSPEC_OK or an error code (see ctcspec_last_error);
+ * nothing is written on an argument error.  Work is queued on the context's stream.
+ */
+typedef struct {
+  const void* ln1;
+  const void* wqkv;
+  const void* wo;
+  const void* ln2;
+  const void* wgu;
+  const void* wd;
+} ctcspec_layer_weights;
+
+size_t draft_layer_workspace_bytes(int B, int T, int D, int H, int F);
+
+int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* x, const ctcspec_layer_weights* w,
+                        const int32_t* pos0, void* k_cache, void* v_cache, const int64_t* kv_off,
+                        const int32_t* ctx_len, int kv_cap, int B, int T, int D, int H, int F, float rms_eps,
+                        float rope_theta, void* workspace, size_t workspace_bytes, void* q_out, void* k_new,
+                        void* v_new, void* out, float* out_f32);
+
 #ifdef __cplusplus
 }
 #endif

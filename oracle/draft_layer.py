@@ -40,33 +40,41 @@ def silu(x):
     return x / (1.0 + np.exp(-x))
 
 
-def draft_layer(x, w, pos0, k_cache, v_cache, ctx_len, n_heads, eps, theta):
-    """One sequence.  x [T, D]: the base model's hidden states at the T positions pos0 .. pos0+T-1.
-    w: dict of float arrays - ln1 [D], wq, wk, wv, wo [D, D] (row = output feature; head h owns output rows
-    h*dh .. h*dh+dh-1 of wq/wk/wv and input columns of wo), ln2 [D], wg, wu [F, D], wd [D, F].
-    k_cache, v_cache [H, cap, dh]: keys (already rotated) and values of the ctx_len earlier positions.
-    Returns (y [T, D], k_new [H, T, dh] rotated keys, v_new [H, T, dh]) in float64."""
+def draft_layer_qkv(x, w, pos0, n_heads, eps, theta):
+    """First half of the layer: normalised input -> queries, keys and values of the T new positions, queries
+    and keys rotated to their positions pos0 .. pos0+T-1.  Returns (q [H, T, dh], k_new [H, T, dh],
+    v_new [H, T, dh]) in float64; k_new and v_new are what the cache stores for these positions."""
     x = np.asarray(x, dtype=np.float64)
     T, D = x.shape
     H = n_heads
     dh = D // H
-    f = {k: np.asarray(v, dtype=np.float64) for k, v in w.items()}
-    kc = np.asarray(k_cache, dtype=np.float64)
-    vc = np.asarray(v_cache, dtype=np.float64)
-
-    h = rms_norm(x, f["ln1"], eps)
-    q = (h @ f["wq"].T).reshape(T, H, dh)
-    k = (h @ f["wk"].T).reshape(T, H, dh)
-    v = (h @ f["wv"].T).reshape(T, H, dh)
+    h = rms_norm(x, w["ln1"], eps)
+    q = (h @ np.asarray(w["wq"], dtype=np.float64).T).reshape(T, H, dh)
+    k = (h @ np.asarray(w["wk"], dtype=np.float64).T).reshape(T, H, dh)
+    v = (h @ np.asarray(w["wv"], dtype=np.float64).T).reshape(T, H, dh)
+    q_rot = np.empty((H, T, dh))
     k_new = np.empty((H, T, dh))
     v_new = np.empty((H, T, dh))
-    q_rot = np.empty((H, T, dh))
     for t in range(T):
         for hd in range(H):
             q_rot[hd, t] = rope(q[t, hd], pos0 + t, theta)
             k_new[hd, t] = rope(k[t, hd], pos0 + t, theta)
             v_new[hd, t] = v[t, hd]
+    return q_rot, k_new, v_new
 
+
+def draft_layer_attend(x, w, q_rot, k_new, v_new, k_cache, v_cache, ctx_len, eps):
+    """Second half: attention of the T new positions over the cached history and, causally, over each other,
+    output projection and residual, then the gated feed-forward block and its residual.  Returns y [T, D]."""
+    x = np.asarray(x, dtype=np.float64)
+    T, D = x.shape
+    q_rot = np.asarray(q_rot, dtype=np.float64)
+    k_new = np.asarray(k_new, dtype=np.float64)
+    v_new = np.asarray(v_new, dtype=np.float64)
+    H, _, dh = q_rot.shape
+    f = {k: np.asarray(v, dtype=np.float64) for k, v in w.items()}
+    kc = np.asarray(k_cache, dtype=np.float64)
+    vc = np.asarray(v_cache, dtype=np.float64)
     attn = np.empty((T, H, dh))
     scale = 1.0 / np.sqrt(dh)
     for hd in range(H):
@@ -79,8 +87,17 @@ def draft_layer(x, w, pos0, k_cache, v_cache, ctx_len, n_heads, eps, theta):
             p /= p.sum()
             attn[t, hd] = p @ vals
     h1 = x + attn.reshape(T, D) @ f["wo"].T
-
     m = rms_norm(h1, f["ln2"], eps)
     act = silu(m @ f["wg"].T) * (m @ f["wu"].T)
-    y = h1 + act @ f["wd"].T
+    return h1 + act @ f["wd"].T
+
+
+def draft_layer(x, w, pos0, k_cache, v_cache, ctx_len, n_heads, eps, theta):
+    """One sequence.  x [T, D]: the base model's hidden states at the T positions pos0 .. pos0+T-1.
+    w: dict of float arrays - ln1 [D], wq, wk, wv, wo [D, D] (row = output feature; head h owns output rows
+    h*dh .. h*dh+dh-1 of wq/wk/wv and input columns of wo), ln2 [D], wg, wu [F, D], wd [D, F].
+    k_cache, v_cache [H, cap, dh]: keys (already rotated) and values of the ctx_len earlier positions.
+    Returns (y [T, D], k_new [H, T, dh] rotated keys, v_new [H, T, dh]) in float64."""
+    q_rot, k_new, v_new = draft_layer_qkv(x, w, pos0, n_heads, eps, theta)
+    y = draft_layer_attend(x, w, q_rot, k_new, v_new, k_cache, v_cache, ctx_len, eps)
     return y, k_new, v_new

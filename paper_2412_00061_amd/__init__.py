@@ -11,7 +11,10 @@ from .binding import (  # noqa: F401
     accept_longest,
     ctc_collapse_tree,
     ctc_draft_topk,
+    draft_layer_forward,
+    draft_layer_workspace_bytes,
     kv_commit,
+    layer_weights,
     library_path,
     load_library,
     prepared,

@@ -15,7 +15,7 @@ _LIB = None
 EXPORTS = (
     "ctcspec_create", "ctcspec_destroy", "ctcspec_set_stream", "ctcspec_last_error",
     "ctcspec_workspace_bytes", "ctcspec_profile_draft_head", "ctcspec_draft_head_kernel_ms", "ctc_draft_topk", "ctc_collapse_tree", "tree_verify_attn",
-    "accept_longest", "verify_head_argmax", "kv_commit",
+    "accept_longest", "verify_head_argmax", "kv_commit", "draft_layer_workspace_bytes", "draft_layer_forward",
 )
 
 CTCSPEC_F32, CTCSPEC_BF16 = 0, 1
@@ -28,6 +28,10 @@ class CtcspecError(RuntimeError):
 class _Limits(ctypes.Structure):
     _fields_ = [(n, c_int) for n in ("max_batch", "max_slots", "max_topk", "max_vocab_rows",
                                      "max_nodes", "max_heads", "max_head_dim")]
+
+
+class _LayerWeights(ctypes.Structure):
+    _fields_ = [(n, c_void_p) for n in ("ln1", "wqkv", "wo", "ln2", "wgu", "wd")]
 
 
 def library_path() -> str:
@@ -77,6 +81,11 @@ def load_library():
     lib.kv_commit.restype = c_int
     lib.kv_commit.argtypes = [c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_void_p,
                               c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p]
+    lib.draft_layer_workspace_bytes.restype = c_size_t
+    lib.draft_layer_workspace_bytes.argtypes = [c_int] * 5
+    lib.draft_layer_forward.restype = c_int
+    lib.draft_layer_forward.argtypes = ([c_void_p, c_int, c_void_p, POINTER(_LayerWeights)] + [c_void_p] * 5 +
+                                        [c_int] * 6 + [c_float, c_float, c_void_p, c_size_t] + [c_void_p] * 5)
     _LIB = lib
     return lib
 
@@ -295,3 +304,41 @@ def kv_commit(ctx, k_tree, v_tree, accept_len, accept_nodes, kv_off, ctx_len, kv
                            _ptr(k_cache, k_tree.dtype), _ptr(v_cache, k_tree.dtype),
                            _ptr(ctx_len_out, torch.int32) if ctx_len_out is not None else None)
     ctx._check(rc, "kv_commit")
+
+
+def layer_weights(ln1, wqkv, wo, ln2, wgu, wd):
+    """The C struct of device pointers that draft_layer_forward takes (the tensors must outlive the calls)."""
+    tensors = (ln1, wqkv, wo, ln2, wgu, wd)
+    for t in tensors:
+        _ptr(t, torch.bfloat16)
+    st = _LayerWeights(*[t.data_ptr() for t in tensors])
+    st._keep = tensors
+    return st
+
+
+def draft_layer_workspace_bytes(B, T, D, H, F) -> int:
+    return int(load_library().draft_layer_workspace_bytes(B, T, D, H, F))
+
+
+def draft_layer_forward(ctx, x, weights, pos0, k_cache, v_cache, kv_off, ctx_len, kv_cap, H, F, rms_eps, rope_theta,
+                        *, workspace=None, want_f32=False, want_q=False, out=None):
+    """x [B,T,D] bf16, weights from layer_weights() -> dict(out [B,T,D], k_new, v_new [B,H,T,dh][, out_f32][, q])."""
+    B, T, D = x.shape
+    dev = x.device
+    need = draft_layer_workspace_bytes(B, T, D, H, F)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    res = {"out": _out(out, "out", (B, T, D), torch.bfloat16, dev),
+           "k_new": _out(out, "k_new", (B, H, T, D // H), torch.bfloat16, dev),
+           "v_new": _out(out, "v_new", (B, H, T, D // H), torch.bfloat16, dev)}
+    if want_f32:
+        res["out_f32"] = _out(out, "out_f32", (B, T, D), torch.float32, dev)
+    if want_q:
+        res["q"] = _out(out, "q", (B, H, T, D // H), torch.bfloat16, dev)
+    rc = ctx.lib.draft_layer_forward(ctx.handle, _dtype_code(x), _ptr(x), ctypes.byref(weights),
+                                     _ptr(pos0, torch.int32), _ptr(k_cache, x.dtype), _ptr(v_cache, x.dtype),
+                                     _ptr(kv_off, torch.int64), _ptr(ctx_len, torch.int32), kv_cap, B, T, D, H, F,
+                                     rms_eps, rope_theta, _ptr(workspace, torch.uint8), workspace.numel(),
+                                     _ptr(res.get("q")), _ptr(res["k_new"]), _ptr(res["v_new"]), _ptr(res["out"]), _ptr(res.get("out_f32")))
+    ctx._check(rc, "draft_layer_forward")
+    return res

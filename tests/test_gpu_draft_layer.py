@@ -1,0 +1,126 @@
+"""GPU parity of draft_layer_forward (the draft module's transformer layer) against the oracle.
+
+bf16 inputs and weights, fp32 accumulation.  The activations that feed a matrix product are carried as fp32
+(two bf16 numbers), so a product loses nothing to them; the one place where values are held in bf16 is the
+attention step, whose queries, keys and values have the cache's storage type.  The test therefore holds each
+half of the layer to 2e-3 (relative, RMS floor) on its own:
+  * q, k_new, v_new against the oracle's first half, plus the storage rounding of bf16 (half an ulp: 2^-8);
+  * the output against the oracle's second half run on the very q, k_new, v_new the kernel stored.
+End to end against the float64 oracle the storage rounding of q/k/v passes through the attention and the output
+projection about one to one: 2e-3 + 2^-8 there.  The bf16 output must be the rounding of the fp32 output bit
+for bit, and a second call must reproduce every output bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from gpu_harness import rel_err_rms_floor
+from workloads.device import dev_i32, dev_i64, to_device
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+TOL_BF16 = 2e-3 + 2.0 ** -8
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2412_00061_amd as m
+    m.load_library()
+    return m
+
+
+def _device_case(pkg, c):
+    w = c.weights
+    cat = np.concatenate
+    dw = pkg.layer_weights(to_device(w["ln1"], "bf16"), to_device(cat([w["wq"], w["wk"], w["wv"]]), "bf16"),
+                           to_device(w["wo"], "bf16"), to_device(w["ln2"], "bf16"),
+                           to_device(cat([w["wg"], w["wu"]]), "bf16"), to_device(w["wd"], "bf16"))
+    return dict(x=to_device(c.x, "bf16"), w=dw, pos0=dev_i32(c.pos0), kc=to_device(c.k_cache, "bf16"),
+                vc=to_device(c.v_cache, "bf16"), off=dev_i64(c.kv_off), len=dev_i32(c.ctx_len))
+
+
+def _run(pkg, ctx, c, d, **kw):
+    return pkg.draft_layer_forward(ctx, d["x"], d["w"], d["pos0"], d["kc"], d["vc"], d["off"], d["len"], c.kv_cap,
+                                   c.H, c.F, c.eps, c.theta, **kw)
+
+
+def _check(pkg, seed, B, T, D, H, F, ctx_len, cap):
+    c = workloads.make_draft_layer_case(seed, B, T, D, H, F, ctx_len, cap, dtype="bf16")
+    ctx = pkg.Context(max_batch=B, max_slots=8, max_topk=4, max_vocab_rows=128, max_nodes=max(T, 8), max_heads=H,
+                      max_head_dim=D // H)
+    d = _device_case(pkg, c)
+    print(f"draft_layer_forward seed={seed} B={B} T={T} D={D} H={H} F={F} ctx={list(c.ctx_len)}", flush=True)
+    res = _run(pkg, ctx, c, d, want_f32=True, want_q=True)
+    again = _run(pkg, ctx, c, d)
+    torch.cuda.synchronize()
+    y32 = res["out_f32"].cpu().numpy()
+    ybf = res["out"].float().cpu().numpy()
+    qn, kn, vn = (res[n].float().cpu().numpy() for n in ("q", "k_new", "v_new"))
+    for b in range(B):
+        q_ref, k_ref, v_ref = oracle.draft_layer_qkv(c.x[b], c.weights, int(c.pos0[b]), H, c.eps, c.theta)
+        for got, ref in ((qn[b], q_ref), (kn[b], k_ref), (vn[b], v_ref)):
+            assert rel_err_rms_floor(got, ref) <= TOL_BF16, (b, rel_err_rms_floor(got, ref))
+        y_chained = oracle.draft_layer_attend(c.x[b], c.weights, qn[b], kn[b], vn[b], c.k_cache[b], c.v_cache[b],
+                                              int(c.ctx_len[b]), c.eps)
+        assert rel_err_rms_floor(y32[b], y_chained) <= TOL, (b, rel_err_rms_floor(y32[b], y_chained))
+        y, _, _ = oracle.draft_layer(c.x[b], c.weights, int(c.pos0[b]), c.k_cache[b], c.v_cache[b],
+                                     int(c.ctx_len[b]), H, c.eps, c.theta)
+        assert rel_err_rms_floor(y32[b], y) <= TOL_BF16, (b, rel_err_rms_floor(y32[b], y))
+    assert np.array_equal(ybf, workloads.round_to_storage(y32, "bf16"))
+    # same bits on a second call (the partial tiles are added in a fixed order), with or without the fp32 copy
+    for name in ("out", "k_new", "v_new"):
+        assert torch.equal(res[name], again[name])
+    ctx.close()
+
+
+@pytest.mark.parametrize("seed,B,T,D,H,F,ctx_len,cap", [
+    (0, 1, 4, 256, 2, 512, [37], 64),             # dh = 128: MFMA attention, one k chunk per matrix row tile
+    (1, 2, 8, 512, 4, 768, [100, 3], 128),        # 16 columns, ragged history, 3 chunks in the down projection
+    (2, 3, 5, 256, 4, 256, [0, 17, 40], 48),      # dh = 64: generic attention; an empty history; 15 columns
+    (3, 3, 8, 256, 2, 512, [5, 9, 2], 16),        # 24 columns: two passes over every matrix
+    (4, 1, 8, 256, 2, 6144, [20], 32),            # the down projection's activations take two k groups
+    (5, 1, 1, 512, 4, 1024, [63], 64),            # a single position
+])
+def test_draft_layer_shapes(pkg, seed, B, T, D, H, F, ctx_len, cap):
+    _check(pkg, seed, B, T, D, H, F, ctx_len, cap)
+
+
+def test_draft_layer_full_size(pkg):
+    """The 7B shape the benchmark times: D=4096, 32 heads, F=11008, 8 positions after 2048 cached ones."""
+    _check(pkg, 7, 1, 8, 4096, 32, 11008, [2048], 2048 + 128)
+
+
+def test_draft_layer_feeds_the_draft_head(pkg):
+    """The layer's bf16 output is what ctc_draft_topk takes as hidden states: the chained call must agree with the
+    oracle's head run on the very same bf16 states."""
+    B, T, D, H, F, V, k = 1, 8, 256, 2, 512, 300, 4
+    c = workloads.make_draft_layer_case(11, B, T, D, H, F, [21], 64, dtype="bf16")
+    ctx = pkg.Context(max_batch=B, max_slots=T, max_topk=k, max_vocab_rows=V + 1, max_nodes=8, max_heads=H,
+                      max_head_dim=D // H)
+    d = _device_case(pkg, c)
+    res = _run(pkg, ctx, c, d)
+    rng = np.random.Generator(np.random.PCG64(12))
+    w_head = workloads.round_to_storage(rng.standard_normal((V + 1, D), dtype=np.float32) * 0.05, "bf16")
+    top = pkg.ctc_draft_topk(ctx, res["out"], to_device(w_head, "bf16"), None, k)
+    torch.cuda.synchronize()
+    hidden = res["out"].float().cpu().numpy()
+    ref = oracle.draft_topk(hidden, w_head, np.zeros(V + 1, dtype=np.float32), k)
+    assert rel_err_rms_floor(top["topk_logp"].cpu().numpy(), ref["topk_logp"]) <= TOL
+    assert rel_err_rms_floor(top["lse"].cpu().numpy(), ref["lse"]) <= TOL
+    ctx.close()
+
+
+def test_draft_layer_rejects_bad_arguments(pkg):
+    c = workloads.make_draft_layer_case(0, 1, 4, 256, 2, 512, [8], 16, dtype="bf16")
+    ctx = pkg.Context(max_batch=1, max_slots=8, max_topk=4, max_vocab_rows=128, max_nodes=8, max_heads=2,
+                      max_head_dim=128)
+    d = _device_case(pkg, c)
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(pkg.CtcspecError, match="workspace"):
+        _run(pkg, ctx, c, d, workspace=small)
+    with pytest.raises(pkg.CtcspecError, match="multiples of 256"):
+        pkg.draft_layer_forward(ctx, d["x"], d["w"], d["pos0"], d["kc"], d["vc"], d["off"], d["len"], c.kv_cap, c.H,
+                                500, c.eps, c.theta)
+    ctx.close()
