@@ -47,6 +47,9 @@ def parse_args():
                          "K/V/Q buffers); default: heads of the config (32 at 7B, 40 at 13B); 0: skip")
     ap.add_argument("--full-depth-steps", type=int, default=24)
     ap.add_argument("--no-closed-step", action="store_true")
+    ap.add_argument("--no-draft-layer", action="store_true")
+    ap.add_argument("--draft-layer-ffn", type=int, default=0,
+                    help="feed-forward width of the draft module's layer (0: the base family's, 43/16 of D)")
     ap.add_argument("--cpu-steps", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run ten 256 MiB device copies (known traffic, for scaling rocprofv3 HBM counters)")
@@ -336,6 +339,65 @@ def main():
                   "verify_head_hbm_gbps": vh_bytes / (vh_us * 1e-6) / 1e9,
                   "verified_tokens_per_sec": int(n_nodes.sum()) / (cs_us * 1e-6)}
 
+    # draft-module variant: the transformer layer that produces the T slot states (its own weights and
+    # cache, the base family's shape), then the step.  Weight copies rotate so that no pass finds its matrix in
+    # a cache; the layer's workspace is allocated once.
+    draft_layer = None
+    if not args.no_draft_layer and cfg.dtype == "bf16" and cfg.D % 256 == 0 and B * T <= 16:
+        D = cfg.D
+        F = args.draft_layer_ffn if args.draft_layer_ffn > 0 else (D * 43 // 16 + 255) // 256 * 256
+        g = torch.Generator(device="cuda").manual_seed(args.seed + 2)
+
+        def rnd(*shape, scale=1.0):
+            return (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * scale).to(torch.bfloat16)
+
+        n_wsets = 2
+        wsets, keep = [], []
+        for _ in range(n_wsets):
+            tens = (1 + 0.1 * rnd(D).float()).to(torch.bfloat16), rnd(3 * D, D, scale=D ** -0.5), \
+                rnd(D, D, scale=D ** -0.5), (1 + 0.1 * rnd(D).float()).to(torch.bfloat16), \
+                rnd(2 * F, D, scale=D ** -0.5), rnd(D, F, scale=F ** -0.5)
+            keep.append(tens)
+            wsets.append(lib.layer_weights(*tens))
+        x_in = rnd(B, T, D)
+        ws = torch.empty(lib.draft_layer_workspace_bytes(B, T, D, H, F), dtype=torch.uint8, device="cuda")
+        kn, vn = torch.empty((B, H, T, dh), dtype=torch.bfloat16, device="cuda"), torch.empty((B, H, T, dh), dtype=torch.bfloat16, device="cuda")
+        slot_hidden = torch.empty((B, T, D), dtype=torch.bfloat16, device="cuda")
+        dl_calls = []
+        for i, wst in enumerate(wsets):
+            q, kt, vt, kc, vc = sets[i % len(sets)]
+            dl_calls.append(lib.prepared(ctx, "draft_layer_forward", dt, x_in, wst, d_len, kc, vc, d_off, d_len,
+                                         cfg.kv_cap, B, T, D, H, F, 1e-6, 10000.0, ws, ws.numel(), None, kn, vn,
+                                         slot_hidden, None))
+        for i in range(4):
+            dl_calls[i % n_wsets]()
+        torch.cuda.synchronize()
+        n_dl = max(24, min(args.steps, 96))
+        dl_ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_dl + 1)]
+        dl_ev[0].record()
+        for i in range(n_dl):
+            dl_calls[i % n_wsets]()
+            dl_ev[i + 1].record()
+        torch.cuda.synchronize()
+        dl_us = np.array([dl_ev[i].elapsed_time(dl_ev[i + 1]) * 1e3 for i in range(n_dl)])
+        # with the step behind it
+        t0 = time.perf_counter()
+        for i in range(n_dl):
+            c1, c2, c3, c4 = slots[i % period]
+            dl_calls[i % n_wsets](); c1(); c2(); c3(); c4()
+        torch.cuda.synchronize()
+        dls_us = (time.perf_counter() - t0) / n_dl * 1e6
+        w_bytes = 2 * (3 * D * D + D * D + 2 * F * D + D * F)
+        kv_bytes = int(sum(2 * H * int(l) * dh * 2 for l in x.ctx_len))
+        dl_bytes = w_bytes + kv_bytes + 2 * D * 2 + 6 * B * T * D * 2
+        draft_layer = {"call": "draft_layer_forward", "shape": f"B={B} T={T} D={D} H={H} F={F} ctx={x.ctx_len.tolist()}",
+                       "calls": n_dl, "us_per_call_median": float(np.median(dl_us)), "us_per_call_mean": float(dl_us.mean()),
+                       "algorithmic_bytes": dl_bytes, "weight_bytes": w_bytes,
+                       "hbm_gbps": dl_bytes / (float(np.median(dl_us)) * 1e-6) / 1e9,
+                       "frac_of_hbm_peak": dl_bytes / (float(np.median(dl_us)) * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                       "layer_plus_step_us": dls_us,
+                       "layer_plus_step_verified_tokens_per_sec": int(n_nodes.sum()) / (dls_us * 1e-6)}
+
     head_b, attn_b, total_b = algorithmic_bytes(cfg, x.ctx_len, n_nodes)
     if n_layers > 0:
         fd_bytes = total_b + (n_layers - 1) * attn_b
@@ -378,6 +440,7 @@ def main():
         "attention_hbm_gbps": attn_b / (float(call_us[2]) * 1e-6) / 1e9,
         "full_depth_variant": full_depth,
         "closed_step_variant": closed,
+        "draft_layer_variant": draft_layer,
         "roofline": {"kernel": "lmhead_bf16_mfma_kernel (ctc_draft_topk)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": read_traffic_summary(), "algorithmic_bytes_per_launch": head_b,

@@ -253,6 +253,8 @@ struct LayerParams {
   unsigned short* act;         // [2][B*T][F]
   int32_t* n_rows;             // [B] = T
   unsigned long long* causal;  // [B][T] bit j of row t set for j <= t
+  float* ss1;                  // [B*T][D/256] partial sums of x^2
+  float* ss2;                  // [B*T][D/256] partial sums of h1^2
   // outputs
   unsigned short* k_new;       // [B][H][T][dh]
   unsigned short* v_new;       // [B][H][T][dh]
@@ -262,22 +264,28 @@ struct LayerParams {
   int col0, cols;              // columns of the current pass
 };
 
-// x -> RMSNorm(x) * ln1 (bf16); block 0 also writes the row counts and the causal mask the attention call takes
-__global__ __launch_bounds__(256) void dl_norm_in_kernel(LayerParams p) {
+// RMSNorm is a per-column scalar times an elementwise gain, and the scalar commutes with the matrix product
+// that follows: the product is taken of x * gain, the kernel that consumes it multiplies by
+// 1 / sqrt(mean(x^2) + eps).  The sum of squares is left as one partial sum per 256 elements, added up by the
+// consumer in ascending order.
+__device__ __forceinline__ float inv_rms(const float* __restrict__ ss, int col, int nseg, int D, float eps) {
+  float t = 0.f;
+  for (int i = 0; i < nseg; ++i) t += ss[col * nseg + i];
+  return 1.0f / sqrtf(t / (float)D + eps);
+}
+
+// x * ln1 (as two bf16 numbers) and the partial sums of x^2; one block per (column, 256 elements).  Block 0 also
+// writes the row counts and the causal mask that the attention call takes.
+__global__ __launch_bounds__(256) void dl_scale_in_kernel(LayerParams p) {
   __shared__ float red[4];
-  const int col = blockIdx.x, tid = threadIdx.x;
-  const unsigned short* xr = p.x + (size_t)col * p.D;
-  float ss = 0.f;
-  for (int d = tid; d < p.D; d += 256) {
-    const float v = bf16_bits_to_float(xr[d]);
-    ss += v * v;
-  }
-  ss = block_sum_256(ss, red);
-  const float inv = 1.0f / sqrtf(ss / (float)p.D + p.eps);
-  for (int d = tid; d < p.D; d += 256)
-    store_split(p.xn, (size_t)p.B * p.T * p.D, (size_t)col * p.D + d,
-                bf16_bits_to_float(xr[d]) * inv * bf16_bits_to_float(p.ln1[d]));
-  if (col == 0) {
+  const int nseg = p.D / 256;
+  const int col = blockIdx.x / nseg, seg = blockIdx.x - col * nseg, tid = threadIdx.x;
+  const size_t o = (size_t)col * p.D + seg * 256 + tid;
+  const float v = bf16_bits_to_float(p.x[o]);
+  store_split(p.xn, (size_t)p.B * p.T * p.D, o, v * bf16_bits_to_float(p.ln1[seg * 256 + tid]));
+  const float ss = block_sum_256(v * v, red);
+  if (tid == 0) p.ss1[blockIdx.x] = ss;
+  if (blockIdx.x == 0) {
     for (int i = tid; i < p.B; i += 256) p.n_rows[i] = p.T;
     for (int i = tid; i < p.B * p.T; i += 256) {
       const int t = i % p.T;
@@ -286,7 +294,8 @@ __global__ __launch_bounds__(256) void dl_norm_in_kernel(LayerParams p) {
   }
 }
 
-// q, k, v of the pass's columns: sum of the partial tiles, rotary embedding on q and k, bf16, head-major layout
+// q, k, v of the pass's columns: sum of the partial tiles times the norm's scalar, rotary embedding on q and k,
+// bf16, head-major layout
 __global__ __launch_bounds__(256) void dl_qkv_finish_kernel(LayerParams p, SkinnyPlan pl) {
   const int half = p.dh / 2;
   const int per_col = 3 * p.H * half;
@@ -295,7 +304,8 @@ __global__ __launch_bounds__(256) void dl_qkv_finish_kernel(LayerParams p, Skinn
     const int hq = rem / half, i = rem - hq * half;  // hq: 0..H-1 q heads, H..2H-1 k heads, 2H..3H-1 v heads
     const int col = p.col0 + cl, b = col / p.T, t = col - b * p.T;
     const int row = hq * p.dh + i;
-    float a = sg_result(p.part, pl, cl, row), c = sg_result(p.part, pl, cl, row + half);
+    const float inv = inv_rms(p.ss1, col, p.D / 256, p.D, p.eps);
+    float a = inv * sg_result(p.part, pl, cl, row), c = inv * sg_result(p.part, pl, cl, row + half);
     const int kind = hq / p.H, h = hq - kind * p.H;
     if (kind < 2) {
       // pair (i, i + dh/2) turned by the angle pos * theta^(-2i/dh)
@@ -322,28 +332,27 @@ __global__ __launch_bounds__(256) void dl_attn_rows_kernel(LayerParams p) {
   }
 }
 
-// h1 = x + attention projection; xn2 = RMSNorm(h1) * ln2.  One block per column of the pass.
+// h1 = x + attention projection; h1 * ln2 (as two bf16 numbers) and the partial sums of h1^2.
+// One block per (column of the pass, 256 elements).
 __global__ __launch_bounds__(256) void dl_oproj_finish_kernel(LayerParams p, SkinnyPlan pl) {
   __shared__ float red[4];
-  const int cl = blockIdx.x, col = p.col0 + cl, tid = threadIdx.x;
-  float ss = 0.f;
-  for (int d = tid; d < p.D; d += 256) {
-    const float v = bf16_bits_to_float(p.x[(size_t)col * p.D + d]) + sg_result(p.part, pl, cl, d);
-    p.h1[(size_t)col * p.D + d] = v;
-    ss += v * v;
-  }
-  ss = block_sum_256(ss, red);
-  const float inv = 1.0f / sqrtf(ss / (float)p.D + p.eps);
-  for (int d = tid; d < p.D; d += 256)
-    store_split(p.xn2, (size_t)p.B * p.T * p.D, (size_t)col * p.D + d,
-                p.h1[(size_t)col * p.D + d] * inv * bf16_bits_to_float(p.ln2[d]));
+  const int nseg = p.D / 256;
+  const int cl = blockIdx.x / nseg, seg = blockIdx.x - cl * nseg, tid = threadIdx.x;
+  const int col = p.col0 + cl, d = seg * 256 + tid;
+  const size_t o = (size_t)col * p.D + d;
+  const float v = bf16_bits_to_float(p.x[o]) + sg_result(p.part, pl, cl, d);
+  p.h1[o] = v;
+  store_split(p.xn2, (size_t)p.B * p.T * p.D, o, v * bf16_bits_to_float(p.ln2[d]));
+  const float ss = block_sum_256(v * v, red);
+  if (tid == 0) p.ss2[col * nseg + seg] = ss;
 }
 
 // act = silu(gate) * up; rows [0, F) of the fused matrix are the gate, rows [F, 2F) the up projection
 __global__ __launch_bounds__(256) void dl_gate_finish_kernel(LayerParams p, SkinnyPlan pl) {
   for (int idx = blockIdx.x * 256 + threadIdx.x; idx < p.cols * p.F; idx += gridDim.x * 256) {
     const int cl = idx / p.F, f = idx - cl * p.F;
-    const float gt = sg_result(p.part, pl, cl, f), up = sg_result(p.part, pl, cl, p.F + f);
+    const float inv = inv_rms(p.ss2, p.col0 + cl, p.D / 256, p.D, p.eps);
+    const float gt = inv * sg_result(p.part, pl, cl, f), up = inv * sg_result(p.part, pl, cl, p.F + f);
     store_split(p.act, (size_t)p.B * p.T * p.F, (size_t)(p.col0 + cl) * p.F + f, gt / (1.0f + expf(-gt)) * up);
   }
 }
@@ -408,7 +417,7 @@ static bool make_plan(SkinnyPlan& pl, int N, int K, int cols, int cus) {
 }
 
 struct LayerWorkspace {
-  size_t xn, q, attn, arows, h1, xn2, act, n_rows, causal, part, total;
+  size_t xn, q, attn, arows, h1, xn2, act, n_rows, causal, ss1, ss2, part, total;
 };
 static LayerWorkspace layer_workspace(int B, int T, int D, int H, int F, int cus) {
   LayerWorkspace w;
@@ -418,6 +427,7 @@ static LayerWorkspace layer_workspace(int B, int T, int D, int H, int F, int cus
   w.xn = carve(BT * D * 4); w.q = carve(BT * D * 2); w.attn = carve(BT * D * 4); w.arows = carve(BT * D * 4);
   w.h1 = carve(BT * D * 4); w.xn2 = carve(BT * D * 4); w.act = carve(BT * F * 4);
   w.n_rows = carve((size_t)B * 4); w.causal = carve(BT * 8);
+  w.ss1 = carve(BT * (D / 256 + 1) * 4); w.ss2 = carve(BT * (D / 256 + 1) * 4);
   size_t max_floats = 0;
   const int shapes[4][2] = {{3 * D, D}, {D, D}, {2 * F, D}, {D, F}};
   for (auto& s : shapes) {
@@ -496,7 +506,7 @@ extern "C" int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
   p.xn = (unsigned short*)(ws + lw.xn); p.q = q_out ? (unsigned short*)q_out : (unsigned short*)(ws + lw.q); p.attn = (float*)(ws + lw.attn);
   p.arows = (unsigned short*)(ws + lw.arows); p.h1 = (float*)(ws + lw.h1); p.xn2 = (unsigned short*)(ws + lw.xn2);
   p.act = (unsigned short*)(ws + lw.act); p.n_rows = (int32_t*)(ws + lw.n_rows);
-  p.causal = (unsigned long long*)(ws + lw.causal);
+  p.causal = (unsigned long long*)(ws + lw.causal); p.ss1 = (float*)(ws + lw.ss1); p.ss2 = (float*)(ws + lw.ss2);
   p.k_new = (unsigned short*)k_new; p.v_new = (unsigned short*)v_new; p.out = (unsigned short*)out; p.out_f32 = out_f32;
   p.part = (const float*)(ws + lw.part); p.col0 = 0; p.cols = 0;
   const int BT = B * T;
@@ -519,7 +529,7 @@ extern "C" int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
   };
   auto blocks_for = [](long long n) { long long b = (n + 255) / 256; return (unsigned)(b > 1024 ? 1024 : (b < 1 ? 1 : b)); };
 
-  hipLaunchKernelGGL(dl_norm_in_kernel, dim3(BT), dim3(256), 0, st, p);
+  hipLaunchKernelGGL(dl_scale_in_kernel, dim3(BT * (D / 256)), dim3(256), 0, st, p);
   CTCSPEC_HIP(ctx, hipGetLastError());
   int rc = gemm_passes(w->wqkv, 3 * D, D, p.xn, [&](const SkinnyPlan& pl) {
     hipLaunchKernelGGL(dl_qkv_finish_kernel, dim3(blocks_for((long long)p.cols * 3 * H * (p.dh / 2))), dim3(256), 0, st, p, pl);
@@ -531,7 +541,7 @@ extern "C" int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
   hipLaunchKernelGGL(dl_attn_rows_kernel, dim3(blocks_for((long long)BT * D)), dim3(256), 0, st, p);
   CTCSPEC_HIP(ctx, hipGetLastError());
   rc = gemm_passes(w->wo, D, D, p.arows, [&](const SkinnyPlan& pl) {
-    hipLaunchKernelGGL(dl_oproj_finish_kernel, dim3(p.cols), dim3(256), 0, st, p, pl);
+    hipLaunchKernelGGL(dl_oproj_finish_kernel, dim3(p.cols * (D / 256)), dim3(256), 0, st, p, pl);
   });
   if (rc != CTCSPEC_OK) return rc;
   rc = gemm_passes(w->wgu, 2 * F, D, p.xn2, [&](const SkinnyPlan& pl) {
