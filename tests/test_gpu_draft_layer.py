@@ -92,6 +92,11 @@ def test_draft_layer_full_size(pkg):
     _check(pkg, 7, 1, 8, 4096, 32, 11008, [2048], 2048 + 128)
 
 
+def test_draft_layer_full_size_two_sequences(pkg):
+    """16 columns at the 7B shape: two MFMA column tiles, nine k groups in the down projection."""
+    _check(pkg, 8, 2, 8, 4096, 32, 11008, [300, 50], 320)
+
+
 def test_draft_layer_feeds_the_draft_head(pkg):
     """The layer's bf16 output is what ctc_draft_topk takes as hidden states: the chained call must agree with the
     oracle's head run on the very same bf16 states."""
