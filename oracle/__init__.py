@@ -22,3 +22,4 @@ from .attention import tree_attention  # noqa: F401
 from .accept import accept_longest, verifier_argmax  # noqa: F401
 from .verify import verifier_head_argmax, argmax_rows, kv_commit  # noqa: F401
 from .draft_layer import draft_layer, draft_layer_qkv, draft_layer_attend, rms_norm, rope, silu  # noqa: F401
+from .sum_score import ctc_sequence_logprob, sum_scores, ranks_desc  # noqa: F401
