@@ -48,6 +48,7 @@ def parse_args():
     ap.add_argument("--full-depth-steps", type=int, default=24)
     ap.add_argument("--no-closed-step", action="store_true")
     ap.add_argument("--no-draft-layer", action="store_true")
+    ap.add_argument("--no-sum-score", action="store_true")
     ap.add_argument("--draft-layer-ffn", type=int, default=0,
                     help="feed-forward width of the draft module's layer (0: the base family's, 43/16 of D)")
     ap.add_argument("--cpu-steps", type=int, default=2)
@@ -398,6 +399,33 @@ def main():
                        "layer_plus_step_us": dls_us,
                        "layer_plus_step_verified_tokens_per_sec": int(n_nodes.sum()) / (dls_us * 1e-6)}
 
+    # Eq. 5 variant of the candidates' value: one more KB-sized call on the step's logits and candidates
+    sum_score = None
+    if not args.no_sum_score:
+        with_logits = lib.ctc_draft_topk(ctx, d_hidden, d_w[0], d_bias, k, want_logits=True)
+        ss_out = {"cand_logp_sum": torch.empty((B, cfg.beam), dtype=torch.float32, device="cuda"),
+                  "cand_rank_sum": i32(B, cfg.beam)}
+        ss_call = lib.prepared(ctx, "ctc_sum_score", with_logits["logits"], with_logits["lse"], cand_tokens, cand_len,
+                               n_cand, B, T, cfg.Vp1, cfg.blank_id, cfg.beam, ss_out["cand_logp_sum"],
+                               ss_out["cand_rank_sum"])
+        for _ in range(5):
+            ss_call()
+        torch.cuda.synchronize()
+        n_ss = 64
+        ss_ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_ss + 1)]
+        ss_ev[0].record()
+        for i in range(n_ss):
+            ss_call()
+            ss_ev[i + 1].record()
+        torch.cuda.synchronize()
+        ss_us = np.array([ss_ev[i].elapsed_time(ss_ev[i + 1]) * 1e3 for i in range(n_ss)])
+        changed = int((ss_out["cand_rank_sum"].cpu().numpy() != np.arange(cfg.beam)[None, :]).sum()
+                      - int((ss_out["cand_rank_sum"].cpu().numpy() < 0).sum()))
+        sum_score = {"call": "ctc_sum_score", "us_per_call_median": float(np.median(ss_us)),
+                     "candidates": n_cand.cpu().numpy().tolist(),
+                     "candidates_whose_rank_differs_from_the_best_alignment_order": changed,
+                     "bound": "latency (KB-sized: one wavefront per candidate, T dependent steps)"}
+
     head_b, attn_b, total_b = algorithmic_bytes(cfg, x.ctx_len, n_nodes)
     if n_layers > 0:
         fd_bytes = total_b + (n_layers - 1) * attn_b
@@ -441,6 +469,7 @@ def main():
         "full_depth_variant": full_depth,
         "closed_step_variant": closed,
         "draft_layer_variant": draft_layer,
+        "sum_score_variant": sum_score,
         "roofline": {"kernel": "lmhead_bf16_mfma_kernel (ctc_draft_topk)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": read_traffic_summary(), "algorithmic_bytes_per_launch": head_b,

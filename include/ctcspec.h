@@ -297,6 +297,26 @@ int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* x, const
                         float rope_theta, void* workspace, size_t workspace_bytes, void* q_out, void* k_new,
                         void* v_new, void* out, float* out_f32);
 
+/*
+ * ctc_sum_score - value of the candidate drafts under Eq. 5 (Sec. 3.2): log P(Y|X) summed over every raw
+ * sequence of T tokens, from the whole vocabulary plus the blank, that the collapse rule turns into Y, each
+ * raw sequence weighted by Eq. 6; computed with the forward recursion of the CTC paper the section cites.
+ * ctc_collapse_tree values a draft by its best alignment alone; this is the alternative, and the rank order it
+ * induces.  Takes the optional logits output and the lse output of ctc_draft_topk and the candidate lists of
+ * ctc_collapse_tree; changes neither.
+ *
+ * logits        [B,T,Vp1] float device in
+ * lse           [B,T] float device in: log p_t(v) = logits[b,t,v] - lse[b,t]
+ * cand_tokens   [B,beam,T] int32 device in; cand_len [B,beam] int32 device in; n_cand [B] int32 device in
+ * cand_logp_sum [B,beam] float device out, -inf beyond n_cand (and for a draft longer than T slots can hold)
+ * cand_rank_sum [B,beam] int32 device out: position of candidate i in the order (cand_logp_sum descending,
+ *               index ascending), decided on the fp32 values; -1 beyond n_cand
+ * Limits: T <= CTCSPEC_MAX_SLOTS, beam <= CTCSPEC_MAX_BEAM, B within the context's limits.
+ */
+int ctc_sum_score(ctcspec_ctx* ctx, const float* logits, const float* lse, const int32_t* cand_tokens,
+                  const int32_t* cand_len, const int32_t* n_cand, int B, int T, int Vp1, int32_t blank_id, int beam,
+                  float* cand_logp_sum, int32_t* cand_rank_sum);
+
 #ifdef __cplusplus
 }
 #endif

@@ -16,6 +16,7 @@ EXPORTS = (
     "ctcspec_create", "ctcspec_destroy", "ctcspec_set_stream", "ctcspec_last_error",
     "ctcspec_workspace_bytes", "ctcspec_profile_draft_head", "ctcspec_draft_head_kernel_ms", "ctc_draft_topk", "ctc_collapse_tree", "tree_verify_attn",
     "accept_longest", "verify_head_argmax", "kv_commit", "draft_layer_workspace_bytes", "draft_layer_forward",
+    "ctc_sum_score",
 )
 
 CTCSPEC_F32, CTCSPEC_BF16 = 0, 1
@@ -86,6 +87,8 @@ def load_library():
     lib.draft_layer_forward.restype = c_int
     lib.draft_layer_forward.argtypes = ([c_void_p, c_int, c_void_p, POINTER(_LayerWeights)] + [c_void_p] * 5 +
                                         [c_int] * 6 + [c_float, c_float, c_void_p, c_size_t] + [c_void_p] * 5)
+    lib.ctc_sum_score.restype = c_int
+    lib.ctc_sum_score.argtypes = [c_void_p] * 6 + [c_int, c_int, c_int, c_int32, c_int, c_void_p, c_void_p]
     _LIB = lib
     return lib
 
@@ -341,4 +344,18 @@ def draft_layer_forward(ctx, x, weights, pos0, k_cache, v_cache, kv_off, ctx_len
                                      rms_eps, rope_theta, _ptr(workspace, torch.uint8), workspace.numel(),
                                      _ptr(res.get("q")), _ptr(res["k_new"]), _ptr(res["v_new"]), _ptr(res["out"]), _ptr(res.get("out_f32")))
     ctx._check(rc, "draft_layer_forward")
+    return res
+
+
+def ctc_sum_score(ctx, logits, lse, cand_tokens, cand_len, n_cand, blank_id, *, out=None):
+    """logits [B,T,V+1] f32, lse [B,T] f32, candidates of ctc_collapse_tree -> dict(cand_logp_sum, cand_rank_sum)."""
+    B, T, Vp1 = logits.shape
+    beam = cand_tokens.shape[1]
+    dev = logits.device
+    res = {"cand_logp_sum": _out(out, "cand_logp_sum", (B, beam), torch.float32, dev),
+           "cand_rank_sum": _out(out, "cand_rank_sum", (B, beam), torch.int32, dev)}
+    rc = ctx.lib.ctc_sum_score(ctx.handle, _ptr(logits, torch.float32), _ptr(lse, torch.float32),
+                               _ptr(cand_tokens, torch.int32), _ptr(cand_len, torch.int32), _ptr(n_cand, torch.int32),
+                               B, T, Vp1, blank_id, beam, _ptr(res["cand_logp_sum"]), _ptr(res["cand_rank_sum"]))
+    ctx._check(rc, "ctc_sum_score")
     return res
