@@ -237,3 +237,114 @@ def test_attention_repeats_bit_identically(pkg, cfg_index):
     for o in outs[1:]:
         assert np.array_equal(o, outs[0])
     ctx.close()
+
+
+def test_whole_decode_step_graph_replay(pkg):
+    """Every call of a decode step in one HIP graph - the draft module's layer, the draft head, collapse/tree,
+    the Eq. 5 values, verification attention, the base head, acceptance and the history update: replays,
+    with eager work and synchronisation between them, must reproduce the eager results bit for bit (the
+    history update writes the same rows each time: ctx_len is an input, the new length goes to its own buffer)."""
+    from paper_2412_00061_amd.binding import CTCSPEC_BF16
+    B, T, k, D, H, F, V, N, beam, cap = 1, 8, 4, 256, 2, 512, 400, 32, 32, 96
+    dh = D // H
+    c = workloads.make_draft_layer_case(21, B, T, D, H, F, [40], cap, dtype="bf16")
+    rng = np.random.Generator(np.random.PCG64(22))
+    rnd = lambda *s, scale=1.0: workloads.round_to_storage(rng.standard_normal(s, dtype=np.float32) * scale, "bf16")
+    ctx = pkg.Context(max_batch=B, max_slots=T, max_topk=k, max_vocab_rows=V + 1, max_nodes=N, max_heads=H,
+                      max_head_dim=dh)
+    w = c.weights
+    lw = pkg.layer_weights(to_device(w["ln1"], "bf16"), to_device(np.concatenate([w["wq"], w["wk"], w["wv"]]), "bf16"),
+                           to_device(w["wo"], "bf16"), to_device(w["ln2"], "bf16"),
+                           to_device(np.concatenate([w["wg"], w["wu"]]), "bf16"), to_device(w["wd"], "bf16"))
+    x_in, pos0 = to_device(c.x, "bf16"), dev_i32(c.pos0)
+    kc_draft, vc_draft = to_device(c.k_cache, "bf16"), to_device(c.v_cache, "bf16")
+    d_off, d_len = dev_i64(c.kv_off), dev_i32(c.ctx_len)
+    w_draft, w_base = to_device(rnd(V + 1, D, scale=0.05), "bf16"), to_device(rnd(V, D, scale=0.05), "bf16")
+    q, kt, vt = (to_device(rnd(B, H, N, dh), "bf16") for _ in range(3))
+    kc, vc = to_device(np.nan_to_num(c.k_cache), "bf16"), to_device(np.nan_to_num(c.v_cache), "bf16")
+    node_hidden = to_device(rnd(B, N, D), "bf16")
+    root = dev_i32(np.array([7], dtype=np.int32))
+
+    def i32(*shape):
+        return torch.full(shape, -7, dtype=torch.int32, device="cuda")
+
+    def f32(*shape):
+        return torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+
+    ws = torch.empty(pkg.draft_layer_workspace_bytes(B, T, D, H, F), dtype=torch.uint8, device="cuda")
+    bf = lambda *shape: torch.zeros(shape, dtype=torch.bfloat16, device="cuda")
+    o = dict(slot=bf(B, T, D), k_new=bf(B, H, T, dh), v_new=bf(B, H, T, dh),
+             topk_id=i32(B, T, k), topk_logp=f32(B, T, k), lse=f32(B, T), logits=f32(B, T, V + 1),
+             n_cand=i32(B), cand_tokens=i32(B, beam, T), cand_len=i32(B, beam), cand_score=f32(B, beam),
+             cand_leaf=i32(B, beam), n_nodes=i32(B), node_token=i32(B, N), node_parent=i32(B, N),
+             node_depth=i32(B, N), anc_mask=torch.zeros((B, N, 1), dtype=torch.int64, device="cuda"),
+             sum=f32(B, beam), rank=i32(B, beam), attn=f32(B, H, N, dh), target=i32(B, N),
+             accept_len=i32(B), accept_nodes=i32(B, T + 1), accept_tokens=i32(B, T + 1), next_token=i32(B),
+             new_len=i32(B))
+    P = pkg.prepared
+    calls = (
+        P(ctx, "draft_layer_forward", CTCSPEC_BF16, x_in, lw, pos0, kc_draft, vc_draft, d_off, d_len, cap, B, T, D, H, F,
+          c.eps, c.theta, ws, ws.numel(), None, o["k_new"], o["v_new"], o["slot"], None),
+        P(ctx, "ctc_draft_topk", CTCSPEC_BF16, o["slot"], w_draft, None, B, T, D, V + 1, k, o["topk_id"],
+          o["topk_logp"], o["lse"], o["logits"]),
+        P(ctx, "ctc_collapse_tree", o["topk_id"], o["topk_logp"], root, B, T, k, V, beam, N, o["n_cand"],
+          o["cand_tokens"], o["cand_len"], o["cand_score"], o["cand_leaf"], o["n_nodes"], o["node_token"],
+          o["node_parent"], o["node_depth"], o["anc_mask"]),
+        P(ctx, "ctc_sum_score", o["logits"], o["lse"], o["cand_tokens"], o["cand_len"], o["n_cand"], B, T, V + 1, V,
+          beam, o["sum"], o["rank"]),
+        P(ctx, "tree_verify_attn", CTCSPEC_BF16, q, kc, vc, d_off, d_len, cap, kt, vt, o["n_nodes"], o["anc_mask"],
+          B, H, dh, N, 1.0 / math.sqrt(dh), o["attn"]),
+        P(ctx, "verify_head_argmax", CTCSPEC_BF16, node_hidden, w_base, o["n_nodes"], B, N, D, V, o["target"], None),
+        P(ctx, "accept_longest", o["n_nodes"], o["node_token"], o["node_parent"], o["node_depth"], o["target"], B, T,
+          N, o["accept_len"], o["accept_nodes"], o["accept_tokens"], o["next_token"]),
+        P(ctx, "kv_commit", CTCSPEC_BF16, kt, vt, o["accept_len"], o["accept_nodes"], T, d_off, d_len, cap, B, H, dh,
+          N, kc, vc, o["new_len"]),
+    )
+
+    def run():
+        for call in calls:
+            call()
+
+    def snapshot():
+        torch.cuda.synchronize()
+        n = int(o["n_nodes"][0])
+        snap = {}
+        for name, t in o.items():
+            a = t.float().cpu().numpy().copy() if t.dtype == torch.bfloat16 else t.cpu().numpy().copy()
+            if name == "attn":
+                a[:, :, n:] = 0
+            snap[name] = a
+        snap["kc"], snap["vc"] = kc.float().cpu().numpy().copy(), vc.float().cpu().numpy().copy()
+        return snap
+
+    def scrub():
+        for name, t in o.items():
+            if t.dtype == torch.float32:
+                t.fill_(float("nan"))
+            elif t.dtype == torch.bfloat16:
+                t.zero_()
+            else:
+                t.fill_(-7 if name != "anc_mask" else 0)
+
+    run()
+    eager = snapshot()
+    assert int(eager["n_nodes"][0]) > 1 and int(eager["new_len"][0]) == 40 + int(eager["accept_len"][0]) + 1
+    stream = torch.cuda.Stream()
+    ctx.set_stream(stream)
+    with torch.cuda.stream(stream):
+        run()  # warm-up on the capture stream: one-time function attribute calls happen outside the capture
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            run()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        scrub()
+        torch.cuda.synchronize()
+        graph.replay()
+        _same(eager, snapshot())
+        junk = torch.randn(1 << 16, device="cuda").sum()  # eager work between the replays
+        torch.cuda.synchronize()
+        assert math.isfinite(float(junk))
+    ctx.set_stream(torch.cuda.current_stream())
+    ctx.close()
