@@ -17,7 +17,7 @@ from .collapse import (  # noqa: F401
     alignment_scores_f32,
     collapse_candidates,
 )
-from .tree import build_prefix_tree, ancestor_mask, pack_mask_u64, collapse_tree  # noqa: F401
+from .tree import build_prefix_tree, ancestor_mask, pack_mask_u64, collapse_tree, raw_tree  # noqa: F401
 from .attention import tree_attention  # noqa: F401
 from .accept import accept_longest, verifier_argmax  # noqa: F401
 from .verify import verifier_head_argmax, argmax_rows, kv_commit  # noqa: F401

@@ -4,7 +4,7 @@ Test infrastructure only (see the package docstring).
 """
 import numpy as np
 
-from .collapse import collapse_candidates
+from .collapse import alignment_ranks, alignment_scores_f32, collapse_candidates
 
 
 def build_prefix_tree(cand_tokens, root_token, max_nodes):
@@ -97,5 +97,57 @@ def collapse_tree(topk_id, topk_logp, root_token, blank, beam, max_nodes):
         "n_cand": n_cand, "cand_tokens": cand_tokens, "cand_len": cand_len, "cand_score": cand_score,
         "cand_leaf": cand_leaf, "cand_rep": cand_rep, "n_nodes": n_nodes, "node_token": node_token,
         "node_parent": node_parent, "node_depth": node_depth, "mask": mask,
+        "anc_mask": pack_mask_u64(mask, max_nodes),
+    }
+
+
+def raw_tree(topk_id, topk_logp, root_token, blank, beam, max_nodes):
+    """The layout Sec. 3.1 describes literally, for one sequence: the raw candidates keep their full length T
+    (blanks and repeats included) and are combined in a token tree as they are; the CTC transform does not
+    shorten them but marks the positions it removes - blanks, and tokens equal to the raw token right before
+    them - and the attention map hides those positions from everything below them.
+
+    Raw candidates are the k^T slot combinations valued by Eq. 6 (float32, left to right), ordered by
+    (score descending, idx ascending); the first `beam` are kept and inserted into a prefix tree over RAW
+    tokens under the same node cap rule as the collapsed tree.  The first slot has no raw token before it
+    (the root is the base model's token, not a draft slot).  mask[i, j]: j is i itself, or the root, or an
+    ancestor of i that is not removed.
+
+    Returns the padded arrays of collapse_tree plus node_removed (1 removed, 0 kept, -1 no node)."""
+    ids = np.asarray(topk_id)
+    T, k = ids.shape
+    ranks = alignment_ranks(T, k)
+    score = alignment_scores_f32(topk_logp, ranks)
+    order = sorted(range(ranks.shape[0]), key=lambda i: (-float(score[i]), i))[:beam]
+    raws = [tuple(int(ids[t, ranks[i, t]]) for t in range(T)) for i in order]
+    tok, par, dep, leaf = build_prefix_tree(raws, root_token, max_nodes)
+    n_cand, n_nodes = len(raws), len(tok)
+    removed = [0] * n_nodes
+    for i in range(1, n_nodes):
+        repeat = dep[i] >= 2 and tok[i] == tok[par[i]]
+        removed[i] = 1 if (tok[i] == blank or repeat) else 0
+    mask = np.zeros((n_nodes, n_nodes), dtype=bool)
+    for i in range(n_nodes):
+        mask[i, i] = True
+        j = par[i]
+        while j >= 0:
+            if not removed[j]:
+                mask[i, j] = True
+            j = par[j]
+    cand_tokens = np.full((beam, T), -1, dtype=np.int32)
+    cand_len = np.zeros(beam, dtype=np.int32)
+    cand_score = np.full(beam, -np.inf, dtype=np.float32)
+    cand_leaf = np.full(beam, -1, dtype=np.int32)
+    for c, (raw, i) in enumerate(zip(raws, order)):
+        cand_tokens[c], cand_len[c], cand_score[c], cand_leaf[c] = raw, T, score[i], leaf[c]
+    node_token = np.full(max_nodes, -1, dtype=np.int32)
+    node_parent = np.full(max_nodes, -1, dtype=np.int32)
+    node_depth = np.full(max_nodes, -1, dtype=np.int32)
+    node_removed = np.full(max_nodes, -1, dtype=np.int32)
+    node_token[:n_nodes], node_parent[:n_nodes], node_depth[:n_nodes], node_removed[:n_nodes] = tok, par, dep, removed
+    return {
+        "n_cand": n_cand, "cand_tokens": cand_tokens, "cand_len": cand_len, "cand_score": cand_score,
+        "cand_leaf": cand_leaf, "n_nodes": n_nodes, "node_token": node_token, "node_parent": node_parent,
+        "node_depth": node_depth, "node_removed": node_removed, "mask": mask,
         "anc_mask": pack_mask_u64(mask, max_nodes),
     }
