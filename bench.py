@@ -49,6 +49,7 @@ def parse_args():
     ap.add_argument("--no-closed-step", action="store_true")
     ap.add_argument("--no-draft-layer", action="store_true")
     ap.add_argument("--no-sum-score", action="store_true")
+    ap.add_argument("--no-literal-layout", action="store_true")
     ap.add_argument("--draft-layer-ffn", type=int, default=0,
                     help="feed-forward width of the draft module's layer (0: the base family's, 43/16 of D)")
     ap.add_argument("--cpu-steps", type=int, default=2)
@@ -426,6 +427,49 @@ def main():
                      "candidates_whose_rank_differs_from_the_best_alignment_order": changed,
                      "bound": "latency (KB-sized: one wavefront per candidate, T dependent steps)"}
 
+    # A/B of the tree layout: the paper's literal one (raw candidates at full length, removed positions masked)
+    # under the same node cap, against the collapsed tree the step uses.  Statistics only; same kernel otherwise.
+    literal = None
+    if not args.no_literal_layout:
+        raw_out = lib.ctc_raw_tree(ctx, topk_id, topk_logp, d_root, cfg.blank_id, cfg.beam, N)
+        raw_call = lib.prepared(ctx, "ctc_raw_tree", topk_id, topk_logp, d_root, B, T, k, cfg.blank_id, cfg.beam, N,
+                                *(raw_out[n_] for n_ in ("n_cand", "cand_tokens", "cand_len", "cand_score", "cand_leaf",
+                                                         "n_nodes", "node_token", "node_parent", "node_depth",
+                                                         "anc_mask", "node_removed")))
+        for _ in range(5):
+            raw_call()
+        torch.cuda.synchronize()
+        rt_ev = [torch.cuda.Event(enable_timing=True) for _ in range(65)]
+        rt_ev[0].record()
+        for i in range(64):
+            raw_call()
+            rt_ev[i + 1].record()
+        torch.cuda.synchronize()
+        rt_us = float(np.median([rt_ev[i].elapsed_time(rt_ev[i + 1]) * 1e3 for i in range(64)]))
+        r_tok, r_leaf, r_rem, r_nn = (raw_out[n_].cpu().numpy() for n_ in ("cand_tokens", "cand_leaf", "node_removed",
+                                                                           "n_nodes"))
+        c_leaf, c_nc = cand_leaf.cpu().numpy(), n_cand.cpu().numpy()
+        drafts_raw, drafts_col = [], []
+        for b in range(B):
+            seen = set()
+            for c in range(cfg.beam):
+                if r_leaf[b, c] < 0:
+                    continue
+                y, prev = [], None
+                for tok in r_tok[b, c]:
+                    if tok != cfg.blank_id and tok != prev:
+                        y.append(int(tok))
+                    prev = tok
+                if y:
+                    seen.add(tuple(y))
+            drafts_raw.append(len(seen))
+            drafts_col.append(int((c_leaf[b, :c_nc[b]] >= 0).sum()))
+        literal = {"call": "ctc_raw_tree", "us_per_call_median": rt_us, "node_cap": N,
+                   "nodes": r_nn.tolist(), "nodes_on_removed_positions": [(int((r_rem[b] == 1).sum())) for b in range(B)],
+                   "distinct_drafts_whole_in_the_tree": drafts_raw,
+                   "collapsed_layout_distinct_drafts_whole_in_the_tree": drafts_col,
+                   "collapsed_layout_nodes": n_nodes.tolist()}
+
     head_b, attn_b, total_b = algorithmic_bytes(cfg, x.ctx_len, n_nodes)
     if n_layers > 0:
         fd_bytes = total_b + (n_layers - 1) * attn_b
@@ -470,6 +514,7 @@ def main():
         "closed_step_variant": closed,
         "draft_layer_variant": draft_layer,
         "sum_score_variant": sum_score,
+        "literal_layout_variant": literal,
         "roofline": {"kernel": "lmhead_bf16_mfma_kernel (ctc_draft_topk)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": read_traffic_summary(), "algorithmic_bytes_per_launch": head_b,

@@ -317,6 +317,26 @@ int ctc_sum_score(ctcspec_ctx* ctx, const float* logits, const float* lse, const
                   const int32_t* cand_len, const int32_t* n_cand, int B, int T, int Vp1, int32_t blank_id, int beam,
                   float* cand_logp_sum, int32_t* cand_rank_sum);
 
+/*
+ * ctc_raw_tree - the tree layout that Sec. 3.1 describes literally, as an alternative to ctc_collapse_tree: the
+ * raw candidates keep their full length T (blanks and repeats included) and form the token tree as they are; the
+ * CTC transform marks the positions it removes (a blank; a token equal to the raw token of the slot before it -
+ * the root is no slot) and the attention map hides those positions from everything below them.
+ * Same arguments, layouts, limits and error behaviour as ctc_collapse_tree, with these differences:
+ * candidates   the `beam` best raw candidates (Eq. 6 value, ties to the smaller index), not collapsed:
+ *              cand_tokens holds raw tokens (the blank id included), cand_len = T
+ * tree         prefix tree over raw tokens, same node cap rule
+ * anc_mask     bit j of row i: j == i, or j an ancestor of i (the root included) that is not removed
+ * node_removed [B,max_nodes] int32 device out: 1 removed, 0 kept, -1 beyond n_nodes
+ * tree_verify_attn takes the result unchanged; a kept node's output equals that of the collapsed tree's node for
+ * the same collapsed prefix.  The layout spends nodes on removed positions: under the same node cap it holds
+ * fewer distinct drafts, which is why the step uses ctc_collapse_tree.
+ */
+int ctc_raw_tree(ctcspec_ctx* ctx, const int32_t* topk_id, const float* topk_logp, const int32_t* root_token, int B,
+                 int T, int k, int32_t blank_id, int beam, int max_nodes, int32_t* n_cand, int32_t* cand_tokens,
+                 int32_t* cand_len, float* cand_score, int32_t* cand_leaf, int32_t* n_nodes, int32_t* node_token,
+                 int32_t* node_parent, int32_t* node_depth, uint64_t* anc_mask, int32_t* node_removed);
+
 #ifdef __cplusplus
 }
 #endif

@@ -108,7 +108,8 @@ def raw_tree(topk_id, topk_logp, root_token, blank, beam, max_nodes):
     them - and the attention map hides those positions from everything below them.
 
     Raw candidates are the k^T slot combinations valued by Eq. 6 (float32, left to right), ordered by
-    (score descending, idx ascending); the first `beam` are kept and inserted into a prefix tree over RAW
+    (score descending, idx ascending); identical raw sequences (possible only when a slot's list names a
+    token twice) count once, at their first place; the first `beam` are kept and inserted into a prefix tree over RAW
     tokens under the same node cap rule as the collapsed tree.  The first slot has no raw token before it
     (the root is the base model's token, not a draft slot).  mask[i, j]: j is i itself, or the root, or an
     ancestor of i that is not removed.
@@ -118,8 +119,16 @@ def raw_tree(topk_id, topk_logp, root_token, blank, beam, max_nodes):
     T, k = ids.shape
     ranks = alignment_ranks(T, k)
     score = alignment_scores_f32(topk_logp, ranks)
-    order = sorted(range(ranks.shape[0]), key=lambda i: (-float(score[i]), i))[:beam]
-    raws = [tuple(int(ids[t, ranks[i, t]]) for t in range(T)) for i in order]
+    order, raws, seen = [], [], set()
+    for i in sorted(range(ranks.shape[0]), key=lambda i: (-float(score[i]), i)):
+        raw = tuple(int(ids[t, ranks[i, t]]) for t in range(T))
+        if raw in seen:      # a list that names a token twice: the same raw sequence again, not a new candidate
+            continue
+        seen.add(raw)
+        order.append(i)
+        raws.append(raw)
+        if len(raws) == beam:
+            break
     tok, par, dep, leaf = build_prefix_tree(raws, root_token, max_nodes)
     n_cand, n_nodes = len(raws), len(tok)
     removed = [0] * n_nodes

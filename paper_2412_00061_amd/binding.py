@@ -16,7 +16,7 @@ EXPORTS = (
     "ctcspec_create", "ctcspec_destroy", "ctcspec_set_stream", "ctcspec_last_error",
     "ctcspec_workspace_bytes", "ctcspec_profile_draft_head", "ctcspec_draft_head_kernel_ms", "ctc_draft_topk", "ctc_collapse_tree", "tree_verify_attn",
     "accept_longest", "verify_head_argmax", "kv_commit", "draft_layer_workspace_bytes", "draft_layer_forward",
-    "ctc_sum_score",
+    "ctc_sum_score", "ctc_raw_tree",
 )
 
 CTCSPEC_F32, CTCSPEC_BF16 = 0, 1
@@ -87,6 +87,8 @@ def load_library():
     lib.draft_layer_forward.restype = c_int
     lib.draft_layer_forward.argtypes = ([c_void_p, c_int, c_void_p, POINTER(_LayerWeights)] + [c_void_p] * 5 +
                                         [c_int] * 6 + [c_float, c_float, c_void_p, c_size_t] + [c_void_p] * 5)
+    lib.ctc_raw_tree.restype = c_int
+    lib.ctc_raw_tree.argtypes = lib.ctc_collapse_tree.argtypes + [c_void_p]
     lib.ctc_sum_score.restype = c_int
     lib.ctc_sum_score.argtypes = [c_void_p] * 6 + [c_int, c_int, c_int, c_int32, c_int, c_void_p, c_void_p]
     _LIB = lib
@@ -246,6 +248,35 @@ def ctc_collapse_tree(ctx, topk_id, topk_logp, root_token, blank_id, beam, max_n
         _ptr(res["cand_len"]), _ptr(res["cand_score"]), _ptr(res["cand_leaf"]), _ptr(res["n_nodes"]),
         _ptr(res["node_token"]), _ptr(res["node_parent"]), _ptr(res["node_depth"]), _ptr(res["anc_mask"]))
     ctx._check(rc, "ctc_collapse_tree")
+    return res
+
+
+def ctc_raw_tree(ctx, topk_id, topk_logp, root_token, blank_id, beam, max_nodes, *, out=None):
+    """The literal layout: raw candidates at full length, removed positions masked.  Outputs of ctc_collapse_tree
+    plus node_removed [B,max_nodes]."""
+    B, T, k = topk_id.shape
+    dev = topk_id.device
+    words = (max_nodes + 63) // 64
+    res = {
+        "n_cand": _out(out, "n_cand", (B,), torch.int32, dev),
+        "cand_tokens": _out(out, "cand_tokens", (B, beam, T), torch.int32, dev),
+        "cand_len": _out(out, "cand_len", (B, beam), torch.int32, dev),
+        "cand_score": _out(out, "cand_score", (B, beam), torch.float32, dev),
+        "cand_leaf": _out(out, "cand_leaf", (B, beam), torch.int32, dev),
+        "n_nodes": _out(out, "n_nodes", (B,), torch.int32, dev),
+        "node_token": _out(out, "node_token", (B, max_nodes), torch.int32, dev),
+        "node_parent": _out(out, "node_parent", (B, max_nodes), torch.int32, dev),
+        "node_depth": _out(out, "node_depth", (B, max_nodes), torch.int32, dev),
+        "anc_mask": _out(out, "anc_mask", (B, max_nodes, words), torch.int64, dev),
+        "node_removed": _out(out, "node_removed", (B, max_nodes), torch.int32, dev),
+    }
+    rc = ctx.lib.ctc_raw_tree(
+        ctx.handle, _ptr(topk_id, torch.int32), _ptr(topk_logp, torch.float32), _ptr(root_token, torch.int32),
+        B, T, k, blank_id, beam, max_nodes, _ptr(res["n_cand"]), _ptr(res["cand_tokens"]),
+        _ptr(res["cand_len"]), _ptr(res["cand_score"]), _ptr(res["cand_leaf"]), _ptr(res["n_nodes"]),
+        _ptr(res["node_token"]), _ptr(res["node_parent"]), _ptr(res["node_depth"]), _ptr(res["anc_mask"]),
+        _ptr(res["node_removed"]))
+    ctx._check(rc, "ctc_raw_tree")
     return res
 
 

@@ -52,6 +52,7 @@ struct CollapseParams {
   int32_t* node_parent;
   int32_t* node_depth;
   unsigned long long* anc_mask;
+  int32_t* node_removed;  // raw layout only
   unsigned char* ws;  // per-sequence global workspace base
 };
 
@@ -67,6 +68,7 @@ struct CollapseShared {
   int red[kWaves];
   float delta;
   int n_nodes;
+  int blank_code;  // raw layout: local code of the blank, -1 if no list holds it
   unsigned long long kept_ck[CTCSPEC_MAX_BEAM];
   int kept_len[CTCSPEC_MAX_BEAM];
   int kept_m[CTCSPEC_MAX_BEAM];
@@ -325,6 +327,8 @@ __device__ __forceinline__ float add_slots(float acc, bool have_acc, const float
 
 // Collapsed-sequence key of the raw candidate (a, b): 7-bit local token codes, position 0 in the low
 // bits, unused positions = kBlankCode.
+// RAW: nothing is merged or dropped - the key holds the raw candidate itself (the literal layout of Sec. 3.1).
+template <bool RAW>
 __device__ __forceinline__ unsigned long long collapse_key(const CollapseShared& s, const Digits4& da,
                                                            const Digits4& db, int T1, int T2, int k, int* len_out) {
   int cd[8];
@@ -341,7 +345,7 @@ __device__ __forceinline__ unsigned long long collapse_key(const CollapseShared&
   int len = 0, prev = -1;
 #pragma unroll
   for (int u = 0; u < 8; ++u) {
-    const bool emit = cd[u] >= 0 && cd[u] != prev && cd[u] != kBlankCode;
+    const bool emit = RAW ? cd[u] >= 0 : (cd[u] >= 0 && cd[u] != prev && cd[u] != kBlankCode);
     const int sh = 7 * len;
     key = emit ? ((key & ~(0x7full << sh)) | ((unsigned long long)cd[u] << sh)) : key;
     len += emit ? 1 : 0;
@@ -351,6 +355,7 @@ __device__ __forceinline__ unsigned long long collapse_key(const CollapseShared&
   return key;
 }
 
+template <bool RAW>
 __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   CollapseShared& s = *reinterpret_cast<CollapseShared*>(smem_raw);
@@ -389,9 +394,14 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
     if (lane < TK) {
       s.ids[lane] = id;
       s.logp[lane] = lp;
-      s.code[lane] = (id == p.blank_id) ? kBlankCode : cd;
+      s.code[lane] = (!RAW && id == p.blank_id) ? kBlankCode : cd;
     }
     if (lane == 0) s.delta = A * (16.0f / 8388608.0f);
+    if (RAW) {
+      const unsigned long long has = __ballot(lane < TK && id == p.blank_id);
+      const int bc = has ? __builtin_amdgcn_readlane(cd, __builtin_ctzll(has)) : -1;
+      if (lane == 0) s.blank_code = bc;
+    }
   }
   const int T1 = (T + 1) >> 1, T2 = T - T1;
   int n1 = 1, n2 = 1, pad1 = 1, pad2 = 1;
@@ -552,7 +562,7 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
         const int a = n2 == 1 ? idx : (int)__umulhi((unsigned)idx, p.magic_n2), bb = idx - a * n2;  // idx / n2
         int len;
         const unsigned long long c =
-            collapse_key(s, split_digits(a, pad1, k, magic), split_digits(bb, pad2, k, magic), T1, T2, k, &len);
+            collapse_key<RAW>(s, split_digits(a, pad1, k, magic), split_digits(bb, pad2, k, magic), T1, T2, k, &len);
         ck = len ? c : ~0ull;
       }
       ckeys[i] = ck;
@@ -709,14 +719,20 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
         const int f = (int)((creators[u] >> (8 * d)) & 0xff);
         const int node = path_node[d];
         if (node >= max_nodes) { leaf = -1; break; }
-        if (node < 64) m0 |= 1ull << node; else m1 |= 1ull << (node - 64);
+        // raw layout: a blank, or a token equal to the raw token right before it, is removed by the CTC transform -
+        // it sees its own prefix but nothing below it sees it
+        const int code = (int)((ck[u] >> (7 * d)) & 0x7f);
+        const bool removed = RAW && (code == s.blank_code || (d > 0 && code == (int)((ck[u] >> (7 * (d - 1))) & 0x7f)));
+        const unsigned long long b0 = node < 64 ? 1ull << node : 0ull, b1 = node < 64 ? 0ull : 1ull << (node - 64);
         if (f == c) {
-          node_token[node] = s.ids[(int)((ck[u] >> (7 * d)) & 0x7f)];
+          node_token[node] = s.ids[code];
           node_parent[node] = par;
           node_depth[node] = d + 1;
-          mask[(size_t)node * W] = m0;
-          if (W > 1) mask[(size_t)node * W + 1] = m1;
+          mask[(size_t)node * W] = m0 | b0;
+          if (W > 1) mask[(size_t)node * W + 1] = m1 | b1;
+          if (RAW) p.node_removed[(size_t)b * max_nodes + node] = removed ? 1 : 0;
         }
+        if (!removed) { m0 |= b0; m1 |= b1; }
         par = node;
         leaf = node;
       }
@@ -749,7 +765,9 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
       node_depth[0] = 0;
       mask[0] = 1ull;
       if (W > 1) mask[1] = 0ull;
+      if (RAW) p.node_removed[(size_t)b * max_nodes] = 0;
     } else if (i >= n_nodes) {
+      if (RAW) p.node_removed[(size_t)b * max_nodes + i] = -1;
       node_token[i] = -1;
       node_parent[i] = -1;
       node_depth[i] = -1;
@@ -763,28 +781,29 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
 
 using namespace ctcspec;
 
-extern "C" int ctc_collapse_tree(ctcspec_ctx* ctx, const int32_t* topk_id, const float* topk_logp,
-                                 const int32_t* root_token, int B, int T, int k, int32_t blank_id, int beam,
-                                 int max_nodes, int32_t* n_cand, int32_t* cand_tokens, int32_t* cand_len,
-                                 float* cand_score, int32_t* cand_leaf, int32_t* n_nodes, int32_t* node_token,
-                                 int32_t* node_parent, int32_t* node_depth, uint64_t* anc_mask) {
+static int collapse_tree_call(ctcspec_ctx* ctx, const char* name, bool raw, const int32_t* topk_id, const float* topk_logp,
+                              const int32_t* root_token, int B, int T, int k, int32_t blank_id, int beam,
+                              int max_nodes, int32_t* n_cand, int32_t* cand_tokens, int32_t* cand_len,
+                              float* cand_score, int32_t* cand_leaf, int32_t* n_nodes, int32_t* node_token,
+                              int32_t* node_parent, int32_t* node_depth, uint64_t* anc_mask, int32_t* node_removed) {
   if (!ctx) return CTCSPEC_EINVAL;
   CTCSPEC_REQUIRE(ctx,
                   topk_id && topk_logp && root_token && n_cand && cand_tokens && cand_len && cand_score &&
-                      cand_leaf && n_nodes && node_token && node_parent && node_depth && anc_mask,
-                  CTCSPEC_EINVAL, "ctc_collapse_tree: null pointer");
+                      cand_leaf && n_nodes && node_token && node_parent && node_depth && anc_mask &&
+                      (!raw || node_removed),
+                  CTCSPEC_EINVAL, "%s: null pointer", name);
   CTCSPEC_REQUIRE(ctx, B > 0 && T > 0 && k > 0 && beam > 0 && max_nodes > 0, CTCSPEC_EINVAL,
-                  "ctc_collapse_tree: sizes must be positive");
+                  "%s: sizes must be positive", name);
   CTCSPEC_REQUIRE(ctx, T <= CTCSPEC_MAX_SLOTS && k <= CTCSPEC_MAX_TOPK && beam <= CTCSPEC_MAX_BEAM &&
                            max_nodes <= CTCSPEC_MAX_NODES,
-                  CTCSPEC_EUNSUPPORTED, "ctc_collapse_tree: T<=%d, k<=%d, beam<=%d, max_nodes<=%d required",
+                  CTCSPEC_EUNSUPPORTED, "%s: T<=%d, k<=%d, beam<=%d, max_nodes<=%d required", name,
                   CTCSPEC_MAX_SLOTS, CTCSPEC_MAX_TOPK, CTCSPEC_MAX_BEAM, CTCSPEC_MAX_NODES);
   long long total = 1;
   for (int t = 0; t < T; ++t) total *= k;
   CTCSPEC_REQUIRE(ctx, total <= CTCSPEC_MAX_ALIGNMENTS, CTCSPEC_EUNSUPPORTED,
-                  "ctc_collapse_tree: k^T=%lld exceeds %d", total, CTCSPEC_MAX_ALIGNMENTS);
+                  "%s: k^T=%lld exceeds %d", name, total, CTCSPEC_MAX_ALIGNMENTS);
   CTCSPEC_REQUIRE(ctx, B <= ctx->lim.max_batch, CTCSPEC_EUNSUPPORTED,
-                  "ctc_collapse_tree: B=%d exceeds the context's max_batch=%d", B, ctx->lim.max_batch);
+                  "%s: B=%d exceeds the context's max_batch=%d", name, B, ctx->lim.max_batch);
 
   CollapseParams p;
   p.topk_id = topk_id; p.topk_logp = topk_logp; p.root_token = root_token;
@@ -797,7 +816,7 @@ extern "C" int ctc_collapse_tree(ctcspec_ctx* ctx, const int32_t* topk_id, const
   }
   p.n_cand = n_cand; p.cand_tokens = cand_tokens; p.cand_len = cand_len; p.cand_score = cand_score;
   p.cand_leaf = cand_leaf; p.n_nodes = n_nodes; p.node_token = node_token; p.node_parent = node_parent;
-  p.node_depth = node_depth; p.anc_mask = (unsigned long long*)anc_mask;
+  p.node_depth = node_depth; p.anc_mask = (unsigned long long*)anc_mask; p.node_removed = node_removed;
   p.ws = ctx->collapse_ws;
   static_assert(sizeof(CollapseShared) <= 160 * 1024, "collapse LDS footprint");
   static_assert(kHalfMax <= 2 * kThreads, "two sorted first-half entries per thread");
@@ -806,13 +825,36 @@ extern "C" int ctc_collapse_tree(ctcspec_ctx* ctx, const int32_t* topk_id, const
   static_assert(CTCSPEC_MAX_SLOTS * CTCSPEC_MAX_TOPK <= 64, "token codes fit 6 bits; the top-k lists fit one wavefront");
   static_assert(CTCSPEC_MAX_BEAM <= 128 && CTCSPEC_MAX_SLOTS * CTCSPEC_MAX_TOPK <= 64, "direct-address table of (creator, code) pairs");
   const int lds = (int)sizeof(CollapseShared);
-  static bool lds_allowed = false;
-  if (!lds_allowed) {
-    CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)collapse_tree_kernel,
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    lds_allowed = true;
+  static bool lds_allowed[2] = {false, false};
+  if (!lds_allowed[raw ? 1 : 0]) {
+    const void* fn = raw ? (const void*)collapse_tree_kernel<true> : (const void*)collapse_tree_kernel<false>;
+    CTCSPEC_HIP(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    lds_allowed[raw ? 1 : 0] = true;
   }
-  hipLaunchKernelGGL(collapse_tree_kernel, dim3(B), dim3(kThreads), lds, ctx->stream, p);
+  if (raw)
+    hipLaunchKernelGGL(collapse_tree_kernel<true>, dim3(B), dim3(kThreads), lds, ctx->stream, p);
+  else
+    hipLaunchKernelGGL(collapse_tree_kernel<false>, dim3(B), dim3(kThreads), lds, ctx->stream, p);
   CTCSPEC_HIP(ctx, hipGetLastError());
   return CTCSPEC_OK;
+}
+
+extern "C" int ctc_collapse_tree(ctcspec_ctx* ctx, const int32_t* topk_id, const float* topk_logp,
+                                 const int32_t* root_token, int B, int T, int k, int32_t blank_id, int beam,
+                                 int max_nodes, int32_t* n_cand, int32_t* cand_tokens, int32_t* cand_len,
+                                 float* cand_score, int32_t* cand_leaf, int32_t* n_nodes, int32_t* node_token,
+                                 int32_t* node_parent, int32_t* node_depth, uint64_t* anc_mask) {
+  return collapse_tree_call(ctx, "ctc_collapse_tree", false, topk_id, topk_logp, root_token, B, T, k, blank_id, beam,
+                            max_nodes, n_cand, cand_tokens, cand_len, cand_score, cand_leaf, n_nodes, node_token,
+                            node_parent, node_depth, anc_mask, nullptr);
+}
+
+extern "C" int ctc_raw_tree(ctcspec_ctx* ctx, const int32_t* topk_id, const float* topk_logp,
+                            const int32_t* root_token, int B, int T, int k, int32_t blank_id, int beam, int max_nodes,
+                            int32_t* n_cand, int32_t* cand_tokens, int32_t* cand_len, float* cand_score,
+                            int32_t* cand_leaf, int32_t* n_nodes, int32_t* node_token, int32_t* node_parent,
+                            int32_t* node_depth, uint64_t* anc_mask, int32_t* node_removed) {
+  return collapse_tree_call(ctx, "ctc_raw_tree", true, topk_id, topk_logp, root_token, B, T, k, blank_id, beam,
+                            max_nodes, n_cand, cand_tokens, cand_len, cand_score, cand_leaf, n_nodes, node_token,
+                            node_parent, node_depth, anc_mask, node_removed);
 }

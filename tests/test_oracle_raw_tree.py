@@ -35,7 +35,7 @@ def test_repeat_after_a_blank_is_kept_and_the_root_is_no_slot():
 
 def _case(seed, T, k, vocab):
     rng = np.random.default_rng(seed)
-    ids = np.stack([rng.permutation(vocab)[:k] for _ in range(T)])
+    ids = np.stack([rng.permutation(vocab)[:k] + 1 for _ in range(T)])  # tokens 1..vocab, each once per list
     ids[rng.integers(0, T), rng.integers(0, k)] = BLANK
     logp = -np.sort(rng.exponential(1.0, size=(T, k)).astype(np.float32), axis=-1)
     return ids, logp
@@ -108,3 +108,11 @@ def test_attention_over_the_raw_tree_equals_the_collapsed_tree():
     for i in kept:
         assert np.allclose(out_raw[0, i], out_col[0, stands_for[i]], rtol=1e-12, atol=1e-12)
     assert nr > nc  # the raw layout spends nodes on removed positions
+
+
+def test_a_token_named_twice_in_a_list_gives_one_candidate():
+    ids = np.array([[A, A], [B_, BLANK]])
+    logp = np.array([[-0.1, -0.3], [-0.2, -0.4]], dtype=np.float32)
+    r = oracle.raw_tree(ids, logp, 1, BLANK, 8, 16)
+    assert r["n_cand"] == 2 and [list(t) for t in r["cand_tokens"][:2]] == [[A, B_], [A, BLANK]]
+    assert np.allclose(r["cand_score"][:2], [-0.3, -0.5])  # the better of the two equal sequences
