@@ -66,6 +66,15 @@ namespace ctcspec {
 
 int fail(ctcspec_ctx* ctx, int code, const char* fmt, ...);
 
+// tree_verify_attn with an optional second output form for callers inside the library: when `rows` is given and
+// the launch uses key splits, the merged result is written as rows [B*max_nodes][H*128] of two-bf16 values
+// (planes of rows_plane elements) instead of `out`, and *rows_written is set to 1.
+int tree_verify_attn_rows(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* q, const void* k_cache,
+                          const void* v_cache, const int64_t* kv_off, const int32_t* ctx_len, int kv_cap,
+                          const void* k_tree, const void* v_tree, const int32_t* n_nodes, const uint64_t* anc_mask,
+                          int B, int H, int dh, int max_nodes, float scale, float* out, unsigned short* rows,
+                          long long rows_plane, int* rows_written);
+
 #define CTCSPEC_REQUIRE(ctx, cond, code, ...) \
   do {                                        \
     if (!(cond)) return ::ctcspec::fail((ctx), (code), __VA_ARGS__); \

@@ -535,11 +535,15 @@ extern "C" int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
     hipLaunchKernelGGL(dl_qkv_finish_kernel, dim3(blocks_for((long long)p.cols * 3 * H * (p.dh / 2))), dim3(256), 0, st, p, pl);
   });
   if (rc != CTCSPEC_OK) return rc;
-  rc = tree_verify_attn(ctx, dt, p.q, k_cache, v_cache, kv_off, ctx_len, kv_cap, k_new, v_new, p.n_rows,
-                        (const uint64_t*)p.causal, B, H, p.dh, T, 1.0f / sqrtf((float)p.dh), p.attn);
+  int rows_written = 0;  // with key splits the attention's merge kernel writes the rows itself
+  rc = tree_verify_attn_rows(ctx, dt, p.q, k_cache, v_cache, kv_off, ctx_len, kv_cap, k_new, v_new, p.n_rows,
+                             (const uint64_t*)p.causal, B, H, p.dh, T, 1.0f / sqrtf((float)p.dh), p.attn, p.arows,
+                             (long long)BT * D, &rows_written);
   if (rc != CTCSPEC_OK) return rc;
-  hipLaunchKernelGGL(dl_attn_rows_kernel, dim3(blocks_for((long long)BT * D)), dim3(256), 0, st, p);
-  CTCSPEC_HIP(ctx, hipGetLastError());
+  if (!rows_written) {
+    hipLaunchKernelGGL(dl_attn_rows_kernel, dim3(blocks_for((long long)BT * D)), dim3(256), 0, st, p);
+    CTCSPEC_HIP(ctx, hipGetLastError());
+  }
   rc = gemm_passes(w->wo, D, D, p.arows, [&](const SkinnyPlan& pl) {
     hipLaunchKernelGGL(dl_oproj_finish_kernel, dim3(p.cols * (D / 256)), dim3(256), 0, st, p, pl);
   });

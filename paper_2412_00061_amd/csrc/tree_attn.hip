@@ -27,6 +27,10 @@ struct AttnParams {
   int B, H, dh, max_nodes;
   float scale;
   float* out;
+  // optional second form of the merged output (key splits only): rows [B*max_nodes][H*128], each value as two
+  // bf16 numbers (high part in plane 0, low part in plane 1) - what the draft layer's next matrix product takes
+  unsigned short* rows;
+  long long rows_plane;  // elements per plane
 };
 
 constexpr int kGenericThreads = 256;
@@ -496,7 +500,23 @@ __global__ __launch_bounds__(kMergeThreads) void tree_attn_merge_kernel(AttnPara
     Lt += f * plv[s];
     acc += pov[s] * f;
   }
-  *(f32x4*)(p.out + ((size_t)bh * p.max_nodes + row) * 128 + d4) = acc * (1.0f / Lt);
+  const f32x4 o = acc * (1.0f / Lt);
+  if (p.rows) {
+    const int h = (int)(bh - (long long)b * p.H);
+    const size_t at = ((size_t)b * p.max_nodes + row) * ((size_t)p.H * 128) + (size_t)h * 128 + d4;
+    unsigned short hi[4], lo[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const unsigned int u = __float_as_uint(o[i]);
+      hi[i] = (u & 0x7fffffffu) > 0x7f800000u ? 0x7fc0 : (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+      const unsigned int v = __float_as_uint(o[i] - __uint_as_float((unsigned int)hi[i] << 16));
+      lo[i] = (v & 0x7fffffffu) > 0x7f800000u ? 0x7fc0 : (unsigned short)((v + 0x7fffu + ((v >> 16) & 1u)) >> 16);
+    }
+    *(u32x2*)(p.rows + at) = u32x2{(unsigned)hi[0] | ((unsigned)hi[1] << 16), (unsigned)hi[2] | ((unsigned)hi[3] << 16)};
+    *(u32x2*)(p.rows + p.rows_plane + at) = u32x2{(unsigned)lo[0] | ((unsigned)lo[1] << 16), (unsigned)lo[2] | ((unsigned)lo[3] << 16)};
+  } else {
+    *(f32x4*)(p.out + ((size_t)bh * p.max_nodes + row) * 128 + d4) = o;
+  }
 }
 
 template <int QT, int NW, int CW, int PF>
@@ -517,11 +537,12 @@ static hipError_t launch_attn_bf16(const AttnParams& p, const AttnSplit& sp, hip
 
 using namespace ctcspec;
 
-extern "C" int tree_verify_attn(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* q, const void* k_cache,
-                                const void* v_cache, const int64_t* kv_off, const int32_t* ctx_len, int kv_cap,
-                                const void* k_tree, const void* v_tree, const int32_t* n_nodes,
-                                const uint64_t* anc_mask, int B, int H, int dh, int max_nodes, float scale,
-                                float* out) {
+int ctcspec::tree_verify_attn_rows(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* q, const void* k_cache,
+                                   const void* v_cache, const int64_t* kv_off, const int32_t* ctx_len, int kv_cap,
+                                   const void* k_tree, const void* v_tree, const int32_t* n_nodes,
+                                   const uint64_t* anc_mask, int B, int H, int dh, int max_nodes, float scale,
+                                   float* out, unsigned short* rows, long long rows_plane, int* rows_written) {
+  if (rows_written) *rows_written = 0;
   if (!ctx) return CTCSPEC_EINVAL;
   CTCSPEC_REQUIRE(ctx, q && k_cache && v_cache && kv_off && ctx_len && k_tree && v_tree && n_nodes && anc_mask && out,
                   CTCSPEC_EINVAL, "tree_verify_attn: null pointer");
@@ -543,6 +564,7 @@ extern "C" int tree_verify_attn(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* 
   p.q = q; p.k_cache = k_cache; p.v_cache = v_cache; p.kv_off = kv_off; p.ctx_len = ctx_len; p.kv_cap = kv_cap;
   p.k_tree = k_tree; p.v_tree = v_tree; p.n_nodes = n_nodes; p.anc_mask = (const unsigned long long*)anc_mask;
   p.B = B; p.H = H; p.dh = dh; p.max_nodes = max_nodes; p.scale = scale; p.out = out;
+  p.rows = nullptr; p.rows_plane = 0;
   if (dt == CTCSPEC_BF16 && dh == 128) {
     CTCSPEC_REQUIRE(ctx, scale > 0.f, CTCSPEC_EINVAL, "tree_verify_attn: scale must be positive");
     // Launch shape.  A workgroup has 8 wavefronts that all fetch tiles; 8 or 4 of them own 16 query rows
@@ -568,6 +590,10 @@ extern "C" int tree_verify_attn(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* 
     sp.po = ctx->attn_po; sp.pm = ctx->attn_pm; sp.pl = ctx->attn_pl;
     CTCSPEC_REQUIRE(ctx, bh * sp.QB * sp.S <= 0x7fffffffLL && bh * max_nodes <= 0x7fffffffLL, CTCSPEC_EUNSUPPORTED,
                     "tree_verify_attn: grid too large");
+    if (rows && sp.S > 1) {  // the merge kernel writes the rows instead of `out`
+      p.rows = rows; p.rows_plane = rows_plane;
+      if (rows_written) *rows_written = 1;
+    }
     const hipError_t e = rows64 ? launch_attn_bf16<1, 8, 4, 2>(p, sp, ctx->stream)
                                 : launch_attn_bf16<1, 8, 8, 2>(p, sp, ctx->stream);
     CTCSPEC_HIP(ctx, e);
@@ -580,4 +606,13 @@ extern "C" int tree_verify_attn(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* 
     hipLaunchKernelGGL(tree_attn_generic_kernel<float>, grid, dim3(kGenericThreads), 0, ctx->stream, p);
   CTCSPEC_HIP(ctx, hipGetLastError());
   return CTCSPEC_OK;
+}
+
+extern "C" int tree_verify_attn(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* q, const void* k_cache,
+                                const void* v_cache, const int64_t* kv_off, const int32_t* ctx_len, int kv_cap,
+                                const void* k_tree, const void* v_tree, const int32_t* n_nodes,
+                                const uint64_t* anc_mask, int B, int H, int dh, int max_nodes, float scale,
+                                float* out) {
+  return ctcspec::tree_verify_attn_rows(ctx, dt, q, k_cache, v_cache, kv_off, ctx_len, kv_cap, k_tree, v_tree, n_nodes,
+                                        anc_mask, B, H, dh, max_nodes, scale, out, nullptr, 0, nullptr);
 }
