@@ -7,14 +7,18 @@
 // device-scope release fence in every workgroup; on this GPU that is an L2 write-back per workgroup
 // and costs far more than the launch of a second kernel.)
 //
-// Two producers of the 128 x columns logit block exist:
-//   * lmhead_bf16_mfma_kernel  - bf16 operands, v_mfma_f32_16x16x32_bf16, HBM-streaming design
+// Three producers of the 128 x columns logit block exist:
+//   * lmhead_bf16_mfma_kernel  - bf16 operands, v_mfma_f32_16x16x32_bf16, HBM-streaming design: a wavefront
+//                                streams 16 rows, the hidden states of all columns sit in LDS (up to 11
+//                                columns at D = 4096)
+//   * lmhead_bf16_tile_kernel  - bf16, more columns than that: the 128 x 64 tile loop of gemm_tile.h, both
+//                                operands stepping through LDS
 //   * lmhead_generic_kernel    - any dtype/shape within the limits, plain fp32 FMA
-// Both hand the block over in LDS to the same epilogue.
+// All hand the block over in LDS to the same epilogue.
 #include <type_traits>
 #include <utility>
 
-#include "common.h"
+#include "gemm_tile.h"
 
 namespace ctcspec {
 
@@ -28,10 +32,11 @@ struct LmHeadParams {
   const void* w;
   const float* bias;
   int BT, D, Vp1, k;
-  int KC;        // mfma kernel: hidden-state chunk held in LDS (elements)
+  int KC;        // mfma kernel: hidden elements per column held in LDS (= D)
   int hs_bytes;  // mfma kernel: bytes of the LDS hidden-state region
   unsigned int hs_magic;  // mfma kernel: ceil(2^32 / (KC / 8)), for index / (KC / 8) by multiplication
   int n_blocks;
+  const void* zeros;  // tile kernel: 256 bytes of zeros
   float* pmax;
   float* psum;
   unsigned long long* pkey;
@@ -187,7 +192,7 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(LmHeadParams p) {
 // (rows past the vocabulary re-read its last row, the tail of the k loop is peeled instead of
 // guarded): the waits can then name the exact number of younger loads that may stay in flight, and
 // the prefetch pipeline never drains.  A load under a condition makes every later wait a full drain.
-template <int NT, int STAGES, bool CHUNKED>
+template <int NT, int STAGES>
 __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHeadParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -217,14 +222,10 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHea
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const int SPC = p.KC / 256;
-  const int nchunks = CHUNKED ? p.D / p.KC : 1;  // !CHUNKED: the host guarantees KC == D
-  const int total_steps = p.D / 256;
+  const int total_steps = p.D / 256;  // the host guarantees KC == D: the hidden states of all columns are in LDS
 
-  // Hidden-state chunk staging: every thread carries kHsPieces 16-byte pieces of the chunk through
-  // registers (pieces past the end of the chunk repeat its last piece and are not written to LDS).
-  // The loads of chunk ch+1 are issued before chunk ch is consumed, so only the very first chunk
-  // exposes its latency - and that one is requested before the first W loads.
+  // Hidden-state staging: every thread carries kHsPieces 16-byte pieces through registers (pieces past the
+  // end repeat the last piece and are not written to LDS); they are requested before the first W loads.
   constexpr int kHsPieces = 12;
   const int per_row = p.KC / 8;  // 16-byte pieces per column
   const int hs_total = p.BT * per_row;
@@ -240,10 +241,9 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHea
     hs_dst[u] = idx < hs_total ? m * HSS + q * 16 : -1;
     hs_src[u] = (size_t)m * p.D * 2 + q * 16;
   }
-  auto hs_request = [&](int ch) __attribute__((always_inline)) {
-    const unsigned char* src = (const unsigned char*)p.hidden + (size_t)ch * p.KC * 2;
+  auto hs_request = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int u = 0; u < kHsPieces; ++u) hreg[u] = *(const u32x4*)(src + hs_src[u]);
+    for (int u = 0; u < kHsPieces; ++u) hreg[u] = *(const u32x4*)((const unsigned char*)p.hidden + hs_src[u]);
   };
   auto hs_commit = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -260,7 +260,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHea
     // issue order, and a stage whose loads are spread among younger ones can only be waited for late
     __builtin_amdgcn_sched_barrier(0);
   };
-  // one step: W registers of stage ST -> LDS strip -> A fragments; i = step inside the hidden chunk
+  // one step: W registers of stage ST -> LDS strip -> A fragments; i = step
   auto consume = [&](int i, auto stage_tag) __attribute__((always_inline)) {
     constexpr int ST = decltype(stage_tag)::value;
 #pragma unroll
@@ -281,12 +281,12 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHea
     (std::make_integer_sequence<int, STAGES>{});
   };
 
-  hs_request(0);
+  hs_request();
   for_each_stage([&](auto st) __attribute__((always_inline)) {
     if constexpr (decltype(st)::value < STAGES - 1) w_request(decltype(st)::value, st);
   });
 
-  if constexpr (!CHUNKED) {
+  {
     hs_commit();
     __syncthreads();
     // blocks of STAGES steps; step i refills, with step i + STAGES - 1, the stage that step i - 1 freed
@@ -306,22 +306,6 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHea
       if constexpr (SS == 0) w_request(i + STAGES - 1, std::integral_constant<int, STAGES - 1>{});
       consume(i, st);
     });
-  } else {
-    for (int ch = 0; ch < nchunks; ++ch) {
-      if (ch > 0) __syncthreads();  // every wave is done reading the previous chunk
-      hs_commit();
-      __syncthreads();
-      if (ch + 1 < nchunks) hs_request(ch + 1);
-      for (int i0 = 0; i0 < SPC; i0 += STAGES) {
-        for_each_stage([&](auto st) __attribute__((always_inline)) {
-          constexpr int SS = decltype(st)::value;
-          const int i = i0 + SS;
-          const int pf = ch * SPC + i + STAGES - 1;
-          if (pf < total_steps) w_request(pf, std::integral_constant<int, (SS + STAGES - 1) % STAGES>{});
-          consume(i, st);
-        });
-      }
-    }
   }
 
   // hand the 128 x BT logit block to the epilogue (the W strips are no longer needed)
@@ -344,6 +328,44 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHea
   lmhead_block_epilogue(p, zbuf);
 }
 
+// ---- bf16 MFMA producer for many columns (more than fit in LDS over the whole hidden dimension) -----------------
+// The 128 x 64 tile loop shared with the base-model head: both operands staged through LDS step by step, the
+// weights still read exactly once.  Then the same block epilogue as the other producers.
+constexpr int kLmTileDist = 4;
+template <int CT>
+__global__ __launch_bounds__(64 * kTileWaves) void lmhead_bf16_tile_kernel(LmHeadParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wr = wave >> 2, wc = wave & 3;
+  const int c = lane & 15, g = lane >> 4;
+  const int row_base = blockIdx.x * kRowsPerBlock;
+  GemmTileArgs t;
+  t.w = p.w; t.hidden = p.hidden; t.zeros = p.zeros; t.D = p.D; t.V = p.Vp1; t.cols = p.BT; t.row_base = row_base;
+  f32x4 acc[4][CT];
+  gemm_tile_128<kLmTileDist, CT>(t, smem, acc);
+  // (the loop's last barrier has every wavefront done with the LDS tiles)
+  float* zbuf = (float*)smem;
+#pragma unroll
+  for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+      const int col = wc * 16 * CT + ct * 16 + c;
+      if (col < p.BT) {
+        f32x4 z;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = row_base + wr * 64 + rt * 16 + g * 4 + i;
+          z[i] = row < p.Vp1 ? acc[rt][ct][i] + (p.bias ? p.bias[row] : 0.f) : -INFINITY;
+        }
+        *(f32x4*)(zbuf + col * kZStride + wr * 64 + rt * 16 + g * 4) = z;
+      }
+    }
+  __syncthreads();
+  lmhead_block_epilogue(p, zbuf);
+}
+static_assert(kMaxCols <= 64 && kMaxCols * kZStride * 4 <= tile_lds_bytes<1>(), "one 64-column tile holds every column");
+
 static void launch_merge(const LmHeadParams& p, hipStream_t stream) {
   if (p.k <= 1) hipLaunchKernelGGL(lmhead_merge_kernel<1>, dim3(p.BT), dim3(64), 0, stream, p);
   else if (p.k <= 2) hipLaunchKernelGGL(lmhead_merge_kernel<2>, dim3(p.BT), dim3(64), 0, stream, p);
@@ -361,9 +383,9 @@ static int pick_kc(int BT, int D, int stages, int budget) {
   return 0;
 }
 
-template <int NT, int STAGES, bool CHUNKED>
+template <int NT, int STAGES>
 static hipError_t launch_mfma(const LmHeadParams& p, int lds_bytes, hipStream_t stream) {
-  auto kern = lmhead_bf16_mfma_kernel<NT, STAGES, CHUNKED>;
+  auto kern = lmhead_bf16_mfma_kernel<NT, STAGES>;
   static int lds_allowed = 0;  // per instantiation; raising the limit is needed once per process
   if (lds_bytes > lds_allowed) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
@@ -398,22 +420,22 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
   LmHeadParams p;
   p.hidden = hidden; p.w = w; p.bias = bias;
   p.BT = B * T; p.D = D; p.Vp1 = Vp1; p.k = k;
-  p.KC = 0; p.hs_bytes = 0; p.hs_magic = 0;
+  p.KC = 0; p.hs_bytes = 0; p.hs_magic = 0; p.zeros = ctx->zeros;
   p.n_blocks = (Vp1 + kRowsPerBlock - 1) / kRowsPerBlock;
   p.pmax = ctx->lm_pmax; p.psum = ctx->lm_psum; p.pkey = ctx->lm_pkey;
   p.topk_id = topk_id; p.topk_logp = topk_logp; p.lse = lse; p.logits_out = logits_out;
 
   if (dt == CTCSPEC_BF16) {
     const int budget = 160 * 1024 - kMfmaWaves * kWStageBytes - 64;
-    // deep prefetch (4 stages) when the whole hidden dimension fits in LDS at once; otherwise the
-    // hidden states are chunked through LDS and the prefetch is 2 stages deep (register budget)
+    // the streaming kernel needs the hidden states of all columns in LDS over the whole hidden dimension
+    // (4 register stages of prefetch; 2 when D is a multiple of 512 but not of 1024)
     int stages = 4;
     int kc = pick_kc(p.BT, D, stages, budget);
     if (kc != D) {
       stages = 2;
       kc = pick_kc(p.BT, D, stages, budget);
     }
-    if (kc > 0) {
+    if (kc == D) {
       p.KC = kc;
       p.hs_bytes = p.BT * (2 * kc + 16);
       p.hs_magic = (unsigned int)((0x100000000ull + (unsigned)(kc / 8) - 1) / (unsigned)(kc / 8));
@@ -423,27 +445,40 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
       if (ctx->lm_profile) CTCSPEC_HIP(ctx, hipEventRecord(ctx->lm_ev0, ctx->stream));
       if (stages == 4) {
         switch (nt) {
-          case 1: e = launch_mfma<1, 4, false>(p, lds, ctx->stream); break;
-          case 2: e = launch_mfma<2, 4, false>(p, lds, ctx->stream); break;
-          case 3: e = launch_mfma<3, 4, false>(p, lds, ctx->stream); break;
-          default: e = launch_mfma<4, 4, false>(p, lds, ctx->stream); break;
-        }
-      } else if (kc == D) {
-        switch (nt) {
-          case 1: e = launch_mfma<1, 2, false>(p, lds, ctx->stream); break;
-          case 2: e = launch_mfma<2, 2, false>(p, lds, ctx->stream); break;
-          case 3: e = launch_mfma<3, 2, false>(p, lds, ctx->stream); break;
-          default: e = launch_mfma<4, 2, false>(p, lds, ctx->stream); break;
+          case 1: e = launch_mfma<1, 4>(p, lds, ctx->stream); break;
+          case 2: e = launch_mfma<2, 4>(p, lds, ctx->stream); break;
+          case 3: e = launch_mfma<3, 4>(p, lds, ctx->stream); break;
+          default: e = launch_mfma<4, 4>(p, lds, ctx->stream); break;
         }
       } else {
         switch (nt) {
-          case 1: e = launch_mfma<1, 2, true>(p, lds, ctx->stream); break;
-          case 2: e = launch_mfma<2, 2, true>(p, lds, ctx->stream); break;
-          case 3: e = launch_mfma<3, 2, true>(p, lds, ctx->stream); break;
-          default: e = launch_mfma<4, 2, true>(p, lds, ctx->stream); break;
+          case 1: e = launch_mfma<1, 2>(p, lds, ctx->stream); break;
+          case 2: e = launch_mfma<2, 2>(p, lds, ctx->stream); break;
+          case 3: e = launch_mfma<3, 2>(p, lds, ctx->stream); break;
+          default: e = launch_mfma<4, 2>(p, lds, ctx->stream); break;
         }
       }
       CTCSPEC_HIP(ctx, e);
+      if (ctx->lm_profile) {
+        CTCSPEC_HIP(ctx, hipEventRecord(ctx->lm_ev1, ctx->stream));
+        ctx->lm_profile_valid = 1;
+      }
+      launch_merge(p, ctx->stream);
+      CTCSPEC_HIP(ctx, hipGetLastError());
+      return CTCSPEC_OK;
+    }
+    if (D % kTileStepK == 0 && p.BT <= 64 && (long long)Vp1 * D * 2 < (1LL << 32)) {
+      // more columns than that: both operands step through LDS
+      static bool lds_allowed = false;  // raising the limit is needed once per process
+      if (!lds_allowed) {
+        CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)lmhead_bf16_tile_kernel<1>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds_bytes<1>()));
+        lds_allowed = true;
+      }
+      if (ctx->lm_profile) CTCSPEC_HIP(ctx, hipEventRecord(ctx->lm_ev0, ctx->stream));
+      hipLaunchKernelGGL(lmhead_bf16_tile_kernel<1>, dim3(p.n_blocks), dim3(64 * kTileWaves), tile_lds_bytes<1>(),
+                         ctx->stream, p);
+      CTCSPEC_HIP(ctx, hipGetLastError());
       if (ctx->lm_profile) {
         CTCSPEC_HIP(ctx, hipEventRecord(ctx->lm_ev1, ctx->stream));
         ctx->lm_profile_valid = 1;

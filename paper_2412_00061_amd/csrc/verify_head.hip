@@ -7,21 +7,15 @@
 //                                  per workgroup, weights read once per block of 128 columns
 //   * verify_head_generic_kernel - any dtype/shape: plain fp32 FMA, one atomic max per (row block, column)
 //   * verify_head_merge_kernel   - best key over the row blocks -> token id, -1 for rows without a node
-#include <type_traits>
-#include <utility>
-
-#include "common.h"
+#include "gemm_tile.h"
 
 namespace ctcspec {
 
 constexpr int kVhCols = kVerifyCols;            // columns (tree nodes) per pass over the weights
-constexpr int kVhWaves = 8;
+constexpr int kVhWaves = kTileWaves;
 constexpr int kVhDist = 4;                      // prefetch distance in steps = register stages per operand
-constexpr int kVhStepK = 128;                   // hidden elements per step
-constexpr int kVhRowPitch = 2 * kVhStepK + 32;  // bytes per staged row: 128 bf16 + pad; fragment reads (16 rows x 4
-                                                // chunks per instruction) measure conflict-free at this pitch
-constexpr int kVhTileBytes = 128 * kVhRowPitch; // one operand of one step: 128 rows (or columns) x 128 k
-constexpr int kVhLdsBytes = 4 * kVhTileBytes;   // W and hidden-state tile, double-buffered
+constexpr int kVhStepK = kTileStepK;
+constexpr int kVhLdsBytes = tile_lds_bytes<2>();
 constexpr int kVhZStride = kRowsPerBlock + 4;   // floats per column of the logit block
 static_assert(kVhCols == 128 && kRowsPerBlock == 128, "tile shape");
 static_assert(kVhCols * kVhZStride * 4 <= kVhLdsBytes, "logit block fits the staging area");
@@ -40,155 +34,21 @@ struct VerifyHeadParams {
   int32_t* target;      // [cols_total]
 };
 
-// ---- bf16 MFMA kernel -----------------------------------------------------------------------------------
-// 128 vocabulary rows x 128 columns per workgroup, 8 wavefronts in a 2 x 4 grid: wavefront (wr, wc) owns
-// rows [64 wr, +64) x columns [32 wc, +32) - 4 x 2 MFMA tiles.  Per step of 128 hidden elements both
-// operands go through LDS: the W tile (128 rows x 256 B, nontemporal, the A operand) and the hidden states
-// of the step (128 columns x 256 B, the B operand) are fetched by all threads together with coalesced
-// 16-byte loads, DIST steps ahead, into rotating register stages, and written to one of two LDS buffers
-// while the other one is computed from: one barrier per step.  A wavefront reads 4 A and 2 B fragments per
-// 32 k for 8 MFMAs; the fragments of the next 32 k are read, and the tiles of the next step are written,
-// between the MFMAs of the current 32 k (the instruction order is pinned with scheduling groups).
-// What bounds it (measured, one CU): b128 fragment reads at 128 B per clock, b128 writes at 79 B per clock -
-// per step 192 KB read + 64 KB written = 2300 clocks against 1024 clocks of MFMA and 1.35 us (3200 clocks)
-// for the 32 KB of W at the HBM rate, so the LDS work fits under the stream only if nothing serialises.
-// All loads are unconditional and counted (indices clamped), so the waits name the loads that stay in flight.
-typedef __attribute__((address_space(1))) u32x4 GlobalU32x4;  // a pointer made from an integer is generic otherwise
+// ---- bf16 MFMA kernel: the shared 128 x 128 tile loop, then the best (logit, id) key per column -----------------
 template <int DIST>
 __global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyHeadParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int NTHREADS = 64 * kVhWaves;
-  constexpr int PIECES = 128 * (2 * kVhStepK / 16) / NTHREADS;  // 16-byte pieces per thread and tile: 4
-  constexpr int ROWS_PER_PIECE = NTHREADS / 16;                 // 32
-  constexpr int KK = kVhStepK / 32;                             // MFMA k-blocks per step
-  constexpr int TRIP = DIST % 2 == 0 ? DIST : 2 * DIST;         // steps per loop trip: stage and buffer static
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wr = wave >> 2, wc = wave & 3;
   const int c = lane & 15, g = lane >> 4;
   const int row_base = blockIdx.x * kRowsPerBlock;
-  const int total_steps = p.D / kVhStepK;
-  // LDS: buffer b holds the hidden-state tile at 2 b and the W tile at 2 b + 1 (in tiles)
-
-  // piece u of a thread: tile row (tid >> 4) + 32 u, 16-byte chunk tid & 15; byte offsets in 32 bits (the host
-  // checks that the matrices are smaller than 4 GB)
-  const unsigned int lane_off = (tid & 15) * 16;
-  const uintptr_t w_addr = (uintptr_t)p.w, h_addr = (uintptr_t)p.hidden + (size_t)p.col0 * p.D * 2;
-  const uintptr_t z_addr = (uintptr_t)p.zeros;
-  unsigned int woff[PIECES], hoff[PIECES];
-  const int dst0 = (tid >> 4) * kVhRowPitch + (tid & 15) * 16;
-#pragma unroll
-  for (int u = 0; u < PIECES; ++u) {
-    const int r = (tid >> 4) + ROWS_PER_PIECE * u;
-    int row = row_base + r;
-    row = row < p.V ? row : p.V - 1;            // the ragged last block re-reads the last row
-    const int col = r < p.cols ? r : p.cols - 1;  // columns past the end repeat the last one (never read back)
-    woff[u] = (unsigned int)row * (unsigned int)(p.D * 2);
-    hoff[u] = (unsigned int)col * (unsigned int)(p.D * 2);
-  }
-  // A request past the last step still issues its loads, so that every wait counts the same loads: it reads
-  // a 256-byte block of zeros (in L2, no HBM traffic) and nothing computes from the result.
-  u32x4 wreg[DIST][PIECES], hreg[DIST][PIECES];
-  auto request = [&](int step, auto stage) __attribute__((always_inline)) {
-    constexpr int S = decltype(stage)::value;
-    // address arithmetic in integers: a select between pointers would become a branch around each load
-    const bool valid = step < total_steps;
-    const unsigned int mask = valid ? ~0u : 0u;
-    const unsigned int st = ((unsigned int)step * (unsigned int)(2 * kVhStepK)) & mask;
-    const uintptr_t hb = (valid ? h_addr : z_addr) + st, wb = (valid ? w_addr : z_addr) + st;
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int u = 0; u < PIECES; ++u) hreg[S][u] = *(const GlobalU32x4*)(hb + ((hoff[u] & mask) + lane_off));
-#pragma unroll
-    for (int u = 0; u < PIECES; ++u)
-      wreg[S][u] = __builtin_nontemporal_load((const GlobalU32x4*)(wb + ((woff[u] & mask) + lane_off)));
-    __builtin_amdgcn_sched_barrier(0);
-  };
-  auto commit = [&](auto stage, auto buffer) __attribute__((always_inline)) {
-    constexpr int S = decltype(stage)::value, BUF = decltype(buffer)::value;
-    unsigned char* hs = smem + (2 * BUF) * kVhTileBytes;
-    unsigned char* ws = smem + (2 * BUF + 1) * kVhTileBytes;
-#pragma unroll
-    for (int u = 0; u < PIECES; ++u) *(u32x4*)(hs + (dst0 + u * ROWS_PER_PIECE * kVhRowPitch)) = hreg[S][u];
-#pragma unroll
-    for (int u = 0; u < PIECES; ++u) *(u32x4*)(ws + (dst0 + u * ROWS_PER_PIECE * kVhRowPitch)) = wreg[S][u];
-  };
+  GemmTileArgs t;
+  t.w = p.w; t.hidden = (const unsigned char*)p.hidden + (size_t)p.col0 * p.D * 2; t.zeros = p.zeros;
+  t.D = p.D; t.V = p.V; t.cols = p.cols; t.row_base = row_base;
   f32x4 acc[4][2];
-#pragma unroll
-  for (int rt = 0; rt < 4; ++rt)
-#pragma unroll
-    for (int ct = 0; ct < 2; ++ct) acc[rt][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const int aoff = (wr * 64 + c) * kVhRowPitch + g * 16, boff = (wc * 32 + c) * kVhRowPitch + g * 16;
-  // compute one step from LDS buffer BUF; with COMMIT, also write stage S of the registers to the other buffer.
-  // Per 32 k: the next fragments' reads and two of the tile writes are issued, then the eight MFMAs of the
-  // current fragments, under which those LDS operations run.
-  auto compute = [&](auto buffer, auto with_commit, auto stage) __attribute__((always_inline)) {
-    constexpr int BUF = decltype(buffer)::value, S = decltype(stage)::value;
-    constexpr bool COMMIT = decltype(with_commit)::value;
-    const unsigned char* hs = smem + (2 * BUF) * kVhTileBytes;
-    const unsigned char* ws = smem + (2 * BUF + 1) * kVhTileBytes;
-    unsigned char* hs_next = smem + (2 * (1 - BUF)) * kVhTileBytes;
-    unsigned char* ws_next = smem + (2 * (1 - BUF) + 1) * kVhTileBytes;
-    bf16x8 a[2][4], b[2][2];
-    auto read_fragments = [&](int kk, int slot) __attribute__((always_inline)) {
-#pragma unroll
-      for (int rt = 0; rt < 4; ++rt)
-        a[slot][rt] = __builtin_bit_cast(bf16x8, *(const u32x4*)(ws + (aoff + rt * 16 * kVhRowPitch + kk * 64)));
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct)
-        b[slot][ct] = __builtin_bit_cast(bf16x8, *(const u32x4*)(hs + (boff + ct * 16 * kVhRowPitch + kk * 64)));
-    };
-    static_assert(PIECES == KK, "one hidden-state and one W piece are written per 32 k");
-    __builtin_amdgcn_sched_barrier(0);
-    read_fragments(0, 0);
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      __builtin_amdgcn_sched_barrier(0);
-      if (kk + 1 < KK) read_fragments(kk + 1, (kk + 1) & 1);
-      if constexpr (COMMIT) {
-        *(u32x4*)(hs_next + (dst0 + kk * ROWS_PER_PIECE * kVhRowPitch)) = hreg[S][kk];
-        *(u32x4*)(ws_next + (dst0 + kk * ROWS_PER_PIECE * kVhRowPitch)) = wreg[S][kk];
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int rt = 0; rt < 4; ++rt)
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-          acc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kk & 1][rt], b[kk & 1][ct], acc[rt][ct], 0, 0, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  };
-  using I0 = std::integral_constant<int, 0>;
-
-  // The pipelined loop takes TRIP steps per trip with no exit in between (an exit inside the trip gives the
-  // loop head a second, differently ordered set of loads in flight and the waits there fall back to draining
-  // everything), so the total_steps % TRIP steps that do not fill a trip run first, unpipelined.
-  const int lead = total_steps % TRIP;
-  for (int i = 0; i < lead; ++i) {
-    request(i, I0{});
-    if (i > 0) lds_barrier();
-    commit(I0{}, I0{});
-    lds_barrier();
-    compute(I0{}, std::false_type{}, I0{});
-  }
-  if (lead < total_steps) {
-    // local step t = step - lead uses register stage t % DIST and LDS buffer t & 1
-    [&]<int... U>(std::integer_sequence<int, U...>) __attribute__((always_inline)) {
-      (request(lead + U, std::integral_constant<int, U>{}), ...);
-    }(std::make_integer_sequence<int, DIST>{});
-    if (lead > 0) lds_barrier();
-    commit(I0{}, I0{});
-    request(lead + DIST, I0{});
-    lds_barrier();
-    for (int t = lead; t < total_steps; t += TRIP) {
-      [&]<int... U>(std::integer_sequence<int, U...>) __attribute__((always_inline)) {
-        // step t + U: write step t + U + 1 (after the last step: zeros into the idle buffer), refill its stage
-        ((compute(std::integral_constant<int, U & 1>{}, std::true_type{}, std::integral_constant<int, (U + 1) % DIST>{}),
-          request(t + U + 1 + DIST, std::integral_constant<int, (U + 1) % DIST>{}), lds_barrier()),
-         ...);
-      }(std::make_integer_sequence<int, TRIP>{});
-    }
-  }
+  gemm_tile_128<DIST, 2>(t, smem, acc);
 
   // ---- best (logit, id) key per column ---------------------------------------------------------------------
   // (the loop's last barrier has every wavefront done with the LDS tiles)
