@@ -83,6 +83,18 @@ def read_traffic_summary():
     return None
 
 
+def read_kernel_trace_us():
+    """Average duration of the draft-head kernel in the committed rocprofv3 kernel trace (us), or None."""
+    path = os.path.join(ROOT, "profiles", "step_7b_ctx2048_kernel_trace.txt")
+    try:
+        for line in open(path):
+            if line.startswith("lmhead_bf16_mfma_kernel"):
+                return float(line.split()[2])
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
+
+
 def cpu_baseline(cfg, x, n_steps):
     """Time the float64 oracle, as it stands, on this host for n_steps whole steps of the same workload."""
     import oracle
@@ -519,6 +531,9 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": read_traffic_summary(), "algorithmic_bytes_per_launch": head_b,
                      "launch_us": head_us, "launch_us_median": float(np.median(head_kernel_us)),
+                     # the same kernel in the committed rocprofv3 trace (7B shape): begin-to-end by the profiler's
+                     # clock, without the dispatch time that an event pair around one launch also spans
+                     "kernel_trace_avg_us": read_kernel_trace_us() if cfg.name == "7b_ctx2048" else None,
                      "call_us_incl_merge_kernel": float(call_us[0])},
     }
     if args.calibrate_copy:
