@@ -85,3 +85,23 @@ def test_sum_score_hand_case_and_edges(pkg):
     assert np.all(np.isneginf(got[len(drafts):]))
     assert np.array_equal(res["cand_rank_sum"].cpu().numpy()[0], oracle.ranks_desc(got, len(drafts)))
     ctx.close()
+
+
+def test_sum_score_and_raw_tree_reject_bad_arguments(pkg):
+    ctx = pkg.Context(max_batch=1, max_slots=8, max_topk=8, max_vocab_rows=8, max_nodes=8, max_heads=1, max_head_dim=8)
+    logits, lse = dev_f32(np.zeros((1, 3, 4), dtype=np.float32)), dev_f32(np.zeros((1, 3), dtype=np.float32))
+    toks, lens = dev_i32(np.zeros((1, 4, 3), dtype=np.int32)), dev_i32(np.zeros((1, 4), dtype=np.int32))
+    n = dev_i32(np.array([1], dtype=np.int32))
+    with pytest.raises(pkg.CtcspecError, match="blank_id"):
+        pkg.ctc_sum_score(ctx, logits, lse, toks, lens, n, 4)
+    two = dev_f32(np.zeros((2, 3, 4), dtype=np.float32))
+    with pytest.raises(pkg.CtcspecError, match="limits"):
+        pkg.ctc_sum_score(ctx, two, dev_f32(np.zeros((2, 3), dtype=np.float32)), dev_i32(np.zeros((2, 4, 3), dtype=np.int32)),
+                          dev_i32(np.zeros((2, 4), dtype=np.int32)), dev_i32(np.array([1, 1], dtype=np.int32)), 3)
+    ids = dev_i32(np.zeros((1, 8, 8), dtype=np.int32))
+    with pytest.raises(pkg.CtcspecError, match="exceeds"):  # 8^8 raw candidates
+        pkg.ctc_raw_tree(ctx, ids, dev_f32(np.zeros((1, 8, 8), dtype=np.float32)), n, 0, 4, 8)
+    with pytest.raises(pkg.CtcspecError, match="max_nodes"):
+        pkg.ctc_raw_tree(ctx, dev_i32(np.zeros((1, 2, 2), dtype=np.int32)), dev_f32(np.zeros((1, 2, 2), dtype=np.float32)),
+                         n, 0, 4, 500)
+    ctx.close()
