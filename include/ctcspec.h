@@ -337,6 +337,29 @@ int ctc_raw_tree(ctcspec_ctx* ctx, const int32_t* topk_id, const float* topk_log
                  int32_t* cand_len, float* cand_score, int32_t* cand_leaf, int32_t* n_nodes, int32_t* node_token,
                  int32_t* node_parent, int32_t* node_depth, uint64_t* anc_mask, int32_t* node_removed);
 
+/*
+ * ctc_loss - the training objective of Sec. 3.2: for every sequence b the loss -log P(Y_b | X_b), P by Eq. 5 with
+ * Eq. 6 (the sum, over all frame-level sequences that the collapse rule turns into the label, of the product of
+ * the per-frame softmax probabilities), and optionally its gradient with respect to the logits - computed with
+ * the forward-backward recursions of the CTC paper the section cites.  The softmax over the V+1 entries of a frame
+ * is part of the differentiated function.
+ *
+ * logits     [B,T,Vp1] float device in: the draft module's outputs for T frames per sequence
+ * labels     [B,Lmax] int32 device in: label tokens (no blanks), padded; label_len [B] int32 device in
+ * frame_len  [B] int32 device in: frames of sequence b that count (<= T)
+ * workspace  device scratch of at least ctc_loss_workspace_bytes(B, T, Lmax) bytes, owned by the caller, contents
+ *            undefined afterwards; calls that share it must not overlap
+ * loss       [B] float device out; +inf when the label cannot be reached in frame_len frames
+ * grad       [B,T,Vp1] float device out or NULL: d loss[b] / d logits[b,t,v]; zero for frames past frame_len and
+ *            for sequences whose loss is +inf
+ * Limits: Lmax <= 2047, Vp1 * 4 bytes <= 150 KB, B <= 65535.  The same bits on every run.
+ */
+size_t ctc_loss_workspace_bytes(int B, int T, int Lmax);
+
+int ctc_loss(ctcspec_ctx* ctx, const float* logits, const int32_t* labels, const int32_t* label_len,
+             const int32_t* frame_len, int B, int T, int Vp1, int Lmax, int32_t blank_id, void* workspace,
+             size_t workspace_bytes, float* loss, float* grad);
+
 #ifdef __cplusplus
 }
 #endif

@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     accept_longest,
     ctc_collapse_tree,
     ctc_draft_topk,
+    ctc_loss,
+    ctc_loss_workspace_bytes,
     ctc_raw_tree,
     ctc_sum_score,
     draft_layer_forward,

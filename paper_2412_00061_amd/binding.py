@@ -16,7 +16,7 @@ EXPORTS = (
     "ctcspec_create", "ctcspec_destroy", "ctcspec_set_stream", "ctcspec_last_error",
     "ctcspec_workspace_bytes", "ctcspec_profile_draft_head", "ctcspec_draft_head_kernel_ms", "ctc_draft_topk", "ctc_collapse_tree", "tree_verify_attn",
     "accept_longest", "verify_head_argmax", "kv_commit", "draft_layer_workspace_bytes", "draft_layer_forward",
-    "ctc_sum_score", "ctc_raw_tree",
+    "ctc_sum_score", "ctc_raw_tree", "ctc_loss_workspace_bytes", "ctc_loss",
 )
 
 CTCSPEC_F32, CTCSPEC_BF16 = 0, 1
@@ -87,6 +87,10 @@ def load_library():
     lib.draft_layer_forward.restype = c_int
     lib.draft_layer_forward.argtypes = ([c_void_p, c_int, c_void_p, POINTER(_LayerWeights)] + [c_void_p] * 5 +
                                         [c_int] * 6 + [c_float, c_float, c_void_p, c_size_t] + [c_void_p] * 5)
+    lib.ctc_loss_workspace_bytes.restype = c_size_t
+    lib.ctc_loss_workspace_bytes.argtypes = [c_int] * 3
+    lib.ctc_loss.restype = c_int
+    lib.ctc_loss.argtypes = [c_void_p] * 5 + [c_int] * 4 + [c_int32, c_void_p, c_size_t, c_void_p, c_void_p]
     lib.ctc_raw_tree.restype = c_int
     lib.ctc_raw_tree.argtypes = lib.ctc_collapse_tree.argtypes + [c_void_p]
     lib.ctc_sum_score.restype = c_int
@@ -389,4 +393,26 @@ def ctc_sum_score(ctx, logits, lse, cand_tokens, cand_len, n_cand, blank_id, *, 
                                _ptr(cand_tokens, torch.int32), _ptr(cand_len, torch.int32), _ptr(n_cand, torch.int32),
                                B, T, Vp1, blank_id, beam, _ptr(res["cand_logp_sum"]), _ptr(res["cand_rank_sum"]))
     ctx._check(rc, "ctc_sum_score")
+    return res
+
+
+def ctc_loss_workspace_bytes(B, T, Lmax) -> int:
+    return int(load_library().ctc_loss_workspace_bytes(B, T, Lmax))
+
+
+def ctc_loss(ctx, logits, labels, label_len, frame_len, blank_id, *, want_grad=True, workspace=None, out=None):
+    """logits [B,T,V+1] f32, labels [B,Lmax] i32 -> dict(loss [B][, grad [B,T,V+1]])."""
+    B, T, Vp1 = logits.shape
+    Lmax = labels.shape[1]
+    dev = logits.device
+    need = ctc_loss_workspace_bytes(B, T, Lmax)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    res = {"loss": _out(out, "loss", (B,), torch.float32, dev)}
+    if want_grad:
+        res["grad"] = _out(out, "grad", (B, T, Vp1), torch.float32, dev)
+    rc = ctx.lib.ctc_loss(ctx.handle, _ptr(logits, torch.float32), _ptr(labels, torch.int32),
+                          _ptr(label_len, torch.int32), _ptr(frame_len, torch.int32), B, T, Vp1, Lmax, blank_id,
+                          _ptr(workspace, torch.uint8), workspace.numel(), _ptr(res["loss"]), _ptr(res.get("grad")))
+    ctx._check(rc, "ctc_loss")
     return res

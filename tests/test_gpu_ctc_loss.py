@@ -1,0 +1,104 @@
+"""GPU parity of ctc_loss (Sec. 3.2: negative log of Eq. 5 and its gradient) against the oracle.
+
+fp32 logits in, the recursions in fp32 log space: a log-probability after t frames has magnitude about t times
+the per-frame entropy, and every frame adds a rounding of its ulp, so the loss is held to a relative 1e-5 + 2e-7
+per frame and the gradient (entries in [-1, 1]) to 2e-3 relative with an RMS floor, the bar of the other float
+outputs.  Rows of the gradient must sum to zero, frames past frame_len and unreachable labels give zeros, and a
+second call reproduces every bit.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_harness import rel_err_rms_floor
+from workloads.device import dev_f32, dev_i32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2412_00061_amd as m
+    m.load_library()
+    return m
+
+
+def _case(seed, B, T, C, Lmax, blank, repeat_heavy=False, scale=2.0):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    logits = (rng.standard_normal((B, T, C), dtype=np.float32) * np.float32(scale))
+    frame_len = rng.integers(max(1, T // 2), T + 1, size=B).astype(np.int32)
+    frame_len[0] = T
+    label_len = np.array([rng.integers(0, min(Lmax, int(f)) + 1) for f in frame_len], dtype=np.int32)
+    label_len[0] = min(Lmax, T // 2)
+    toks = [v for v in range(C) if v != blank]
+    pool = toks[:3] if repeat_heavy else toks
+    labels = rng.choice(pool, size=(B, Lmax)).astype(np.int32)
+    return logits, labels, label_len, frame_len
+
+
+def _check(pkg, seed, B, T, C, Lmax, blank, **kw):
+    logits, labels, label_len, frame_len = _case(seed, B, T, C, Lmax, blank, **kw)
+    ctx = pkg.Context(max_batch=max(B, 1), max_slots=8, max_topk=4, max_vocab_rows=max(C, 8), max_nodes=8, max_heads=1,
+                      max_head_dim=8)
+    print(f"ctc_loss seed={seed} B={B} T={T} V+1={C} Lmax={Lmax}", flush=True)
+    args = (dev_f32(logits), dev_i32(labels), dev_i32(label_len), dev_i32(frame_len), blank)
+    res = pkg.ctc_loss(ctx, *args)
+    again = pkg.ctc_loss(ctx, *args)
+    only_loss = pkg.ctc_loss(ctx, *args, want_grad=False)
+    torch.cuda.synchronize()
+    loss, grad = res["loss"].cpu().numpy(), res["grad"].cpu().numpy()
+    assert torch.equal(res["loss"], again["loss"]) and torch.equal(res["grad"], again["grad"])
+    assert torch.equal(res["loss"], only_loss["loss"])
+    for b in range(B):
+        Tb, L = int(frame_len[b]), int(label_len[b])
+        ref_loss, ref_grad = oracle.ctc_loss_and_grad(logits[b, :Tb], tuple(int(v) for v in labels[b, :L]), blank)
+        if math.isinf(ref_loss):
+            assert math.isinf(loss[b]) and not grad[b].any()
+            continue
+        assert abs(loss[b] - ref_loss) <= (1e-5 + 2e-7 * Tb) * max(1.0, abs(ref_loss)), (b, loss[b], ref_loss)
+        assert rel_err_rms_floor(grad[b, :Tb], ref_grad) <= 2e-3, (b, rel_err_rms_floor(grad[b, :Tb], ref_grad))
+        assert np.max(np.abs(grad[b, :Tb].sum(-1))) <= 2e-3, np.max(np.abs(grad[b, :Tb].sum(-1)))
+        assert not grad[b, Tb:].any()
+    ctx.close()
+
+
+@pytest.mark.parametrize("seed,B,T,C,Lmax,blank,kw", [
+    (0, 4, 8, 12, 8, 11, {}),                         # the draft slots' shape: 8 frames, at most 8 labels
+    (1, 3, 40, 50, 16, 0, {}),                        # blank first in the vocabulary
+    (2, 5, 24, 9, 12, 4, dict(repeat_heavy=True)),    # repeated tokens: blanks forced between, shared rows
+    (3, 2, 96, 300, 40, 299, {}),                     # several states per thread's row in LDS
+    (4, 2, 200, 64, 100, 63, dict(scale=1.0)),        # 201 states
+    (5, 1, 6, 5, 6, 2, dict(repeat_heavy=True)),      # labels that cannot be reached
+])
+def test_ctc_loss_shapes(pkg, seed, B, T, C, Lmax, blank, kw):
+    _check(pkg, seed, B, T, C, Lmax, blank, **kw)
+
+
+def test_ctc_loss_vocabulary_size_of_the_head(pkg):
+    """V+1 = 32001 rows through LDS, 8 frames per position as the draft head produces them."""
+    _check(pkg, 7, 6, 8, 32001, 8, 32000)
+
+
+def test_ctc_loss_many_states(pkg):
+    """1025 labels: 2051 states, three per thread; the float64 oracle takes a few seconds."""
+    _check(pkg, 8, 1, 1300, 40, 1025, 39, scale=0.5)
+
+
+def test_ctc_loss_rejects_bad_arguments(pkg):
+    ctx = pkg.Context(max_batch=1, max_slots=8, max_topk=4, max_vocab_rows=8, max_nodes=8, max_heads=1, max_head_dim=8)
+    z = dev_f32(np.zeros((1, 4, 6), dtype=np.float32))
+    one = dev_i32(np.array([1], dtype=np.int32))
+    with pytest.raises(pkg.CtcspecError, match="blank_id"):
+        pkg.ctc_loss(ctx, z, dev_i32(np.zeros((1, 2), dtype=np.int32)), one, one, 6)
+    with pytest.raises(pkg.CtcspecError, match="Lmax"):
+        pkg.ctc_loss(ctx, z, dev_i32(np.zeros((1, 2048), dtype=np.int32)), one, one, 5)
+    with pytest.raises(pkg.CtcspecError, match="workspace"):
+        pkg.ctc_loss(ctx, z, dev_i32(np.zeros((1, 2), dtype=np.int32)), one, one, 5,
+                     workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    wide = dev_f32(np.zeros((1, 1, 40000), dtype=np.float32))
+    with pytest.raises(pkg.CtcspecError, match="LDS"):
+        pkg.ctc_loss(ctx, wide, dev_i32(np.zeros((1, 2), dtype=np.int32)), one, one, 5)
+    ctx.close()
