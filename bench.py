@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--no-draft-layer", action="store_true")
     ap.add_argument("--no-sum-score", action="store_true")
     ap.add_argument("--no-literal-layout", action="store_true")
+    ap.add_argument("--no-ctc-loss", action="store_true")
+    ap.add_argument("--ctc-loss-positions", type=int, default=4096,
+                    help="training positions of the ctc_loss line, each with T frames over V+1 symbols")
     ap.add_argument("--draft-layer-ffn", type=int, default=0,
                     help="feed-forward width of the draft module's layer (0: the base family's, 43/16 of D)")
     ap.add_argument("--cpu-steps", type=int, default=12)
@@ -440,6 +443,44 @@ def main():
                      "candidates_whose_rank_differs_from_the_best_alignment_order": changed,
                      "bound": "latency (KB-sized: one wavefront per candidate, T dependent steps)"}
 
+    # the training objective (Sec. 3.2) at two shapes: T frames per position against the next <= T tokens, for many
+    # positions at once (bandwidth: each row of logits read once, its gradient row written once), and whole
+    # sequences at the paper's maximum training length (the recursions' latency: two dependent passes over the frames)
+    ctc_loss = None
+    if not args.no_ctc_loss:
+        ctc_loss = {}
+        for tag, (nb, nt, nl) in {"per_position": (args.ctc_loss_positions, T, T), "whole_sequence": (4, 2048, 1024)}.items():
+            gen = torch.Generator(device="cuda").manual_seed(args.seed + 17)
+            z = torch.randn((nb, nt, cfg.Vp1), dtype=torch.float32, device="cuda", generator=gen) * 2.0
+            lab = torch.randint(0, cfg.Vp1 - 1, (nb, nl), dtype=torch.int32, device="cuda", generator=gen)
+            lab_len = torch.randint(1, nl + 1, (nb,), dtype=torch.int32, device="cuda", generator=gen)
+            fr_len = torch.full((nb,), nt, dtype=torch.int32, device="cuda")
+            ws = torch.empty(lib.ctc_loss_workspace_bytes(nb, nt, nl), dtype=torch.uint8, device="cuda")
+            out_l = torch.empty((nb,), dtype=torch.float32, device="cuda")
+            out_g = torch.empty_like(z)
+            cl_call = lib.prepared(ctx, "ctc_loss", z, lab, lab_len, fr_len, nb, nt, cfg.Vp1, nl, cfg.blank_id, ws,
+                                   ws.numel(), out_l, out_g)
+            for _ in range(3):
+                cl_call()
+            torch.cuda.synchronize()
+            n_cl = 10
+            cl_ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_cl + 1)]
+            cl_ev[0].record()
+            for i in range(n_cl):
+                cl_call()
+                cl_ev[i + 1].record()
+            torch.cuda.synchronize()
+            cl_us = float(np.median([cl_ev[i].elapsed_time(cl_ev[i + 1]) * 1e3 for i in range(n_cl)]))
+            cl_bytes = nb * nt * cfg.Vp1 * 8
+            rows_zero = float(out_g.sum(-1).abs().max())
+            ctc_loss[tag] = {"call": "ctc_loss", "shape": f"B={nb} T={nt} V+1={cfg.Vp1} Lmax={nl}", "us_per_call_median": cl_us,
+                             "frames_per_sec": nb * nt / (cl_us * 1e-6), "algorithmic_bytes": cl_bytes,
+                             "hbm_gbps": cl_bytes / (cl_us * 1e-6) / 1e9,
+                             "frac_of_hbm_peak": cl_bytes / (cl_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                             "finite_losses": int(torch.isfinite(out_l).sum()), "max_abs_gradient_row_sum": rows_zero}
+            del z, out_g, ws
+        torch.cuda.empty_cache()
+
     # A/B of the tree layout: the paper's literal one (raw candidates at full length, removed positions masked)
     # under the same node cap, against the collapsed tree the step uses.  Statistics only; same kernel otherwise.
     literal = None
@@ -528,6 +569,7 @@ def main():
         "draft_layer_variant": draft_layer,
         "sum_score_variant": sum_score,
         "literal_layout_variant": literal,
+        "ctc_loss_variant": ctc_loss,
         "roofline": {"kernel": "lmhead_bf16_mfma_kernel (ctc_draft_topk)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": read_traffic_summary(), "algorithmic_bytes_per_launch": head_b,

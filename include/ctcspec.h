@@ -352,7 +352,7 @@ int ctc_raw_tree(ctcspec_ctx* ctx, const int32_t* topk_id, const float* topk_log
  * loss       [B] float device out; +inf when the label cannot be reached in frame_len frames
  * grad       [B,T,Vp1] float device out or NULL: d loss[b] / d logits[b,t,v]; zero for frames past frame_len and
  *            for sequences whose loss is +inf
- * Limits: Lmax <= 2047, Vp1 * 4 bytes <= 150 KB, B <= 65535.  The same bits on every run.
+ * Limits: Lmax <= 2047, Vp1 <= 65536, B <= 65535; logits and grad 16-byte aligned.  The same bits on every run.
  */
 size_t ctc_loss_workspace_bytes(int B, int T, int Lmax);
 

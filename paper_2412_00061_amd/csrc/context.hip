@@ -85,7 +85,7 @@ extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec
   unsigned char* base = (unsigned char*)ctx->ws;
   e = hipMemset(base + o_zero, 0, 256);  // read by loads that must fetch something harmless
   if (e != hipSuccess) {
-    hipFree(ctx->ws);
+    (void)hipFree(ctx->ws);
     delete ctx;
     return fail(nullptr, CTCSPEC_EHIP, "hipMemset failed: %s", hipGetErrorString(e));
   }

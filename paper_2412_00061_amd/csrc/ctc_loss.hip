@@ -2,15 +2,16 @@
 // with respect to the logits, by the forward-backward recursions of the CTC paper the section cites.
 //
 // Two kinds of work, kept apart:
-//   * the rows of logits ([V+1] floats per frame, 128 KB at V = 32000) are what costs HBM time.  They are read
-//     twice and written once, each time a whole row through LDS by one workgroup: ctc_row_kernel takes the
-//     log-sum-exp of a row and picks out the few log-probabilities the recursions need (the label's tokens and
-//     the blank); ctc_grad_kernel turns the row into its softmax, subtracts the occupancies of those few
-//     symbols and writes the gradient row.
+//   * the rows of logits ([V+1] floats per frame, 128 KB at V = 32000) are what costs HBM time.  Each is read
+//     once and its gradient row written once, by one workgroup that holds the row in registers: ctc_row_kernel takes
+//     the log-sum-exp, picks out the few log-probabilities the recursions need (the label's tokens and the
+//     blank) and writes the row's softmax as the gradient; after the recursions ctc_fix_kernel subtracts the
+//     occupancies from those few entries.
 //   * the recursions themselves are KB-sized and sequential in the frames: ctc_dp_kernel, one workgroup per
-//     sequence, a thread per state of the extended sequence (blank, y1, blank, ..., blank), the neighbours'
-//     values through LDS, one barrier per frame.  Forward stores log alpha per frame; backward turns it in place
-//     into the occupancy gamma_t(s) = alpha_t(s) beta_t(s) / (p_t(z_s) P).
+//     sequence and direction, a thread per state of the extended sequence (blank, y1, blank, ..., blank), the neighbours'
+//     values through LDS, one barrier per frame.  The forward and the backward recursion of a sequence run at
+//     the same time in two workgroups; the occupancy gamma_t(s) = alpha_t(s) beta_t(s) / (p_t(z_s) P) is formed
+//     where it is used.
 // A token that occurs several times in a label has several states; their occupancies are added in label order
 // by the thread of the first occurrence (links built once per sequence), so no atomic is needed and the result
 // has the same bits on every run.
@@ -20,6 +21,9 @@ namespace ctcspec {
 
 constexpr int kCtcMaxLabels = 2047;  // 2L + 1 states <= 4 per thread of a 1024-thread workgroup
 constexpr int kCtcRowThreads = 512;
+constexpr int kCtcMaxRow = 32 * kCtcRowThreads * 4;  // 65536 symbols: 32 16-byte loads per thread
+constexpr int kCtcFixThreads = 256;
+constexpr int kCtcAhead = 8;  // frames between a load and its use in the recursions
 
 struct CtcParams {
   const float* logits;      // [B][T][Vp1]
@@ -30,8 +34,11 @@ struct CtcParams {
   // workspace
   float* lse;     // [B][T]
   float* lpc;     // [B][T][Lmax + 1]: log p_t(y_j) for j < L, log p_t(blank) at Lmax
-  float* ag;      // [B][T][2 Lmax + 1]: log alpha minus the frame's offset, then gamma
-  double* coff;   // [B][T]: offset of the frame's log alpha values
+  float* ag;      // [B][T][2 Lmax + 1]: log alpha minus the frame's offset
+  float* bg;      // [B][T][2 Lmax + 1]: log beta minus the frame's offset
+  double* coff_a; // [B][T]: offset of the frame's log alpha values
+  double* coff_b; // [B][T]: offset of the frame's log beta values
+  double* logp;   // [B]: log P(Y | X)
   int32_t* next;  // [B][Lmax]: next label position with the same token, -1: none
   int32_t* first; // [B][Lmax]: 1 when no earlier position holds the same token
   // outputs
@@ -39,62 +46,116 @@ struct CtcParams {
   float* grad;    // [B][T][Vp1] or null
 };
 
-__device__ __forceinline__ float ctc_log_add(float a, float b) {
-  const float hi = fmaxf(a, b), lo = fminf(a, b);
-  if (hi == -INFINITY) return -INFINITY;
-  return hi + log1pf(expf(lo - hi));
+// log(e^a + e^b + e^c) without a branch; -inf stands for an impossible state and any of the three may be -inf.
+// The bare exp2/log2 instructions carry an absolute error near 1e-7 here (the arguments of exp are <= 0, the
+// argument of log is in [1, 3]; a term below 2^-126 of the largest is dropped), far below what the occupancies need.
+__device__ __forceinline__ float ctc_log_add3(float a, float b, float c) {
+  const float m = fmaxf(fmaxf(a, b), c);
+  const float ms = m > -INFINITY ? m : 0.f;
+  constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+  const float sum = __builtin_amdgcn_exp2f((a - ms) * kLog2e) + __builtin_amdgcn_exp2f((b - ms) * kLog2e) +
+                    __builtin_amdgcn_exp2f((c - ms) * kLog2e);
+  return ms + kLn2 * __builtin_amdgcn_logf(sum);  // the bare log2 instruction; sum = 0 gives -inf
 }
-// largest of the wavefronts' maxima of one frame; 0 when every state is impossible, so that offsets stay finite
-__device__ __forceinline__ float frame_max(const float* w, int n) {
-  float m = w[0];
-  for (int i = 1; i < n; ++i) m = fmaxf(m, w[i]);
+// largest of the wavefronts' maxima of one frame (slots of absent wavefronts hold -inf); 0 when every state is
+// impossible, so that offsets stay finite
+__device__ __forceinline__ float frame_max(const float* w) {
+  const f32x4* v = (const f32x4*)w;
+  const f32x4 a = v[0], b = v[1], c = v[2], d = v[3];
+  float m = fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])), fmaxf(fmaxf(b[0], b[1]), fmaxf(b[2], b[3])));
+  m = fmaxf(m, fmaxf(fmaxf(fmaxf(c[0], c[1]), fmaxf(c[2], c[3])), fmaxf(fmaxf(d[0], d[1]), fmaxf(d[2], d[3]))));
   return m > -INFINITY ? m : 0.f;
 }
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-// per sequence: links between the label positions that hold the same token
-__global__ __launch_bounds__(256) void ctc_links_kernel(CtcParams p) {
-  const int b = blockIdx.x;
+// per sequence: links between the label positions that hold the same token.  The label is staged in LDS; one
+// wavefront per position looks for the nearest later position with the same token, 64 candidates at a time, and
+// a position that some earlier one points to is not a first occurrence.
+__global__ __launch_bounds__(1024) void ctc_links_kernel(CtcParams p) {
+  extern __shared__ int32_t ytok[];  // [Lmax]
+  const int b = blockIdx.x, tid = threadIdx.x, n = blockDim.x;
+  const int lane = tid & 63, wave = tid >> 6, nwaves = n >> 6;
   const int L = clampi(p.label_len[b], 0, p.Lmax);
-  const int32_t* y = p.labels + (size_t)b * p.Lmax;
-  for (int j = threadIdx.x; j < p.Lmax; j += 256) {
-    int nx = -1, fst = 1;
-    if (j < L) {
-      const int tok = y[j];
-      for (int i = j + 1; i < L; ++i)
-        if (y[i] == tok) { nx = i; break; }
-      for (int i = 0; i < j; ++i)
-        if (y[i] == tok) { fst = 0; break; }
-    } else {
-      fst = 0;
+  int32_t* next = p.next + (size_t)b * p.Lmax;
+  int32_t* first = p.first + (size_t)b * p.Lmax;
+  for (int j = tid; j < p.Lmax; j += n) {
+    ytok[j] = j < L ? p.labels[(size_t)b * p.Lmax + j] : -1;
+    next[j] = -1;
+    first[j] = j < L;
+  }
+  __syncthreads();  // also puts the defaults just stored before the updates below
+  for (int j = wave; j < L; j += nwaves) {
+    const int tok = ytok[j];
+    int found = -1;
+    for (int i0 = j + 1; i0 < L && found < 0; i0 += 64) {
+      const int i = i0 + lane;
+      const unsigned long long hits = __ballot(i < L && ytok[i] == tok);
+      if (hits) found = i0 + __ffsll((long long)hits) - 1;
     }
-    p.next[(size_t)b * p.Lmax + j] = nx;
-    p.first[(size_t)b * p.Lmax + j] = fst;
+    if (found >= 0 && lane == 0) {
+      next[j] = found;
+      first[found] = 0;
+    }
   }
 }
 
-// one workgroup per frame row: row -> LDS, log-sum-exp, the log-probabilities of the label's tokens and the blank
+// One workgroup per frame row, the row held in registers: every load of the row is in flight before the first
+// is used, then log-sum-exp, the few log-probabilities the recursions need (the label's tokens and the blank),
+// and the row's softmax written as the gradient.  Rows start at any multiple of 4 bytes (V + 1 is odd at
+// V = 32000), so the up to three elements in front of the first 16-byte boundary and behind the last go through
+// single lanes and the body through 16-byte loads and stores.
+template <int NV>  // 16-byte loads per thread: NV * kCtcRowThreads * 4 >= V + 1
 __global__ __launch_bounds__(kCtcRowThreads) void ctc_row_kernel(CtcParams p) {
-  extern __shared__ __attribute__((aligned(16))) float row[];
   __shared__ float red[kCtcRowThreads / 64];
   const int t = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int Tb = clampi(p.frame_len[b], 0, p.T);
-  if (t >= Tb) return;
-  const float* z = p.logits + ((size_t)b * p.T + t) * p.Vp1;
-  float mx = -INFINITY;
-  for (int v = tid; v < p.Vp1; v += kCtcRowThreads) {
-    const float x = z[v];
-    row[v] = x;
-    mx = fmaxf(mx, x);
+  const size_t row0 = ((size_t)b * p.T + t) * p.Vp1;
+  int head = (int)((4 - (row0 & 3)) & 3);
+  head = head < p.Vp1 ? head : p.Vp1;
+  const int nvec = (p.Vp1 - head) >> 2;
+  const int tail0 = head + 4 * nvec;
+  // the lane of an edge element: lanes 0..2 take the head, lanes 64..66 the tail
+  int edge = -1;
+  if (tid < head) edge = tid;
+  else if (tid >= 64 && tid - 64 < p.Vp1 - tail0) edge = tail0 + tid - 64;
+  float* g = p.grad ? p.grad + row0 : nullptr;
+  if (t >= Tb) {  // frames past the sequence: no gradient
+    if (g) {
+      f32x4* gv = (f32x4*)(g + head);
+      for (int i = tid; i < nvec; i += kCtcRowThreads) gv[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (edge >= 0) g[edge] = 0.f;
+    }
+    return;
   }
+  const float* z = p.logits + row0;
+  const f32x4* zv = (const f32x4*)(z + head);
+  f32x4 x[NV];
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int i = tid + k * kCtcRowThreads;
+    x[k] = i < nvec ? zv[i] : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  }
+  float xe = edge >= 0 ? z[edge] : -INFINITY;
+  float mx = xe;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) mx = fmaxf(fmaxf(fmaxf(mx, x[k][0]), fmaxf(x[k][1], x[k][2])), x[k][3]);
   mx = wave_max_f32(mx);
   if ((tid & 63) == 0) red[tid >> 6] = mx;
   __syncthreads();
   mx = red[0];
 #pragma unroll
   for (int w = 1; w < kCtcRowThreads / 64; ++w) mx = fmaxf(mx, red[w]);
-  float sum = 0.f;
-  for (int v = tid; v < p.Vp1; v += kCtcRowThreads) sum += expf(row[v] - mx);
+  // e = exp(x - max) stays in the registers: the softmax is e / sum
+  xe = expf(xe - mx);
+  float sum = xe;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      x[k][c] = expf(x[k][c] - mx);
+      sum += x[k][c];
+    }
+  }
   sum = wave_sum_f32(sum);
   __syncthreads();
   if ((tid & 63) == 0) red[tid >> 6] = sum;
@@ -106,29 +167,41 @@ __global__ __launch_bounds__(kCtcRowThreads) void ctc_row_kernel(CtcParams p) {
   if (tid == 0) p.lse[(size_t)b * p.T + t] = lse;
   const int L = clampi(p.label_len[b], 0, p.Lmax);
   float* out = p.lpc + ((size_t)b * p.T + t) * (p.Lmax + 1);
-  for (int j = tid; j < L; j += kCtcRowThreads) out[j] = row[clampi(p.labels[(size_t)b * p.Lmax + j], 0, p.Vp1 - 1)] - lse;
-  if (tid == 0) out[p.Lmax] = row[p.blank] - lse;
+  for (int j = tid; j < L; j += kCtcRowThreads) out[j] = z[clampi(p.labels[(size_t)b * p.Lmax + j], 0, p.Vp1 - 1)] - lse;
+  if (tid == 0) out[p.Lmax] = z[p.blank] - lse;
+  if (g) {
+    const float inv = 1.f / sum;
+    f32x4* gv = (f32x4*)(g + head);
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int i = tid + k * kCtcRowThreads;
+      if (i < nvec) gv[i] = x[k] * inv;
+    }
+    if (edge >= 0) g[edge] = xe * inv;
+  }
 }
 
-// one workgroup per sequence: forward and backward recursion over the frames
+// Two workgroups per sequence, on different compute units at the same time: blockIdx.y = 0 runs the forward
+// recursion (log alpha, the loss), blockIdx.y = 1 the backward one (log beta).  Neither needs the other's values;
+// the occupancies that need both are formed afterwards, in ctc_fix_kernel.
 template <int NS>  // states per thread
 __global__ __launch_bounds__(1024) void ctc_dp_kernel(CtcParams p) {
   extern __shared__ float lds[];  // two rows of Smax + 4 values (two -inf entries in front and behind)
   const int b = blockIdx.x, tid = threadIdx.x, nthreads = blockDim.x;
+  const bool backward = blockIdx.y != 0;
   const int Smax = 2 * p.Lmax + 1;
   const int L = clampi(p.label_len[b], 0, p.Lmax);
   const int S = 2 * L + 1;
   const int Tb = clampi(p.frame_len[b], 0, p.T);
   const int pitch = Smax + 4;
-  float* rowbuf[2] = {lds + 2, lds + pitch + 2};
-  __shared__ float wmax[2][16];  // per frame parity: the wavefronts' largest value
-  const int nwaves = nthreads >> 6;
+  __shared__ __attribute__((aligned(16))) float wmax[2][16];  // per frame parity: the wavefronts' largest value
   const int32_t* y = p.labels + (size_t)b * p.Lmax;
   const float* lpc = p.lpc + (size_t)b * p.T * (p.Lmax + 1);
-  float* ag = p.ag + (size_t)b * p.T * Smax;
-  double* coff = p.coff + (size_t)b * p.T;
   if (Tb == 0) {
-    if (tid == 0) p.loss[b] = L == 0 ? 0.f : INFINITY;
+    if (tid == 0 && !backward) {
+      p.loss[b] = L == 0 ? 0.f : INFINITY;
+      p.logp[b] = L == 0 ? 0.0 : -(double)INFINITY;
+    }
     return;
   }
   // per state of this thread: index of its log-probability in a frame's compact row, and whether the transition
@@ -139,144 +212,170 @@ __global__ __launch_bounds__(1024) void ctc_dp_kernel(CtcParams p) {
   for (int u = 0; u < NS; ++u) {
     const int s = tid + u * nthreads;
     const int j = s >> 1;
-    col[u] = (s & 1) ? j : p.Lmax;
+    col[u] = ((s & 1) && s < S) ? j : p.Lmax;  // states past the label read the blank's entry and drop it
     skip_in[u] = (s & 1) && s >= 3 && s < S && y[j] != y[j - 1];
     skip_out[u] = (s & 1) && s + 2 < S && y[j] != y[j + 1];
   }
   for (int i = tid; i < 2 * pitch; i += nthreads) lds[i] = -INFINITY;
+  if (tid < 32) wmax[tid >> 4][tid & 15] = -INFINITY;
   __syncthreads();
 
-  // ---- forward ------------------------------------------------------------------------------------------------
-  double c_alpha = 0.0;  // the stored values of the frame are log alpha - c_alpha
-  for (int t = 0; t < Tb; ++t) {
-    float* cur = rowbuf[t & 1];
-    const float* prev = rowbuf[(t & 1) ^ 1];
-    const float* lp = lpc + (size_t)t * (p.Lmax + 1);
-    float shift = 0.f;
-    if (t > 0) {
-      shift = frame_max(wmax[(t & 1) ^ 1], nwaves);
-      c_alpha += (double)shift;
-    }
-    float mine = -INFINITY;
-#pragma unroll
-    for (int u = 0; u < NS; ++u) {
-      const int s = tid + u * nthreads;
-      if (s < S) {
-        float a;
-        if (t == 0) {
-          a = s < 2 ? 0.f : -INFINITY;
-        } else {
-          a = ctc_log_add(prev[s], prev[s - 1]);
-          if (skip_in[u]) a = ctc_log_add(a, prev[s - 2]);
-        }
-        a += lp[col[u]] - shift;
-        cur[s] = a;
-        ag[(size_t)t * Smax + s] = a;
-        mine = fmaxf(mine, a);
-      }
-    }
-    mine = wave_max_f32(mine);
-    if ((tid & 63) == 0) wmax[t & 1][tid >> 6] = mine;
-    if (tid == 0) coff[t] = c_alpha;
-    __syncthreads();
-  }
-  const float* last = rowbuf[(Tb - 1) & 1];
-  const float tail = S > 1 ? ctc_log_add(last[S - 1], last[S - 2]) : last[S - 1];
-  const double logP = c_alpha + (double)tail;  // -inf when the label cannot be reached
-  if (tid == 0) p.loss[b] = (float)-logP;
-  __syncthreads();
-  for (int i = tid; i < 2 * pitch; i += nthreads) lds[i] = -INFINITY;
-  __syncthreads();
-  if (!p.grad) return;
+  // A frame's log-probabilities are loaded several frames before the frame's turn, into a ring of registers: the
+  // chain from frame to frame then runs through LDS and arithmetic only.  The barrier of a frame orders LDS
+  // alone, so these loads and the stores of the frame's results stay in flight across it.
+  constexpr int AHEAD = NS >= 4 ? kCtcAhead / 2 : kCtcAhead;  // the ring has to fit 128 registers at 1024 threads
+  const int lp_pitch = p.Lmax + 1;
+  float lpr[AHEAD][NS];
 
-  // ---- backward; log alpha in the workspace becomes gamma -------------------------------------------------------
-  const bool reachable = tail > -INFINITY;
-  double c_beta = 0.0;  // the values of the frame in LDS are log beta - c_beta
-  for (int t = Tb - 1; t >= 0; --t) {
-    float* cur = rowbuf[t & 1];
-    const float* nxt = rowbuf[(t & 1) ^ 1];
-    const float* lp = lpc + (size_t)t * (p.Lmax + 1);
-    float shift = 0.f;
-    if (t < Tb - 1) {
-      shift = frame_max(wmax[(t & 1) ^ 1], nwaves);
-      c_beta += (double)shift;
-    }
-    // log of P over the two offsets of this frame: what alpha-hat + beta-hat - log p has to be measured against
-    const float z = reachable ? (float)(logP - coff[t] - c_beta) : 0.f;
-    float mine = -INFINITY;
+  if (!backward) {
+    float* ag = p.ag + (size_t)b * p.T * Smax;
+    double* coff = p.coff_a + (size_t)b * p.T;
 #pragma unroll
-    for (int u = 0; u < NS; ++u) {
-      const int s = tid + u * nthreads;
-      if (s < S) {
-        float bt;
-        if (t == Tb - 1) {
-          bt = s >= S - 2 ? 0.f : -INFINITY;
-        } else {
-          bt = ctc_log_add(nxt[s], nxt[s + 1]);
-          if (skip_out[u]) bt = ctc_log_add(bt, nxt[s + 2]);
+    for (int i = 0; i < AHEAD; ++i) {
+      const int tt = i < Tb ? i : Tb - 1;
+#pragma unroll
+      for (int u = 0; u < NS; ++u) lpr[i][u] = lpc[(size_t)tt * lp_pitch + col[u]];
+    }
+    double c_alpha = 0.0;  // the stored values of the frame are log alpha - c_alpha
+    for (int t0 = 0; t0 < Tb; t0 += AHEAD) {
+#pragma unroll
+      for (int i = 0; i < AHEAD; ++i) {
+        const int t = t0 + i;
+        if (t < Tb) {
+          float* cur = lds + 2 + (t & 1) * pitch;  // offsets, not a table of pointers: keeps these LDS accesses
+          const float* prev = lds + 2 + ((t & 1) ^ 1) * pitch;
+          float shift = 0.f;
+          if (t > 0) {
+            shift = frame_max(wmax[(t & 1) ^ 1]);
+            c_alpha += (double)shift;
+          }
+          float mine = -INFINITY;
+#pragma unroll
+          for (int u = 0; u < NS; ++u) {
+            const int s = tid + u * nthreads;
+            if (s < S) {
+              float a;
+              if (t == 0) a = s < 2 ? 0.f : -INFINITY;
+              else a = ctc_log_add3(prev[s], prev[s - 1], skip_in[u] ? prev[s - 2] : -INFINITY);
+              a += lpr[i][u] - shift;
+              cur[s] = a;
+              ag[(size_t)t * Smax + s] = a;
+              mine = fmaxf(mine, a);
+            }
+          }
+          mine = wave_max_f32(mine);
+          if ((tid & 63) == 0) wmax[t & 1][tid >> 6] = mine;
+          if (tid == 0) coff[t] = c_alpha;
+          const int tn = t + AHEAD < Tb ? t + AHEAD : Tb - 1;
+#pragma unroll
+          for (int u = 0; u < NS; ++u) lpr[i][u] = lpc[(size_t)tn * lp_pitch + col[u]];
+          lds_barrier();
         }
-        const float l = lp[col[u]];
-        bt += l - shift;
-        cur[s] = bt;
-        mine = fmaxf(mine, bt);
-        const float al = ag[(size_t)t * Smax + s];
-        const float e = al + bt - l - z;
-        ag[(size_t)t * Smax + s] = (reachable && al > -INFINITY && bt > -INFINITY) ? expf(e) : 0.f;
       }
     }
-    mine = wave_max_f32(mine);
-    if ((tid & 63) == 0) wmax[t & 1][tid >> 6] = mine;
-    __syncthreads();
+    const float* last = lds + 2 + ((Tb - 1) & 1) * pitch;
+    const float tail = ctc_log_add3(last[S - 1], S > 1 ? last[S - 2] : -INFINITY, -INFINITY);
+    const double logP = c_alpha + (double)tail;  // -inf when the label cannot be reached
+    if (tid == 0) {
+      p.loss[b] = (float)-logP;
+      p.logp[b] = logP;
+    }
+  } else {
+    float* bg = p.bg + (size_t)b * p.T * Smax;
+    double* coff = p.coff_b + (size_t)b * p.T;
+#pragma unroll
+    for (int i = 0; i < AHEAD; ++i) {
+      const int tt = Tb - 1 - i >= 0 ? Tb - 1 - i : 0;
+#pragma unroll
+      for (int u = 0; u < NS; ++u) lpr[i][u] = lpc[(size_t)tt * lp_pitch + col[u]];
+    }
+    double c_beta = 0.0;  // the stored values of the frame are log beta - c_beta
+    for (int t0 = Tb - 1; t0 >= 0; t0 -= AHEAD) {
+#pragma unroll
+      for (int i = 0; i < AHEAD; ++i) {
+        const int t = t0 - i;
+        if (t >= 0) {
+          float* cur = lds + 2 + (t & 1) * pitch;
+          const float* nxt = lds + 2 + ((t & 1) ^ 1) * pitch;
+          float shift = 0.f;
+          if (t < Tb - 1) {
+            shift = frame_max(wmax[(t & 1) ^ 1]);
+            c_beta += (double)shift;
+          }
+          float mine = -INFINITY;
+#pragma unroll
+          for (int u = 0; u < NS; ++u) {
+            const int s = tid + u * nthreads;
+            if (s < S) {
+              float bt;
+              if (t == Tb - 1) bt = s >= S - 2 ? 0.f : -INFINITY;
+              else bt = ctc_log_add3(nxt[s], nxt[s + 1], skip_out[u] ? nxt[s + 2] : -INFINITY);
+              bt += lpr[i][u] - shift;  // beta_t(s) includes p_t(z_s)
+              cur[s] = bt;
+              bg[(size_t)t * Smax + s] = bt;
+              mine = fmaxf(mine, bt);
+            }
+          }
+          mine = wave_max_f32(mine);
+          if ((tid & 63) == 0) wmax[t & 1][tid >> 6] = mine;
+          if (tid == 0) coff[t] = c_beta;
+          const int tn = t - AHEAD >= 0 ? t - AHEAD : 0;
+#pragma unroll
+          for (int u = 0; u < NS; ++u) lpr[i][u] = lpc[(size_t)tn * lp_pitch + col[u]];
+          lds_barrier();
+        }
+      }
+    }
   }
 }
 
-// one workgroup per frame row: softmax of the row minus the occupancies of the label's tokens and of the blank
-__global__ __launch_bounds__(kCtcRowThreads) void ctc_grad_kernel(CtcParams p) {
-  extern __shared__ __attribute__((aligned(16))) float row[];
-  __shared__ float red[kCtcRowThreads / 64];
-  const int t = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+// One wavefront per frame: the occupancies gamma_t(s) = alpha_t(s) beta_t(s) / (p_t(z_s) P) of the label's tokens
+// and of the blank come off the softmax that ctc_row_kernel left in the gradient row.  Only these few entries of
+// the row are touched.
+__global__ __launch_bounds__(kCtcFixThreads) void ctc_fix_kernel(CtcParams p) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * (kCtcFixThreads / 64) + (threadIdx.x >> 6), b = blockIdx.y;
   const int Tb = clampi(p.frame_len[b], 0, p.T);
-  float* g = p.grad + ((size_t)b * p.T + t) * p.Vp1;
-  const float loss = p.loss[b];
-  if (t >= Tb || !(loss < INFINITY)) {  // frames past the sequence, or a label that cannot be reached: no gradient
-    for (int v = tid; v < p.Vp1; v += kCtcRowThreads) g[v] = 0.f;
+  if (t >= Tb) return;  // rows past the sequence were written as zeros
+  float* __restrict__ g = p.grad + ((size_t)b * p.T + t) * p.Vp1;
+  const double logP = p.logp[b];
+  if (!(logP > -(double)INFINITY)) {  // a label that cannot be reached has no gradient
+    for (int v = lane; v < p.Vp1; v += 64) g[v] = 0.f;
     return;
   }
-  const float* z = p.logits + ((size_t)b * p.T + t) * p.Vp1;
-  const float lse = p.lse[(size_t)b * p.T + t];
-  for (int v = tid; v < p.Vp1; v += kCtcRowThreads) row[v] = expf(z[v] - lse);
   const int L = clampi(p.label_len[b], 0, p.Lmax);
   const int Smax = 2 * p.Lmax + 1;
-  const float* gamma = p.ag + ((size_t)b * p.T + t) * Smax;
+  const size_t frame = (size_t)b * p.T + t;
+  const float* __restrict__ al = p.ag + frame * Smax;
+  const float* __restrict__ be = p.bg + frame * Smax;
+  const float* __restrict__ lp = p.lpc + frame * (p.Lmax + 1);
+  // log of P over the two offsets of this frame: what the stored alpha + beta - log p is measured against
+  const float z = (float)(logP - p.coff_a[frame] - p.coff_b[frame]);
+  auto gamma = [&](int s, float l) {
+    const float a = al[s], bt = be[s];
+    return (a > -INFINITY && bt > -INFINITY) ? expf(a + bt - l - z) : 0.f;
+  };
   // the blank: all even states, added in a fixed order
+  const float lblank = lp[p.Lmax];
   float gb = 0.f;
-  for (int s = 2 * tid; s < 2 * L + 1; s += 2 * kCtcRowThreads) gb += gamma[s];
+  for (int s = 2 * lane; s < 2 * L + 1; s += 128) gb += gamma(s, lblank);
   gb = wave_sum_f32(gb);
-  if ((tid & 63) == 0) red[tid >> 6] = gb;
-  __syncthreads();
-  if (tid == 0) {
-    float tot = 0.f;
-#pragma unroll
-    for (int w = 0; w < kCtcRowThreads / 64; ++w) tot += red[w];
-    row[p.blank] -= tot;
-  }
-  // the label's tokens: the thread of a token's first position adds the occupancies of all its positions
-  const int32_t* y = p.labels + (size_t)b * p.Lmax;
-  const int32_t* nx = p.next + (size_t)b * p.Lmax;
-  const int32_t* fs = p.first + (size_t)b * p.Lmax;
-  for (int j = tid; j < L; j += kCtcRowThreads) {
+  if (lane == 0) g[p.blank] -= gb;
+  // the label's tokens: the lane of a token's first position adds the occupancies of all its positions
+  const int32_t* __restrict__ y = p.labels + (size_t)b * p.Lmax;
+  const int32_t* __restrict__ nx = p.next + (size_t)b * p.Lmax;
+  const int32_t* __restrict__ fs = p.first + (size_t)b * p.Lmax;
+  for (int j = lane; j < L; j += 64) {
     if (!fs[j]) continue;
     float tot = 0.f;
-    for (int i = j; i >= 0; i = nx[i]) tot += gamma[2 * i + 1];
+    for (int i = j; i >= 0; i = nx[i]) tot += gamma(2 * i + 1, lp[i]);
     const int tok = clampi(y[j], 0, p.Vp1 - 1);
-    if (tok != p.blank) row[tok] -= tot;  // a label never holds the blank; ids come from the caller
+    if (tok != p.blank) g[tok] -= tot;  // a label never holds the blank; ids come from the caller
   }
-  __syncthreads();
-  for (int v = tid; v < p.Vp1; v += kCtcRowThreads) g[v] = row[v];
 }
 
 struct CtcWorkspace {
-  size_t lse, lpc, ag, coff, next, first, total;
+  size_t lse, lpc, ag, bg, coff_a, coff_b, logp, next, first, total;
 };
 static CtcWorkspace ctc_workspace(int B, int T, int Lmax) {
   CtcWorkspace w;
@@ -285,7 +384,10 @@ static CtcWorkspace ctc_workspace(int B, int T, int Lmax) {
   w.lse = carve((size_t)B * T * 4);
   w.lpc = carve((size_t)B * T * (Lmax + 1) * 4);
   w.ag = carve((size_t)B * T * (2 * (size_t)Lmax + 1) * 4);
-  w.coff = carve((size_t)B * T * 8);
+  w.bg = carve((size_t)B * T * (2 * (size_t)Lmax + 1) * 4);
+  w.coff_a = carve((size_t)B * T * 8);
+  w.coff_b = carve((size_t)B * T * 8);
+  w.logp = carve((size_t)B * 8);
   w.next = carve((size_t)B * Lmax * 4);
   w.first = carve((size_t)B * Lmax * 4);
   w.total = off;
@@ -309,10 +411,11 @@ extern "C" int ctc_loss(ctcspec_ctx* ctx, const float* logits, const int32_t* la
                   "ctc_loss: null pointer");
   CTCSPEC_REQUIRE(ctx, B > 0 && T > 0 && Vp1 > 0 && Lmax > 0, CTCSPEC_EINVAL, "ctc_loss: sizes must be positive");
   CTCSPEC_REQUIRE(ctx, blank_id >= 0 && blank_id < Vp1, CTCSPEC_EINVAL, "ctc_loss: blank_id out of range");
-  CTCSPEC_REQUIRE(ctx, Lmax <= kCtcMaxLabels && (long long)Vp1 * 4 <= 150 * 1024 && B <= 65535 && T <= 65535 * 32,
-                  CTCSPEC_EUNSUPPORTED, "ctc_loss: Lmax <= %d, (V+1) * 4 bytes <= 150 KB (a row goes through LDS), B <= 65535",
-                  kCtcMaxLabels);
-  CTCSPEC_REQUIRE(ctx, aligned16(workspace), CTCSPEC_EINVAL, "ctc_loss: workspace must be 16-byte aligned");
+  CTCSPEC_REQUIRE(ctx, Lmax <= kCtcMaxLabels && Vp1 <= kCtcMaxRow && B <= 65535 && T <= 65535 * 32,
+                  CTCSPEC_EUNSUPPORTED, "ctc_loss: Lmax <= %d, V+1 <= %d (a row is held in one workgroup's registers), B <= 65535",
+                  kCtcMaxLabels, kCtcMaxRow);
+  CTCSPEC_REQUIRE(ctx, aligned16(workspace) && aligned16(logits) && (!grad || aligned16(grad)), CTCSPEC_EINVAL,
+                  "ctc_loss: logits, grad and workspace must be 16-byte aligned");
   const CtcWorkspace w = ctc_workspace(B, T, Lmax);
   CTCSPEC_REQUIRE(ctx, workspace_bytes >= w.total, CTCSPEC_EINVAL, "ctc_loss: workspace of %zu bytes needed, %zu given",
                   w.total, workspace_bytes);
@@ -321,35 +424,38 @@ extern "C" int ctc_loss(ctcspec_ctx* ctx, const float* logits, const int32_t* la
   p.logits = logits; p.labels = labels; p.label_len = label_len; p.frame_len = frame_len;
   p.B = B; p.T = T; p.Vp1 = Vp1; p.Lmax = Lmax; p.blank = blank_id;
   p.lse = (float*)(ws + w.lse); p.lpc = (float*)(ws + w.lpc); p.ag = (float*)(ws + w.ag);
-  p.coff = (double*)(ws + w.coff);
+  p.bg = (float*)(ws + w.bg);
+  p.coff_a = (double*)(ws + w.coff_a); p.coff_b = (double*)(ws + w.coff_b); p.logp = (double*)(ws + w.logp);
   p.next = (int32_t*)(ws + w.next); p.first = (int32_t*)(ws + w.first);
   p.loss = loss; p.grad = grad;
   hipStream_t st = ctx->stream;
-  const int row_lds = Vp1 * 4;
-  static bool lds_allowed = false;  // raising the limit is needed once per process
-  if (!lds_allowed) {
-    CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)ctc_row_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
-    CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)ctc_grad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
-    lds_allowed = true;
-  }
-  hipLaunchKernelGGL(ctc_links_kernel, dim3(B), dim3(256), 0, st, p);
+  hipLaunchKernelGGL(ctc_links_kernel, dim3(B), dim3(Lmax > 256 ? 1024 : 256), Lmax * 4, st, p);
   CTCSPEC_HIP(ctx, hipGetLastError());
-  hipLaunchKernelGGL(ctc_row_kernel, dim3(T, B), dim3(kCtcRowThreads), row_lds, st, p);
+  const int nv = (Vp1 / 4 + kCtcRowThreads - 1) / kCtcRowThreads;  // 16-byte loads per thread
+  const dim3 rows(T, B), row_threads(kCtcRowThreads);
+  if (nv <= 1) hipLaunchKernelGGL(ctc_row_kernel<1>, rows, row_threads, 0, st, p);
+  else if (nv <= 2) hipLaunchKernelGGL(ctc_row_kernel<2>, rows, row_threads, 0, st, p);
+  else if (nv <= 4) hipLaunchKernelGGL(ctc_row_kernel<4>, rows, row_threads, 0, st, p);
+  else if (nv <= 8) hipLaunchKernelGGL(ctc_row_kernel<8>, rows, row_threads, 0, st, p);
+  else if (nv <= 16) hipLaunchKernelGGL(ctc_row_kernel<16>, rows, row_threads, 0, st, p);
+  else hipLaunchKernelGGL(ctc_row_kernel<32>, rows, row_threads, 0, st, p);
   CTCSPEC_HIP(ctx, hipGetLastError());
   const int S = 2 * Lmax + 1;
   int threads = (S + 63) / 64 * 64;
   threads = threads > 1024 ? 1024 : threads;
   const int ns = (S + threads - 1) / threads;
   const int dp_lds = 2 * (S + 4) * 4;
+  const dim3 dp_grid(B, grad ? 2 : 1);  // without a gradient only the forward recursion runs
   switch (ns) {
-    case 1: hipLaunchKernelGGL(ctc_dp_kernel<1>, dim3(B), dim3(threads), dp_lds, st, p); break;
-    case 2: hipLaunchKernelGGL(ctc_dp_kernel<2>, dim3(B), dim3(threads), dp_lds, st, p); break;
-    case 3: hipLaunchKernelGGL(ctc_dp_kernel<3>, dim3(B), dim3(threads), dp_lds, st, p); break;
-    default: hipLaunchKernelGGL(ctc_dp_kernel<4>, dim3(B), dim3(threads), dp_lds, st, p); break;
+    case 1: hipLaunchKernelGGL(ctc_dp_kernel<1>, dp_grid, dim3(threads), dp_lds, st, p); break;
+    case 2: hipLaunchKernelGGL(ctc_dp_kernel<2>, dp_grid, dim3(threads), dp_lds, st, p); break;
+    case 3: hipLaunchKernelGGL(ctc_dp_kernel<3>, dp_grid, dim3(threads), dp_lds, st, p); break;
+    default: hipLaunchKernelGGL(ctc_dp_kernel<4>, dp_grid, dim3(threads), dp_lds, st, p); break;
   }
   CTCSPEC_HIP(ctx, hipGetLastError());
   if (grad) {
-    hipLaunchKernelGGL(ctc_grad_kernel, dim3(T, B), dim3(kCtcRowThreads), row_lds, st, p);
+    const int per = kCtcFixThreads / 64;
+    hipLaunchKernelGGL(ctc_fix_kernel, dim3((T + per - 1) / per, B), dim3(kCtcFixThreads), 0, st, p);
     CTCSPEC_HIP(ctx, hipGetLastError());
   }
   return CTCSPEC_OK;

@@ -78,8 +78,15 @@ def test_ctc_loss_shapes(pkg, seed, B, T, C, Lmax, blank, kw):
 
 
 def test_ctc_loss_vocabulary_size_of_the_head(pkg):
-    """V+1 = 32001 rows through LDS, 8 frames per position as the draft head produces them."""
+    """V+1 = 32001 symbols (odd: the rows start at every alignment), 8 frames per position as the draft head
+    produces them."""
     _check(pkg, 7, 6, 8, 32001, 8, 32000)
+
+
+@pytest.mark.parametrize("C", [2, 3, 4, 5, 7, 2049, 4100, 65536])
+def test_ctc_loss_row_widths(pkg, C):
+    """Widths around the 16-byte boundaries and the steps in loads per thread, up to the largest supported."""
+    _check(pkg, 20 + C, 3, 5, C, 3, C - 1)
 
 
 def test_ctc_loss_many_states(pkg):
@@ -98,7 +105,12 @@ def test_ctc_loss_rejects_bad_arguments(pkg):
     with pytest.raises(pkg.CtcspecError, match="workspace"):
         pkg.ctc_loss(ctx, z, dev_i32(np.zeros((1, 2), dtype=np.int32)), one, one, 5,
                      workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
-    wide = dev_f32(np.zeros((1, 1, 40000), dtype=np.float32))
-    with pytest.raises(pkg.CtcspecError, match="LDS"):
+    wide = dev_f32(np.zeros((1, 1, 70000), dtype=np.float32))
+    with pytest.raises(pkg.CtcspecError, match="registers"):
         pkg.ctc_loss(ctx, wide, dev_i32(np.zeros((1, 2), dtype=np.int32)), one, one, 5)
     ctx.close()
+
+
+def test_ctc_loss_largest_label_capacity(pkg):
+    """Lmax = 2047: four states per thread, the shorter ring of loads ahead."""
+    _check(pkg, 9, 2, 600, 33, 2047, 32, scale=0.5)
