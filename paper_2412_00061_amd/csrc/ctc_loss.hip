@@ -20,8 +20,8 @@
 namespace ctcspec {
 
 constexpr int kCtcMaxLabels = 2047;  // 2L + 1 states <= 4 per thread of a 1024-thread workgroup
-constexpr int kCtcRowThreads = 512;
-constexpr int kCtcMaxRow = 32 * kCtcRowThreads * 4;  // 65536 symbols: 32 16-byte loads per thread
+constexpr int kCtcRowThreads = 1024;
+constexpr int kCtcMaxRow = 16 * kCtcRowThreads * 4;  // 65536 symbols: 16 16-byte loads per thread
 constexpr int kCtcFixThreads = 256;
 constexpr int kCtcAhead = 8;  // frames between a load and its use in the recursions
 
@@ -104,9 +104,9 @@ __global__ __launch_bounds__(1024) void ctc_links_kernel(CtcParams p) {
 // and the row's softmax written as the gradient.  Rows start at any multiple of 4 bytes (V + 1 is odd at
 // V = 32000), so the up to three elements in front of the first 16-byte boundary and behind the last go through
 // single lanes and the body through 16-byte loads and stores.
-template <int NV>  // 16-byte loads per thread: NV * kCtcRowThreads * 4 >= V + 1
-__global__ __launch_bounds__(kCtcRowThreads) void ctc_row_kernel(CtcParams p) {
-  __shared__ float red[kCtcRowThreads / 64];
+template <int NV, int THREADS>  // 16-byte loads per thread: NV * THREADS * 4 >= V + 1
+__global__ __launch_bounds__(THREADS) void ctc_row_kernel(CtcParams p) {
+  __shared__ float red[THREADS / 64];
   const int t = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int Tb = clampi(p.frame_len[b], 0, p.T);
   const size_t row0 = ((size_t)b * p.T + t) * p.Vp1;
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(kCtcRowThreads) void ctc_row_kernel(CtcParams p) {
   if (t >= Tb) {  // frames past the sequence: no gradient
     if (g) {
       f32x4* gv = (f32x4*)(g + head);
-      for (int i = tid; i < nvec; i += kCtcRowThreads) gv[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int i = tid; i < nvec; i += THREADS) gv[i] = f32x4{0.f, 0.f, 0.f, 0.f};
       if (edge >= 0) g[edge] = 0.f;
     }
     return;
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kCtcRowThreads) void ctc_row_kernel(CtcParams p) {
   f32x4 x[NV];
 #pragma unroll
   for (int k = 0; k < NV; ++k) {
-    const int i = tid + k * kCtcRowThreads;
+    const int i = tid + k * THREADS;
     x[k] = i < nvec ? zv[i] : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
   }
   float xe = edge >= 0 ? z[edge] : -INFINITY;
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(kCtcRowThreads) void ctc_row_kernel(CtcParams p) {
   __syncthreads();
   mx = red[0];
 #pragma unroll
-  for (int w = 1; w < kCtcRowThreads / 64; ++w) mx = fmaxf(mx, red[w]);
+  for (int w = 1; w < THREADS / 64; ++w) mx = fmaxf(mx, red[w]);
   // e = exp(x - max) stays in the registers: the softmax is e / sum
   xe = expf(xe - mx);
   float sum = xe;
@@ -162,19 +162,19 @@ __global__ __launch_bounds__(kCtcRowThreads) void ctc_row_kernel(CtcParams p) {
   __syncthreads();
   sum = 0.f;
 #pragma unroll
-  for (int w = 0; w < kCtcRowThreads / 64; ++w) sum += red[w];
+  for (int w = 0; w < THREADS / 64; ++w) sum += red[w];
   const float lse = mx + logf(sum);
   if (tid == 0) p.lse[(size_t)b * p.T + t] = lse;
   const int L = clampi(p.label_len[b], 0, p.Lmax);
   float* out = p.lpc + ((size_t)b * p.T + t) * (p.Lmax + 1);
-  for (int j = tid; j < L; j += kCtcRowThreads) out[j] = z[clampi(p.labels[(size_t)b * p.Lmax + j], 0, p.Vp1 - 1)] - lse;
+  for (int j = tid; j < L; j += THREADS) out[j] = z[clampi(p.labels[(size_t)b * p.Lmax + j], 0, p.Vp1 - 1)] - lse;
   if (tid == 0) out[p.Lmax] = z[p.blank] - lse;
   if (g) {
     const float inv = 1.f / sum;
     f32x4* gv = (f32x4*)(g + head);
 #pragma unroll
     for (int k = 0; k < NV; ++k) {
-      const int i = tid + k * kCtcRowThreads;
+      const int i = tid + k * THREADS;
       if (i < nvec) gv[i] = x[k] * inv;
     }
     if (edge >= 0) g[edge] = xe * inv;
@@ -355,22 +355,36 @@ __global__ __launch_bounds__(kCtcFixThreads) void ctc_fix_kernel(CtcParams p) {
     const float a = al[s], bt = be[s];
     return (a > -INFINITY && bt > -INFINITY) ? expf(a + bt - l - z) : 0.f;
   };
-  // the blank: all even states, added in a fixed order
+  // The occupancies of a frame sum to one (every alignment is in exactly one state at frame t).  What is left
+  // of the recursions' rounding after thousands of frames is mostly common to all states of a frame - it sits in
+  // z - so dividing by the computed sum removes it.  First pass: the sums, in a fixed order.
   const float lblank = lp[p.Lmax];
-  float gb = 0.f;
+  float gb = 0.f, go = 0.f;
+#pragma unroll 4
   for (int s = 2 * lane; s < 2 * L + 1; s += 128) gb += gamma(s, lblank);
+#pragma unroll 4
+  for (int j = lane; j < L; j += 64) go += gamma(2 * j + 1, lp[j]);
   gb = wave_sum_f32(gb);
-  if (lane == 0) g[p.blank] -= gb;
-  // the label's tokens: the lane of a token's first position adds the occupancies of all its positions
+  go = wave_sum_f32(go);
+  const float total = gb + go;
+  const float inv = total > 0.f ? 1.f / total : 1.f;
+  // the blank: all even states
+  if (lane == 0) g[p.blank] -= gb * inv;
+  // the label's tokens: the lane of a token's first position adds the occupancies of all its positions (nearly
+  // always just the one, so every lane forms its own position's occupancy first and the loads of several
+  // positions are in flight together)
   const int32_t* __restrict__ y = p.labels + (size_t)b * p.Lmax;
   const int32_t* __restrict__ nx = p.next + (size_t)b * p.Lmax;
   const int32_t* __restrict__ fs = p.first + (size_t)b * p.Lmax;
+#pragma unroll 4
   for (int j = lane; j < L; j += 64) {
-    if (!fs[j]) continue;
-    float tot = 0.f;
-    for (int i = j; i >= 0; i = nx[i]) tot += gamma(2 * i + 1, lp[i]);
+    const int is_first = fs[j];
     const int tok = clampi(y[j], 0, p.Vp1 - 1);
-    if (tok != p.blank) g[tok] -= tot;  // a label never holds the blank; ids come from the caller
+    float tot = gamma(2 * j + 1, lp[j]);
+    if (is_first) {
+      for (int i = nx[j]; i >= 0; i = nx[i]) tot += gamma(2 * i + 1, lp[i]);
+      if (tok != p.blank) g[tok] -= tot * inv;  // a label never holds the blank; ids come from the caller
+    }
   }
 }
 
@@ -433,12 +447,11 @@ extern "C" int ctc_loss(ctcspec_ctx* ctx, const float* logits, const int32_t* la
   CTCSPEC_HIP(ctx, hipGetLastError());
   const int nv = (Vp1 / 4 + kCtcRowThreads - 1) / kCtcRowThreads;  // 16-byte loads per thread
   const dim3 rows(T, B), row_threads(kCtcRowThreads);
-  if (nv <= 1) hipLaunchKernelGGL(ctc_row_kernel<1>, rows, row_threads, 0, st, p);
-  else if (nv <= 2) hipLaunchKernelGGL(ctc_row_kernel<2>, rows, row_threads, 0, st, p);
-  else if (nv <= 4) hipLaunchKernelGGL(ctc_row_kernel<4>, rows, row_threads, 0, st, p);
-  else if (nv <= 8) hipLaunchKernelGGL(ctc_row_kernel<8>, rows, row_threads, 0, st, p);
-  else if (nv <= 16) hipLaunchKernelGGL(ctc_row_kernel<16>, rows, row_threads, 0, st, p);
-  else hipLaunchKernelGGL(ctc_row_kernel<32>, rows, row_threads, 0, st, p);
+  if (nv <= 1) hipLaunchKernelGGL((ctc_row_kernel<1, kCtcRowThreads>), rows, row_threads, 0, st, p);
+  else if (nv <= 2) hipLaunchKernelGGL((ctc_row_kernel<2, kCtcRowThreads>), rows, row_threads, 0, st, p);
+  else if (nv <= 4) hipLaunchKernelGGL((ctc_row_kernel<4, kCtcRowThreads>), rows, row_threads, 0, st, p);
+  else if (nv <= 8) hipLaunchKernelGGL((ctc_row_kernel<8, kCtcRowThreads>), rows, row_threads, 0, st, p);
+  else hipLaunchKernelGGL((ctc_row_kernel<16, kCtcRowThreads>), rows, row_threads, 0, st, p);
   CTCSPEC_HIP(ctx, hipGetLastError());
   const int S = 2 * Lmax + 1;
   int threads = (S + 63) / 64 * 64;

@@ -1,10 +1,11 @@
 """GPU parity of ctc_loss (Sec. 3.2: negative log of Eq. 5 and its gradient) against the oracle.
 
-fp32 logits in, the recursions in fp32 log space: a log-probability after t frames has magnitude about t times
-the per-frame entropy, and every frame adds a rounding of its ulp, so the loss is held to a relative 1e-5 + 2e-7
-per frame and the gradient (entries in [-1, 1]) to 2e-3 relative with an RMS floor, the bar of the other float
-outputs.  Rows of the gradient must sum to zero, frames past frame_len and unreachable labels give zeros, and a
-second call reproduces every bit.
+fp32 logits in.  The recursions run in fp32 log space with every frame's values held relative to the frame's
+largest (offsets summed in double), and the occupancies of a frame are divided by their computed sum, so the error
+does not grow with the number of frames: measured, the loss agrees to the last float digit or two and the gradient
+to about 1e-5 of max(|entry|, rms) from 8 to 1300 frames.  The bars: loss 2e-6 relative (a few float ulps),
+gradient 1e-4.  Rows of the gradient must sum to zero (1e-5), frames past frame_len and unreachable labels give
+zeros, and a second call reproduces every bit.
 """
 import math
 
@@ -58,9 +59,9 @@ def _check(pkg, seed, B, T, C, Lmax, blank, **kw):
         if math.isinf(ref_loss):
             assert math.isinf(loss[b]) and not grad[b].any()
             continue
-        assert abs(loss[b] - ref_loss) <= (1e-5 + 2e-7 * Tb) * max(1.0, abs(ref_loss)), (b, loss[b], ref_loss)
-        assert rel_err_rms_floor(grad[b, :Tb], ref_grad) <= 2e-3, (b, rel_err_rms_floor(grad[b, :Tb], ref_grad))
-        assert np.max(np.abs(grad[b, :Tb].sum(-1))) <= 2e-3, np.max(np.abs(grad[b, :Tb].sum(-1)))
+        assert abs(loss[b] - ref_loss) <= 2e-6 * max(1.0, abs(ref_loss)), (b, loss[b], ref_loss)
+        assert rel_err_rms_floor(grad[b, :Tb], ref_grad) <= 1e-4, (b, rel_err_rms_floor(grad[b, :Tb], ref_grad))
+        assert np.max(np.abs(grad[b, :Tb].astype(np.float64).sum(-1))) <= 1e-5
         assert not grad[b, Tb:].any()
     ctx.close()
 
