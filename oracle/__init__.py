@@ -24,3 +24,11 @@ from .verify import verifier_head_argmax, argmax_rows, kv_commit  # noqa: F401
 from .draft_layer import draft_layer, draft_layer_qkv, draft_layer_attend, rms_norm, rope, silu  # noqa: F401
 from .sum_score import ctc_sequence_logprob, sum_scores, ranks_desc  # noqa: F401
 from .ctc_loss import ctc_alpha_beta, ctc_loss_and_grad  # noqa: F401
+from .sampling import (  # noqa: F401
+    target_probs,
+    sample_token,
+    sample_nodes,
+    accept_sampled,
+    sec2_rule_distribution,
+    sample_and_match_distribution,
+)
