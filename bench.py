@@ -51,6 +51,7 @@ def parse_args():
     ap.add_argument("--no-sum-score", action="store_true")
     ap.add_argument("--no-literal-layout", action="store_true")
     ap.add_argument("--no-ctc-loss", action="store_true")
+    ap.add_argument("--no-sampled-acceptance", action="store_true")
     ap.add_argument("--ctc-loss-positions", type=int, default=4096,
                     help="training positions of the ctc_loss line, each with T frames over V+1 symbols")
     ap.add_argument("--draft-layer-ffn", type=int, default=0,
@@ -356,6 +357,41 @@ def main():
                   "verify_head_argmax_us_median": vh_us, "verify_head_algorithmic_bytes": vh_bytes,
                   "verify_head_hbm_gbps": vh_bytes / (vh_us * 1e-6) / 1e9,
                   "verified_tokens_per_sec": int(n_nodes.sum()) / (cs_us * 1e-6)}
+
+        # sampling-based acceptance on the same step: the head also writes its logits, one uniform number per node
+        # draws the target's token from them, and the walk follows the drawn tokens
+        if not args.no_sampled_acceptance:
+            vh_logits = torch.empty((B, N, cfg.V), dtype=torch.float32, device="cuda")
+            drawn = i32(B, N)
+            uni = torch.rand((B, N), generator=g, device="cuda", dtype=torch.float32)
+            head_z = lib.prepared(ctx, "verify_head_argmax", dt, node_hidden, w_base[0], n_nodes_d, B, N, cfg.D, cfg.V,
+                                  vh_targets, vh_logits)
+            draw = lib.prepared(ctx, "verify_sample_tokens", vh_logits, n_nodes_d, uni, 1.0, B, N, cfg.V, drawn)
+            walk = lib.prepared(ctx, "accept_longest", n_nodes_d, node_token, node_parent, node_depth, drawn,
+                                B, T, N, accept_len, accept_nodes, accept_tokens, next_token)
+            for _ in range(5):
+                head_z(); draw(); walk()
+            torch.cuda.synchronize()
+            n_sa = 48
+            sa_ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * n_sa)]
+            for i in range(n_sa):
+                sa_ev[3 * i].record()
+                head_z()
+                sa_ev[3 * i + 1].record()
+                draw()
+                sa_ev[3 * i + 2].record()
+                walk()
+            torch.cuda.synchronize()
+            hz_us = float(np.median([sa_ev[3 * i].elapsed_time(sa_ev[3 * i + 1]) * 1e3 for i in range(n_sa)]))
+            dr_us = float(np.median([sa_ev[3 * i + 1].elapsed_time(sa_ev[3 * i + 2]) * 1e3 for i in range(n_sa)]))
+            dr_bytes = int(n_nodes.sum()) * cfg.V * 4
+            closed["sampled_acceptance"] = {
+                "calls": "verify_head_argmax (logits written), verify_sample_tokens, accept_longest",
+                "verify_head_with_logits_us_median": hz_us, "verify_sample_tokens_us_median": dr_us,
+                "verify_sample_algorithmic_bytes": dr_bytes, "verify_sample_gbps": dr_bytes / (dr_us * 1e-6) / 1e9,
+                "extra_us_over_greedy": hz_us - vh_us + dr_us,
+                "accepted_plus_bonus": (accept_len.cpu().numpy() + 1).tolist()}
+            del vh_logits
 
     # draft-module variant: the transformer layer that produces the T slot states (its own weights and
     # cache, the base family's shape), then the step.  Weight copies rotate so that no pass finds its matrix in

@@ -338,6 +338,33 @@ int ctc_raw_tree(ctcspec_ctx* ctx, const int32_t* topk_id, const float* topk_log
                  int32_t* node_parent, int32_t* node_depth, uint64_t* anc_mask, int32_t* node_removed);
 
 /*
+ * verify_sample_tokens - sampling-based acceptance (Sec. 2.1: a drafted token is accepted with probability
+ * min(1, P/P') and a rejected one re-drawn from norm(max(0, P - P')); Sec. 3.3: the longest sequence that satisfies
+ * the criterion is the step's output).  The tree is built deterministically, so the draft distribution behind a
+ * node's token is a point mass; the rule then emits tokens with the target model's own distribution, which one
+ * uniform number per node realises: draw the target's token after the node; accept_longest, given these tokens in
+ * place of the greedy ones, walks to the child that carries the drawn token and stops where none does.
+ * For sequence b and node i < n_nodes[b]:
+ *
+ *   p[v] = softmax_v(logits[b,i,:] / temperature)
+ *   target_sampled[b,i] = the first v, in vocabulary order, with p[0] + ... + p[v] > uniforms[b,i]
+ *
+ * (the last v with p[v] > 0 when rounding leaves no such v).  Sums are fp32 in a fixed order: the token is the exact
+ * one unless uniforms[b,i] lies within rounding (about 1e-6) of a boundary of the cumulative distribution, where
+ * it may be the neighbour.  Rows i >= n_nodes[b] receive -1.
+ *
+ * logits         [B,max_nodes,V] float device in, 16-byte aligned: the target model's logits after every node (the
+ *                logits_out of verify_head_argmax)
+ * n_nodes        [B] int32 device in
+ * uniforms       [B,max_nodes] float device in: independent uniform numbers in [0, 1), drawn by the caller
+ * temperature    > 0, finite
+ * target_sampled [B,max_nodes] int32 device out
+ * Limits: V <= 65533, B <= 65535.  The same bits on every run.
+ */
+int verify_sample_tokens(ctcspec_ctx* ctx, const float* logits, const int32_t* n_nodes, const float* uniforms,
+                         float temperature, int B, int max_nodes, int V, int32_t* target_sampled);
+
+/*
  * ctc_loss - the training objective of Sec. 3.2: for every sequence b the loss -log P(Y_b | X_b), P by Eq. 5 with
  * Eq. 6 (the sum, over all frame-level sequences that the collapse rule turns into the label, of the product of
  * the per-frame softmax probabilities), and optionally its gradient with respect to the logits - computed with

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     ctc_collapse_tree,
     ctc_draft_topk,
     ctc_loss,
+    verify_sample_tokens,
     ctc_loss_workspace_bytes,
     ctc_raw_tree,
     ctc_sum_score,

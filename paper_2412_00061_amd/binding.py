@@ -16,7 +16,7 @@ EXPORTS = (
     "ctcspec_create", "ctcspec_destroy", "ctcspec_set_stream", "ctcspec_last_error",
     "ctcspec_workspace_bytes", "ctcspec_profile_draft_head", "ctcspec_draft_head_kernel_ms", "ctc_draft_topk", "ctc_collapse_tree", "tree_verify_attn",
     "accept_longest", "verify_head_argmax", "kv_commit", "draft_layer_workspace_bytes", "draft_layer_forward",
-    "ctc_sum_score", "ctc_raw_tree", "ctc_loss_workspace_bytes", "ctc_loss",
+    "ctc_sum_score", "ctc_raw_tree", "ctc_loss_workspace_bytes", "ctc_loss", "verify_sample_tokens",
 )
 
 CTCSPEC_F32, CTCSPEC_BF16 = 0, 1
@@ -89,6 +89,8 @@ def load_library():
                                         [c_int] * 6 + [c_float, c_float, c_void_p, c_size_t] + [c_void_p] * 5)
     lib.ctc_loss_workspace_bytes.restype = c_size_t
     lib.ctc_loss_workspace_bytes.argtypes = [c_int] * 3
+    lib.verify_sample_tokens.restype = c_int
+    lib.verify_sample_tokens.argtypes = [c_void_p] * 4 + [c_float] + [c_int] * 3 + [c_void_p]
     lib.ctc_loss.restype = c_int
     lib.ctc_loss.argtypes = [c_void_p] * 5 + [c_int] * 4 + [c_int32, c_void_p, c_size_t, c_void_p, c_void_p]
     lib.ctc_raw_tree.restype = c_int
@@ -415,4 +417,14 @@ def ctc_loss(ctx, logits, labels, label_len, frame_len, blank_id, *, want_grad=T
                           _ptr(label_len, torch.int32), _ptr(frame_len, torch.int32), B, T, Vp1, Lmax, blank_id,
                           _ptr(workspace, torch.uint8), workspace.numel(), _ptr(res["loss"]), _ptr(res.get("grad")))
     ctx._check(rc, "ctc_loss")
+    return res
+
+
+def verify_sample_tokens(ctx, logits, n_nodes, uniforms, temperature, *, out=None):
+    """logits [B,N,V] f32, uniforms [B,N] f32 in [0,1) -> target_sampled [B,N] i32."""
+    B, N, V = logits.shape
+    res = _out(out, "target_sampled", (B, N), torch.int32, logits.device)
+    rc = ctx.lib.verify_sample_tokens(ctx.handle, _ptr(logits, torch.float32), _ptr(n_nodes, torch.int32),
+                                      _ptr(uniforms, torch.float32), float(temperature), B, N, V, _ptr(res))
+    ctx._check(rc, "verify_sample_tokens")
     return res

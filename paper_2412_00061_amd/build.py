@@ -11,7 +11,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["context.hip", "draft_topk.hip", "collapse_tree.hip", "tree_attn.hip", "accept.hip", "verify_head.hip", "draft_layer.hip", "sum_score.hip", "ctc_loss.hip"]
+SOURCES = ["context.hip", "draft_topk.hip", "collapse_tree.hip", "tree_attn.hip", "accept.hip", "verify_head.hip", "draft_layer.hip", "sum_score.hip", "ctc_loss.hip", "verify_sample.hip"]
 LIB = os.path.join(HERE, "libctcspec.so")
 
 HIPCC_FLAGS = [
