@@ -348,3 +348,71 @@ def test_whole_decode_step_graph_replay(pkg):
         assert math.isfinite(float(junk))
     ctx.set_stream(torch.cuda.current_stream())
     ctx.close()
+
+
+def test_loss_and_sampled_draw_graph_replay(pkg):
+    """ctc_loss (with its gradient) and the sampled draw followed by the acceptance walk, captured in one HIP graph:
+    replays, with eager work and synchronisation between them, reproduce the eager results bit for bit."""
+    rng = np.random.Generator(np.random.PCG64(31))
+    B, T, C, Lmax = 3, 12, 301, 6
+    logits = dev_f32(rng.standard_normal((B, T, C), dtype=np.float32) * 2)
+    labels = dev_i32(rng.integers(0, C - 1, size=(B, Lmax)).astype(np.int32))
+    label_len = dev_i32(np.array([6, 0, 3], dtype=np.int32))
+    frame_len = dev_i32(np.array([12, 5, 9], dtype=np.int32))
+    N, V = 6, 301
+    node_token = dev_i32(np.array([[9, 4, 5, 6, 7, 8]], dtype=np.int32))
+    node_parent = dev_i32(np.array([[-1, 0, 0, 1, 1, 3]], dtype=np.int32))
+    node_depth = dev_i32(np.array([[0, 1, 1, 2, 2, 3]], dtype=np.int32))
+    n_nodes = dev_i32(np.array([N], dtype=np.int32))
+    z = rng.standard_normal((1, N, V), dtype=np.float32)
+    z[0, 0, 4] += 9.0
+    z[0, 1, 6] += 9.0
+    uniforms = dev_f32(rng.random((1, N), dtype=np.float32))
+    z = dev_f32(z)
+    ctx = pkg.Context(max_batch=B, max_slots=8, max_topk=4, max_vocab_rows=C, max_nodes=8, max_heads=1, max_head_dim=8)
+    ws = torch.empty(pkg.ctc_loss_workspace_bytes(B, T, Lmax), dtype=torch.uint8, device="cuda")
+    o = dict(loss=torch.full((B,), float("nan"), device="cuda"), grad=torch.full((B, T, C), float("nan"), device="cuda"),
+             drawn=torch.full((1, N), -7, dtype=torch.int32, device="cuda"),
+             accept_len=torch.full((1,), -7, dtype=torch.int32, device="cuda"),
+             accept_nodes=torch.full((1, 5), -7, dtype=torch.int32, device="cuda"),
+             accept_tokens=torch.full((1, 5), -7, dtype=torch.int32, device="cuda"),
+             next_token=torch.full((1,), -7, dtype=torch.int32, device="cuda"))
+    P = pkg.prepared
+    calls = (
+        P(ctx, "ctc_loss", logits, labels, label_len, frame_len, B, T, C, Lmax, C - 1, ws, ws.numel(), o["loss"], o["grad"]),
+        P(ctx, "verify_sample_tokens", z, n_nodes, uniforms, 0.9, 1, N, V, o["drawn"]),
+        P(ctx, "accept_longest", n_nodes, node_token, node_parent, node_depth, o["drawn"], 1, 4, N, o["accept_len"],
+          o["accept_nodes"], o["accept_tokens"], o["next_token"]),
+    )
+
+    def run():
+        for call in calls:
+            call()
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return {name: t.cpu().numpy().copy() for name, t in o.items()}
+
+    run()
+    eager = snapshot()
+    assert np.isfinite(eager["loss"]).all() and int(eager["accept_len"][0]) >= 1
+    stream = torch.cuda.Stream()
+    ctx.set_stream(stream)
+    with torch.cuda.stream(stream):
+        run()
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            run()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in o.values():
+            t.fill_(float("nan") if t.dtype == torch.float32 else -7)
+        torch.cuda.synchronize()
+        graph.replay()
+        _same(eager, snapshot())
+        junk = torch.randn(1 << 16, device="cuda").sum()
+        torch.cuda.synchronize()
+        assert math.isfinite(float(junk))
+    ctx.set_stream(torch.cuda.current_stream())
+    ctx.close()
