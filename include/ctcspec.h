@@ -372,7 +372,9 @@ int verify_sample_tokens(ctcspec_ctx* ctx, const float* logits, const int32_t* n
  * is part of the differentiated function.
  *
  * logits     [B,T,Vp1] float device in: the draft module's outputs for T frames per sequence
- * labels     [B,Lmax] int32 device in: label tokens (no blanks), padded; label_len [B] int32 device in
+ * labels     [B,Lmax] int32 device in: label tokens in [0, Vp1) other than blank_id, padded; label_len [B] int32
+ *            device in.  Ids outside the range are clamped into it and a blank among the labels gets no
+ *            gradient of its own: the values are then unspecified, nothing is read or written out of bounds
  * frame_len  [B] int32 device in: frames of sequence b that count (<= T)
  * workspace  device scratch of at least ctc_loss_workspace_bytes(B, T, Lmax) bytes, owned by the caller, contents
  *            undefined afterwards; calls that share it must not overlap
