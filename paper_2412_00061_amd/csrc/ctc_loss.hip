@@ -32,7 +32,6 @@ struct CtcParams {
   const int32_t* frame_len; // [B]
   int B, T, Vp1, Lmax, blank;
   // workspace
-  float* lse;     // [B][T]
   float* lpc;     // [B][T][Lmax + 1]: log p_t(y_j) for j < L, log p_t(blank) at Lmax
   float* ag;      // [B][T][2 Lmax + 1]: log alpha minus the frame's offset
   float* bg;      // [B][T][2 Lmax + 1]: log beta minus the frame's offset
@@ -164,7 +163,6 @@ __global__ __launch_bounds__(THREADS) void ctc_row_kernel(CtcParams p) {
 #pragma unroll
   for (int w = 0; w < THREADS / 64; ++w) sum += red[w];
   const float lse = mx + logf(sum);
-  if (tid == 0) p.lse[(size_t)b * p.T + t] = lse;
   const int L = clampi(p.label_len[b], 0, p.Lmax);
   float* out = p.lpc + ((size_t)b * p.T + t) * (p.Lmax + 1);
   for (int j = tid; j < L; j += THREADS) out[j] = z[clampi(p.labels[(size_t)b * p.Lmax + j], 0, p.Vp1 - 1)] - lse;
@@ -389,13 +387,12 @@ __global__ __launch_bounds__(kCtcFixThreads) void ctc_fix_kernel(CtcParams p) {
 }
 
 struct CtcWorkspace {
-  size_t lse, lpc, ag, bg, coff_a, coff_b, logp, next, first, total;
+  size_t lpc, ag, bg, coff_a, coff_b, logp, next, first, total;
 };
 static CtcWorkspace ctc_workspace(int B, int T, int Lmax) {
   CtcWorkspace w;
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t at = off; off = (off + bytes + 255) / 256 * 256; return at; };
-  w.lse = carve((size_t)B * T * 4);
   w.lpc = carve((size_t)B * T * (Lmax + 1) * 4);
   w.ag = carve((size_t)B * T * (2 * (size_t)Lmax + 1) * 4);
   w.bg = carve((size_t)B * T * (2 * (size_t)Lmax + 1) * 4);
@@ -437,7 +434,7 @@ extern "C" int ctc_loss(ctcspec_ctx* ctx, const float* logits, const int32_t* la
   CtcParams p;
   p.logits = logits; p.labels = labels; p.label_len = label_len; p.frame_len = frame_len;
   p.B = B; p.T = T; p.Vp1 = Vp1; p.Lmax = Lmax; p.blank = blank_id;
-  p.lse = (float*)(ws + w.lse); p.lpc = (float*)(ws + w.lpc); p.ag = (float*)(ws + w.ag);
+  p.lpc = (float*)(ws + w.lpc); p.ag = (float*)(ws + w.ag);
   p.bg = (float*)(ws + w.bg);
   p.coff_a = (double*)(ws + w.coff_a); p.coff_b = (double*)(ws + w.coff_b); p.logp = (double*)(ws + w.logp);
   p.next = (int32_t*)(ws + w.next); p.first = (int32_t*)(ws + w.first);
