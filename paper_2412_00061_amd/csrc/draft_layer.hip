@@ -9,11 +9,12 @@
 //     same number of bytes whatever the matrix shape (12288, 4096 or 22016 rows; 4096 or 11008 columns);
 //   * a wavefront streams its range through registers (STAGES - 1 units ahead) and a private LDS strip into
 //     MFMA A fragments, as the draft head does; the activations (B operand) sit in LDS per workgroup.  A range
-//     is at most as long as a row tile's units, so it touches at most two row tiles: two accumulators, the
-//     A fragment zeroed for the one that a unit does not belong to - no branch, no flush inside the stream;
-//   * matrices whose activations do not fit in LDS (the down projection) are split along k into groups of
-//     workgroups, each with its slice of the activations;
-//   * every wavefront leaves two 16 x 16 partial tiles; the kernel that follows (rotary embedding, residual +
+//     is at most twice as long as a row tile's units, so it touches at most three row tiles: three
+//     accumulators, the A fragment zeroed for those that a unit does not belong to - no branch, no flush inside
+//     the stream;
+//   * matrices whose activation slice does not fit in LDS are split along k into groups of workgroups, each
+//     with its slice of the activations;
+//   * every wavefront leaves three 16 x 16 partial tiles; the kernel that follows (rotary embedding, residual +
 //     norm, gate, residual) adds the partial tiles of a row tile in a fixed order - same bits on every run.
 #include <type_traits>
 #include <utility>
