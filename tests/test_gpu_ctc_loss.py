@@ -115,3 +115,38 @@ def test_ctc_loss_rejects_bad_arguments(pkg):
 def test_ctc_loss_largest_label_capacity(pkg):
     """Lmax = 2047: four states per thread, the shorter ring of loads ahead."""
     _check(pkg, 9, 2, 600, 33, 2047, 32, scale=0.5)
+
+
+@pytest.mark.parametrize("B,T,Lmax,picks", [(4096, 8, 8, 8), (4, 2048, 1024, 1)])
+def test_ctc_loss_at_the_benchmark_shapes(pkg, B, T, Lmax, picks):
+    """The two shapes bench.py times (V+1 = 32001), logits drawn on the device: sampled sequences against the oracle,
+    and for all of them finite losses and gradient rows that sum to zero."""
+    C, blank = 32001, 32000
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    z = torch.randn((B, T, C), dtype=torch.float32, device="cuda", generator=gen) * 2.0
+    labels = torch.randint(0, C - 1, (B, Lmax), dtype=torch.int32, device="cuda", generator=gen)
+    label_len = torch.randint(1, Lmax + 1, (B,), dtype=torch.int32, device="cuda", generator=gen)
+    frame_len = torch.full((B,), T, dtype=torch.int32, device="cuda")
+    ctx = pkg.Context(max_batch=1, max_slots=8, max_topk=4, max_vocab_rows=C, max_nodes=8, max_heads=1, max_head_dim=8)
+    print(f"ctc_loss bench shape B={B} T={T} Lmax={Lmax}", flush=True)
+    res = pkg.ctc_loss(ctx, z, labels, label_len, frame_len, blank)
+    torch.cuda.synchronize()
+    # a label with a repeated token needs a blank in between and may not fit T frames: those are +inf with zero rows
+    finite = torch.isfinite(res["loss"])
+    assert int(finite.sum()) >= B * 3 // 4
+    sums = res["grad"].sum(-1).abs().amax(-1)
+    assert float(sums.max()) <= 2e-5
+    assert not bool(res["grad"][~finite].any())
+    step = max(1, B // picks)
+    for b in range(0, B, step)[:picks]:
+        L = int(label_len[b])
+        ref_loss, ref_grad = oracle.ctc_loss_and_grad(z[b].cpu().numpy(), tuple(int(v) for v in labels[b, :L].cpu().numpy()), blank)
+        got_loss, got_grad = float(res["loss"][b]), res["grad"][b].cpu().numpy()
+        if math.isinf(ref_loss):
+            assert math.isinf(got_loss) and not got_grad.any()
+            continue
+        assert abs(got_loss - ref_loss) <= 2e-6 * max(1.0, abs(ref_loss)), (b, got_loss, ref_loss)
+        assert rel_err_rms_floor(got_grad, ref_grad) <= 1e-4, (b, rel_err_rms_floor(got_grad, ref_grad))
+    del z, res
+    torch.cuda.empty_cache()
+    ctx.close()
