@@ -19,7 +19,9 @@
 
 namespace ctcspec {
 
-constexpr int kCtcMaxLabels = 2047;  // 2L + 1 states <= 4 per thread of a 1024-thread workgroup
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+constexpr int kCtcMaxLabels = 2047;  // L + 1 pairs of states <= 2 per thread of a 1024-thread workgroup
 constexpr int kCtcRowThreads = 1024;
 constexpr int kCtcMaxRow = 16 * kCtcRowThreads * 4;  // 65536 symbols: 16 16-byte loads per thread
 constexpr int kCtcFixThreads = 256;
@@ -33,8 +35,8 @@ struct CtcParams {
   int B, T, Vp1, Lmax, blank;
   // workspace
   float* lpc;     // [B][T][Lmax + 1]: log p_t(y_j) for j < L, log p_t(blank) at Lmax
-  float* ag;      // [B][T][2 Lmax + 1]: log alpha minus the frame's offset
-  float* bg;      // [B][T][2 Lmax + 1]: log beta minus the frame's offset
+  float* ag;      // [B][T][2 Lmax + 2]: log alpha minus the frame's offset (state s at s; the last entry unused)
+  float* bg;      // [B][T][2 Lmax + 2]: log beta minus the frame's offset
   double* coff_a; // [B][T]: offset of the frame's log alpha values
   double* coff_b; // [B][T]: offset of the frame's log beta values
   double* logp;   // [B]: log P(Y | X)
@@ -56,16 +58,13 @@ __device__ __forceinline__ float ctc_log_add3(float a, float b, float c) {
                     __builtin_amdgcn_exp2f((c - ms) * kLog2e);
   return ms + kLn2 * __builtin_amdgcn_logf(sum);  // the bare log2 instruction; sum = 0 gives -inf
 }
-// largest of the wavefronts' maxima of one frame (slots of absent wavefronts hold -inf); 0 when every state is
-// impossible, so that offsets stay finite
-__device__ __forceinline__ float frame_max(const float* w) {
-  const f32x4* v = (const f32x4*)w;
-  const f32x4 a = v[0], b = v[1], c = v[2], d = v[3];
-  float m = fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])), fmaxf(fmaxf(b[0], b[1]), fmaxf(b[2], b[3])));
-  m = fmaxf(m, fmaxf(fmaxf(fmaxf(c[0], c[1]), fmaxf(c[2], c[3])), fmaxf(fmaxf(d[0], d[1]), fmaxf(d[2], d[3]))));
-  return m > -INFINITY ? m : 0.f;
-}
+// the reference value a frame's results are stored against: the largest value of the frame before, 0 when every
+// state is impossible, so that offsets stay finite
+__device__ __forceinline__ float frame_shift(float frame_max) { return frame_max > -INFINITY ? frame_max : 0.f; }
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+// floats per frame in the alpha and beta arrays: the 2 Lmax + 1 states and one more, so that pairs of states sit
+// on 8-byte boundaries
+__host__ __device__ __forceinline__ int ctc_state_pitch(int Lmax) { return 2 * Lmax + 2; }
 
 // per sequence: links between the label positions that hold the same token.  The label is staged in LDS; one
 // wavefront per position looks for the nearest later position with the same token, 64 candidates at a time, and
@@ -179,20 +178,37 @@ __global__ __launch_bounds__(THREADS) void ctc_row_kernel(CtcParams p) {
   }
 }
 
+// log(e^a + e^b) without a branch (see ctc_log_add3)
+__device__ __forceinline__ float ctc_log_add2(float a, float b) {
+  constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+  const float m = fmaxf(a, b);
+  const float ms = m > -INFINITY ? m : 0.f;
+  const float sum = __builtin_amdgcn_exp2f((a - ms) * kLog2e) + __builtin_amdgcn_exp2f((b - ms) * kLog2e);
+  return ms + kLn2 * __builtin_amdgcn_logf(sum);
+}
+
 // Two workgroups per sequence, on different compute units at the same time: blockIdx.y = 0 runs the forward
 // recursion (log alpha, the loss), blockIdx.y = 1 the backward one (log beta).  Neither needs the other's values;
 // the occupancies that need both are formed afterwards, in ctc_fix_kernel.
-template <int NS>  // states per thread
+//
+// A thread owns pairs of states: pair q is the blank in front of label position q (state 2q) and that label's own
+// state (2q + 1); pair L is the final blank alone.  The two states of a pair share their neighbours' values (three
+// LDS reads forward, four backward, instead of three per state), the blank needs a two-way log-add and only the
+// label a three-way one, and no lane has to find out which kind of state it holds.
+template <int NP>  // pairs per thread
 __global__ __launch_bounds__(1024) void ctc_dp_kernel(CtcParams p) {
-  extern __shared__ float lds[];  // two rows of Smax + 4 values (two -inf entries in front and behind)
+  extern __shared__ __attribute__((aligned(16))) float lds[];  // two rows of 2 Lmax + 6 values, -inf around the states
   const int b = blockIdx.x, tid = threadIdx.x, nthreads = blockDim.x;
   const bool backward = blockIdx.y != 0;
-  const int Smax = 2 * p.Lmax + 1;
+  const int SP = ctc_state_pitch(p.Lmax);
   const int L = clampi(p.label_len[b], 0, p.Lmax);
   const int S = 2 * L + 1;
   const int Tb = clampi(p.frame_len[b], 0, p.T);
-  const int pitch = Smax + 4;
-  __shared__ __attribute__((aligned(16))) float wmax[2][16];  // per frame parity: the wavefronts' largest value
+  const int pitch = 2 * p.Lmax + 6;  // even: state 2q of either row sits on an 8-byte boundary
+  // The largest value of a frame: every wavefront's maximum goes into one LDS word with an atomic max.  Three
+  // words in turn: frame t collects into word t % 3, reads word (t - 1) % 3 and resets word (t + 1) % 3, which
+  // was last read before the barrier of frame t - 1 and is next written after the barrier of frame t.
+  __shared__ float fmax3[3];
   const int32_t* y = p.labels + (size_t)b * p.Lmax;
   const float* lpc = p.lpc + (size_t)b * p.T * (p.Lmax + 1);
   if (Tb == 0) {
@@ -202,39 +218,43 @@ __global__ __launch_bounds__(1024) void ctc_dp_kernel(CtcParams p) {
     }
     return;
   }
-  // per state of this thread: index of its log-probability in a frame's compact row, and whether the transition
-  // that skips the blank before it exists (into s from s - 2) / after it (from s into s + 2)
-  int col[NS];
-  bool skip_in[NS], skip_out[NS];
+  // per pair of this thread: whether the pair (its blank) and its label state exist, the label's entry in a
+  // frame's compact row, and whether the transition that skips the blank exists into the label state (from
+  // state 2q - 1) / out of it (to state 2q + 3)
+  int col[NP];
+  bool has_pair[NP], has_label[NP], skip_in[NP], skip_out[NP];
 #pragma unroll
-  for (int u = 0; u < NS; ++u) {
-    const int s = tid + u * nthreads;
-    const int j = s >> 1;
-    col[u] = ((s & 1) && s < S) ? j : p.Lmax;  // states past the label read the blank's entry and drop it
-    skip_in[u] = (s & 1) && s >= 3 && s < S && y[j] != y[j - 1];
-    skip_out[u] = (s & 1) && s + 2 < S && y[j] != y[j + 1];
+  for (int u = 0; u < NP; ++u) {
+    const int q = tid + u * nthreads;
+    has_pair[u] = q <= L;
+    has_label[u] = q < L;
+    col[u] = q < L ? q : p.Lmax;  // pairs without a label read the blank's entry and drop it
+    skip_in[u] = q >= 1 && q < L && y[q] != y[q - 1];
+    skip_out[u] = q + 1 < L && y[q] != y[q + 1];
   }
   for (int i = tid; i < 2 * pitch; i += nthreads) lds[i] = -INFINITY;
-  if (tid < 32) wmax[tid >> 4][tid & 15] = -INFINITY;
+  if (tid < 3) fmax3[tid] = -INFINITY;
   __syncthreads();
 
   // A frame's log-probabilities are loaded several frames before the frame's turn, into a ring of registers: the
   // chain from frame to frame then runs through LDS and arithmetic only.  The barrier of a frame orders LDS
   // alone, so these loads and the stores of the frame's results stay in flight across it.
-  constexpr int AHEAD = NS >= 4 ? kCtcAhead / 2 : kCtcAhead;  // the ring has to fit 128 registers at 1024 threads
+  constexpr int AHEAD = kCtcAhead;
   const int lp_pitch = p.Lmax + 1;
-  float lpr[AHEAD][NS];
+  float lpr[AHEAD][NP], lpb[AHEAD];
 
   if (!backward) {
-    float* ag = p.ag + (size_t)b * p.T * Smax;
+    float* ag = p.ag + (size_t)b * p.T * SP;
     double* coff = p.coff_a + (size_t)b * p.T;
 #pragma unroll
     for (int i = 0; i < AHEAD; ++i) {
       const int tt = i < Tb ? i : Tb - 1;
+      lpb[i] = lpc[(size_t)tt * lp_pitch + p.Lmax];
 #pragma unroll
-      for (int u = 0; u < NS; ++u) lpr[i][u] = lpc[(size_t)tt * lp_pitch + col[u]];
+      for (int u = 0; u < NP; ++u) lpr[i][u] = lpc[(size_t)tt * lp_pitch + col[u]];
     }
     double c_alpha = 0.0;  // the stored values of the frame are log alpha - c_alpha
+    int slot_prev = 2, slot = 0, slot_next = 1;
     for (int t0 = 0; t0 < Tb; t0 += AHEAD) {
 #pragma unroll
       for (int i = 0; i < AHEAD; ++i) {
@@ -244,50 +264,66 @@ __global__ __launch_bounds__(1024) void ctc_dp_kernel(CtcParams p) {
           const float* prev = lds + 2 + ((t & 1) ^ 1) * pitch;
           float shift = 0.f;
           if (t > 0) {
-            shift = frame_max(wmax[(t & 1) ^ 1]);
+            shift = frame_shift(fmax3[slot_prev]);
             c_alpha += (double)shift;
           }
           float mine = -INFINITY;
 #pragma unroll
-          for (int u = 0; u < NS; ++u) {
-            const int s = tid + u * nthreads;
-            if (s < S) {
-              float a;
-              if (t == 0) a = s < 2 ? 0.f : -INFINITY;
-              else a = ctc_log_add3(prev[s], prev[s - 1], skip_in[u] ? prev[s - 2] : -INFINITY);
-              a += lpr[i][u] - shift;
-              cur[s] = a;
-              ag[(size_t)t * Smax + s] = a;
-              mine = fmaxf(mine, a);
+          for (int u = 0; u < NP; ++u) {
+            const int q = tid + u * nthreads;
+            if (has_pair[u]) {
+              float a_blank, a_label;
+              if (t == 0) {
+                a_blank = q == 0 ? 0.f : -INFINITY;
+                a_label = q == 0 ? 0.f : -INFINITY;
+              } else {
+                const float before = prev[2 * q - 1];
+                const f32x2 own = *(const f32x2*)(prev + 2 * q);
+                a_blank = ctc_log_add2(own[0], before);
+                a_label = ctc_log_add3(own[1], own[0], skip_in[u] ? before : -INFINITY);
+              }
+              a_blank += lpb[i] - shift;
+              a_label = has_label[u] ? a_label + (lpr[i][u] - shift) : -INFINITY;
+              const f32x2 both = {a_blank, a_label};
+              *(f32x2*)(cur + 2 * q) = both;
+              *(f32x2*)(ag + (size_t)t * SP + 2 * q) = both;
+              mine = fmaxf(mine, fmaxf(a_blank, a_label));
             }
           }
           mine = wave_max_f32(mine);
-          if ((tid & 63) == 0) wmax[t & 1][tid >> 6] = mine;
-          if (tid == 0) coff[t] = c_alpha;
+          if ((tid & 63) == 0) __hip_atomic_fetch_max(&fmax3[slot], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          if (tid == 0) {
+            fmax3[slot_next] = -INFINITY;
+            coff[t] = c_alpha;
+          }
+          slot_prev = slot; slot = slot_next; slot_next = slot_next == 2 ? 0 : slot_next + 1;
           const int tn = t + AHEAD < Tb ? t + AHEAD : Tb - 1;
+          lpb[i] = lpc[(size_t)tn * lp_pitch + p.Lmax];
 #pragma unroll
-          for (int u = 0; u < NS; ++u) lpr[i][u] = lpc[(size_t)tn * lp_pitch + col[u]];
+          for (int u = 0; u < NP; ++u) lpr[i][u] = lpc[(size_t)tn * lp_pitch + col[u]];
           lds_barrier();
         }
       }
     }
     const float* last = lds + 2 + ((Tb - 1) & 1) * pitch;
-    const float tail = ctc_log_add3(last[S - 1], S > 1 ? last[S - 2] : -INFINITY, -INFINITY);
+    const float tail = ctc_log_add2(last[S - 1], S > 1 ? last[S - 2] : -INFINITY);
     const double logP = c_alpha + (double)tail;  // -inf when the label cannot be reached
     if (tid == 0) {
       p.loss[b] = (float)-logP;
       p.logp[b] = logP;
     }
   } else {
-    float* bg = p.bg + (size_t)b * p.T * Smax;
+    float* bg = p.bg + (size_t)b * p.T * SP;
     double* coff = p.coff_b + (size_t)b * p.T;
 #pragma unroll
     for (int i = 0; i < AHEAD; ++i) {
       const int tt = Tb - 1 - i >= 0 ? Tb - 1 - i : 0;
+      lpb[i] = lpc[(size_t)tt * lp_pitch + p.Lmax];
 #pragma unroll
-      for (int u = 0; u < NS; ++u) lpr[i][u] = lpc[(size_t)tt * lp_pitch + col[u]];
+      for (int u = 0; u < NP; ++u) lpr[i][u] = lpc[(size_t)tt * lp_pitch + col[u]];
     }
     double c_beta = 0.0;  // the stored values of the frame are log beta - c_beta
+    int slot_prev = 2, slot = 0, slot_next = 1;
     for (int t0 = Tb - 1; t0 >= 0; t0 -= AHEAD) {
 #pragma unroll
       for (int i = 0; i < AHEAD; ++i) {
@@ -297,29 +333,43 @@ __global__ __launch_bounds__(1024) void ctc_dp_kernel(CtcParams p) {
           const float* nxt = lds + 2 + ((t & 1) ^ 1) * pitch;
           float shift = 0.f;
           if (t < Tb - 1) {
-            shift = frame_max(wmax[(t & 1) ^ 1]);
+            shift = frame_shift(fmax3[slot_prev]);
             c_beta += (double)shift;
           }
           float mine = -INFINITY;
 #pragma unroll
-          for (int u = 0; u < NS; ++u) {
-            const int s = tid + u * nthreads;
-            if (s < S) {
-              float bt;
-              if (t == Tb - 1) bt = s >= S - 2 ? 0.f : -INFINITY;
-              else bt = ctc_log_add3(nxt[s], nxt[s + 1], skip_out[u] ? nxt[s + 2] : -INFINITY);
-              bt += lpr[i][u] - shift;  // beta_t(s) includes p_t(z_s)
-              cur[s] = bt;
-              bg[(size_t)t * Smax + s] = bt;
-              mine = fmaxf(mine, bt);
+          for (int u = 0; u < NP; ++u) {
+            const int q = tid + u * nthreads;
+            if (has_pair[u]) {
+              float b_blank, b_label;
+              if (t == Tb - 1) {
+                b_blank = q == L ? 0.f : -INFINITY;
+                b_label = q == L - 1 ? 0.f : -INFINITY;
+              } else {
+                const f32x2 own = *(const f32x2*)(nxt + 2 * q);        // states 2q, 2q + 1
+                const f32x2 after = *(const f32x2*)(nxt + 2 * q + 2);  // states 2q + 2, 2q + 3
+                b_blank = ctc_log_add2(own[0], own[1]);
+                b_label = ctc_log_add3(own[1], after[0], skip_out[u] ? after[1] : -INFINITY);
+              }
+              b_blank += lpb[i] - shift;  // beta_t(s) includes p_t(z_s)
+              b_label = has_label[u] ? b_label + (lpr[i][u] - shift) : -INFINITY;
+              const f32x2 both = {b_blank, b_label};
+              *(f32x2*)(cur + 2 * q) = both;
+              *(f32x2*)(bg + (size_t)t * SP + 2 * q) = both;
+              mine = fmaxf(mine, fmaxf(b_blank, b_label));
             }
           }
           mine = wave_max_f32(mine);
-          if ((tid & 63) == 0) wmax[t & 1][tid >> 6] = mine;
-          if (tid == 0) coff[t] = c_beta;
+          if ((tid & 63) == 0) __hip_atomic_fetch_max(&fmax3[slot], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          if (tid == 0) {
+            fmax3[slot_next] = -INFINITY;
+            coff[t] = c_beta;
+          }
+          slot_prev = slot; slot = slot_next; slot_next = slot_next == 2 ? 0 : slot_next + 1;
           const int tn = t - AHEAD >= 0 ? t - AHEAD : 0;
+          lpb[i] = lpc[(size_t)tn * lp_pitch + p.Lmax];
 #pragma unroll
-          for (int u = 0; u < NS; ++u) lpr[i][u] = lpc[(size_t)tn * lp_pitch + col[u]];
+          for (int u = 0; u < NP; ++u) lpr[i][u] = lpc[(size_t)tn * lp_pitch + col[u]];
           lds_barrier();
         }
       }
@@ -342,10 +392,10 @@ __global__ __launch_bounds__(kCtcFixThreads) void ctc_fix_kernel(CtcParams p) {
     return;
   }
   const int L = clampi(p.label_len[b], 0, p.Lmax);
-  const int Smax = 2 * p.Lmax + 1;
+  const int SP = ctc_state_pitch(p.Lmax);
   const size_t frame = (size_t)b * p.T + t;
-  const float* __restrict__ al = p.ag + frame * Smax;
-  const float* __restrict__ be = p.bg + frame * Smax;
+  const float* __restrict__ al = p.ag + frame * SP;
+  const float* __restrict__ be = p.bg + frame * SP;
   const float* __restrict__ lp = p.lpc + frame * (p.Lmax + 1);
   // log of P over the two offsets of this frame: what the stored alpha + beta - log p is measured against
   const float z = (float)(logP - p.coff_a[frame] - p.coff_b[frame]);
@@ -394,8 +444,8 @@ static CtcWorkspace ctc_workspace(int B, int T, int Lmax) {
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t at = off; off = (off + bytes + 255) / 256 * 256; return at; };
   w.lpc = carve((size_t)B * T * (Lmax + 1) * 4);
-  w.ag = carve((size_t)B * T * (2 * (size_t)Lmax + 1) * 4);
-  w.bg = carve((size_t)B * T * (2 * (size_t)Lmax + 1) * 4);
+  w.ag = carve((size_t)B * T * ctc_state_pitch(Lmax) * 4);
+  w.bg = carve((size_t)B * T * ctc_state_pitch(Lmax) * 4);
   w.coff_a = carve((size_t)B * T * 8);
   w.coff_b = carve((size_t)B * T * 8);
   w.logp = carve((size_t)B * 8);
@@ -450,18 +500,14 @@ extern "C" int ctc_loss(ctcspec_ctx* ctx, const float* logits, const int32_t* la
   else if (nv <= 8) hipLaunchKernelGGL((ctc_row_kernel<8, kCtcRowThreads>), rows, row_threads, 0, st, p);
   else hipLaunchKernelGGL((ctc_row_kernel<16, kCtcRowThreads>), rows, row_threads, 0, st, p);
   CTCSPEC_HIP(ctx, hipGetLastError());
-  const int S = 2 * Lmax + 1;
-  int threads = (S + 63) / 64 * 64;
+  const int pairs = Lmax + 1;  // a blank and a label state each; the last one is the final blank alone
+  int threads = (pairs + 63) / 64 * 64;
   threads = threads > 1024 ? 1024 : threads;
-  const int ns = (S + threads - 1) / threads;
-  const int dp_lds = 2 * (S + 4) * 4;
+  const int np = (pairs + threads - 1) / threads;
+  const int dp_lds = 2 * (2 * Lmax + 6) * 4;
   const dim3 dp_grid(B, grad ? 2 : 1);  // without a gradient only the forward recursion runs
-  switch (ns) {
-    case 1: hipLaunchKernelGGL(ctc_dp_kernel<1>, dp_grid, dim3(threads), dp_lds, st, p); break;
-    case 2: hipLaunchKernelGGL(ctc_dp_kernel<2>, dp_grid, dim3(threads), dp_lds, st, p); break;
-    case 3: hipLaunchKernelGGL(ctc_dp_kernel<3>, dp_grid, dim3(threads), dp_lds, st, p); break;
-    default: hipLaunchKernelGGL(ctc_dp_kernel<4>, dp_grid, dim3(threads), dp_lds, st, p); break;
-  }
+  if (np <= 1) hipLaunchKernelGGL(ctc_dp_kernel<1>, dp_grid, dim3(threads), dp_lds, st, p);
+  else hipLaunchKernelGGL(ctc_dp_kernel<2>, dp_grid, dim3(threads), dp_lds, st, p);
   CTCSPEC_HIP(ctx, hipGetLastError());
   if (grad) {
     const int per = kCtcFixThreads / 64;
