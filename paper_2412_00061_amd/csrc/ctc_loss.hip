@@ -34,12 +34,12 @@ struct CtcParams {
   const int32_t* frame_len; // [B]
   int B, T, Vp1, Lmax, blank;
   // workspace
-  float* lpc;     // [B][T][Lmax + 1]: log p_t(y_j) for j < L, log p_t(blank) at Lmax
-  float* ag;      // [B][T][2 Lmax + 2]: log alpha minus the frame's offset (state s at s; the last entry unused)
-  float* bg;      // [B][T][2 Lmax + 2]: log beta minus the frame's offset
+  float* lpc;     // [B][T][Lmax + 1]: log2 p_t(y_j) for j < L, log2 p_t(blank) at Lmax
+  float* ag;      // [B][T][2 Lmax + 2]: log2 alpha minus the frame's offset (state s at s; the last entry unused)
+  float* bg;      // [B][T][2 Lmax + 2]: log2 beta minus the frame's offset
   double* coff_a; // [B][T]: offset of the frame's log alpha values
   double* coff_b; // [B][T]: offset of the frame's log beta values
-  double* logp;   // [B]: log P(Y | X)
+  double* logp;   // [B]: log2 P(Y | X)
   int32_t* next;  // [B][Lmax]: next label position with the same token, -1: none
   int32_t* first; // [B][Lmax]: 1 when no earlier position holds the same token
   // outputs
@@ -47,16 +47,16 @@ struct CtcParams {
   float* grad;    // [B][T][Vp1] or null
 };
 
-// log(e^a + e^b + e^c) without a branch; -inf stands for an impossible state and any of the three may be -inf.
-// The bare exp2/log2 instructions carry an absolute error near 1e-7 here (the arguments of exp are <= 0, the
-// argument of log is in [1, 3]; a term below 2^-126 of the largest is dropped), far below what the occupancies need.
+// The recursions run on base-2 logarithms (ctc_row_kernel hands out log2 p, the loss is turned back at the end):
+// the exp2 and log2 instructions then need no scaling of their argument or result.
+// log2(2^a + 2^b + 2^c) without a branch; -inf stands for an impossible state and any of the three may be -inf.
+// The bare instructions carry an absolute error near 1e-7 here (the arguments of exp2 are <= 0, the argument of
+// log2 is in [1, 3]; a term below 2^-126 of the largest is dropped), far below what the occupancies need.
 __device__ __forceinline__ float ctc_log_add3(float a, float b, float c) {
   const float m = fmaxf(fmaxf(a, b), c);
   const float ms = m > -INFINITY ? m : 0.f;
-  constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
-  const float sum = __builtin_amdgcn_exp2f((a - ms) * kLog2e) + __builtin_amdgcn_exp2f((b - ms) * kLog2e) +
-                    __builtin_amdgcn_exp2f((c - ms) * kLog2e);
-  return ms + kLn2 * __builtin_amdgcn_logf(sum);  // the bare log2 instruction; sum = 0 gives -inf
+  const float sum = __builtin_amdgcn_exp2f(a - ms) + __builtin_amdgcn_exp2f(b - ms) + __builtin_amdgcn_exp2f(c - ms);
+  return ms + __builtin_amdgcn_logf(sum);  // the bare log2 instruction; sum = 0 gives -inf
 }
 // the reference value a frame's results are stored against: the largest value of the frame before, 0 when every
 // state is impossible, so that offsets stay finite
@@ -164,8 +164,10 @@ __global__ __launch_bounds__(THREADS) void ctc_row_kernel(CtcParams p) {
   const float lse = mx + logf(sum);
   const int L = clampi(p.label_len[b], 0, p.Lmax);
   float* out = p.lpc + ((size_t)b * p.T + t) * (p.Lmax + 1);
-  for (int j = tid; j < L; j += THREADS) out[j] = z[clampi(p.labels[(size_t)b * p.Lmax + j], 0, p.Vp1 - 1)] - lse;
-  if (tid == 0) out[p.Lmax] = z[p.blank] - lse;
+  constexpr float kLog2e = 1.4426950408889634f;  // the recursions take base-2 logarithms
+  for (int j = tid; j < L; j += THREADS)
+    out[j] = (z[clampi(p.labels[(size_t)b * p.Lmax + j], 0, p.Vp1 - 1)] - lse) * kLog2e;
+  if (tid == 0) out[p.Lmax] = (z[p.blank] - lse) * kLog2e;
   if (g) {
     const float inv = 1.f / sum;
     f32x4* gv = (f32x4*)(g + head);
@@ -178,13 +180,12 @@ __global__ __launch_bounds__(THREADS) void ctc_row_kernel(CtcParams p) {
   }
 }
 
-// log(e^a + e^b) without a branch (see ctc_log_add3)
+// log2(2^a + 2^b) without a branch (see ctc_log_add3)
 __device__ __forceinline__ float ctc_log_add2(float a, float b) {
-  constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
   const float m = fmaxf(a, b);
   const float ms = m > -INFINITY ? m : 0.f;
-  const float sum = __builtin_amdgcn_exp2f((a - ms) * kLog2e) + __builtin_amdgcn_exp2f((b - ms) * kLog2e);
-  return ms + kLn2 * __builtin_amdgcn_logf(sum);
+  const float sum = __builtin_amdgcn_exp2f(a - ms) + __builtin_amdgcn_exp2f(b - ms);
+  return ms + __builtin_amdgcn_logf(sum);
 }
 
 // Two workgroups per sequence, on different compute units at the same time: blockIdx.y = 0 runs the forward
@@ -307,9 +308,9 @@ __global__ __launch_bounds__(1024) void ctc_dp_kernel(CtcParams p) {
     }
     const float* last = lds + 2 + ((Tb - 1) & 1) * pitch;
     const float tail = ctc_log_add2(last[S - 1], S > 1 ? last[S - 2] : -INFINITY);
-    const double logP = c_alpha + (double)tail;  // -inf when the label cannot be reached
+    const double logP = c_alpha + (double)tail;  // base 2; -inf when the label cannot be reached
     if (tid == 0) {
-      p.loss[b] = (float)-logP;
+      p.loss[b] = (float)(-logP * 0.6931471805599453);
       p.logp[b] = logP;
     }
   } else {
@@ -401,7 +402,7 @@ __global__ __launch_bounds__(kCtcFixThreads) void ctc_fix_kernel(CtcParams p) {
   const float z = (float)(logP - p.coff_a[frame] - p.coff_b[frame]);
   auto gamma = [&](int s, float l) {
     const float a = al[s], bt = be[s];
-    return (a > -INFINITY && bt > -INFINITY) ? expf(a + bt - l - z) : 0.f;
+    return (a > -INFINITY && bt > -INFINITY) ? exp2f(a + bt - l - z) : 0.f;  // base-2 logarithms throughout
   };
   // The occupancies of a frame sum to one (every alignment is in exactly one state at frame t).  What is left
   // of the recursions' rounding after thousands of frames is mostly common to all states of a frame - it sits in
