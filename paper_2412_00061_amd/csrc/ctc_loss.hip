@@ -22,10 +22,12 @@ namespace ctcspec {
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 constexpr int kCtcMaxLabels = 2047;  // L + 1 pairs of states <= 2 per thread of a 1024-thread workgroup
-constexpr int kCtcRowThreads = 1024;
+constexpr int kCtcRowThreads = 1024;  // with two label positions per thread: kCtcMaxLabels + 1 <= 2 * kCtcRowThreads
 constexpr int kCtcMaxRow = 16 * kCtcRowThreads * 4;  // 65536 symbols: 16 16-byte loads per thread
 constexpr int kCtcFixThreads = 256;
 constexpr int kCtcAhead = 8;  // frames between a load and its use in the recursions
+
+static_assert(kCtcMaxLabels + 1 <= 2 * kCtcRowThreads, "ctc_row_kernel fetches two label positions per thread");
 
 struct CtcParams {
   const float* logits;      // [B][T][Vp1]
@@ -127,6 +129,15 @@ __global__ __launch_bounds__(THREADS) void ctc_row_kernel(CtcParams p) {
   }
   const float* z = p.logits + row0;
   const f32x4* zv = (const f32x4*)(z + head);
+  // the label's token ids first (kCtcMaxLabels < 2 * THREADS: two per thread), then the row, then the label's
+  // logits while the row's cache lines are still on their way - asked for later they come from HBM a second time
+  const int L = clampi(p.label_len[b], 0, p.Lmax);
+  int yid[2];
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int j = tid + r * THREADS;
+    yid[r] = j < L ? clampi(p.labels[(size_t)b * p.Lmax + j], 0, p.Vp1 - 1) : p.blank;
+  }
   f32x4 x[NV];
 #pragma unroll
   for (int k = 0; k < NV; ++k) {
@@ -134,6 +145,7 @@ __global__ __launch_bounds__(THREADS) void ctc_row_kernel(CtcParams p) {
     x[k] = i < nvec ? zv[i] : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
   }
   float xe = edge >= 0 ? z[edge] : -INFINITY;
+  const float zy[2] = {z[yid[0]], z[yid[1]]};
   float mx = xe;
 #pragma unroll
   for (int k = 0; k < NV; ++k) mx = fmaxf(fmaxf(fmaxf(mx, x[k][0]), fmaxf(x[k][1], x[k][2])), x[k][3]);
@@ -162,12 +174,14 @@ __global__ __launch_bounds__(THREADS) void ctc_row_kernel(CtcParams p) {
 #pragma unroll
   for (int w = 0; w < THREADS / 64; ++w) sum += red[w];
   const float lse = mx + logf(sum);
-  const int L = clampi(p.label_len[b], 0, p.Lmax);
   float* out = p.lpc + ((size_t)b * p.T + t) * (p.Lmax + 1);
   constexpr float kLog2e = 1.4426950408889634f;  // the recursions take base-2 logarithms
-  for (int j = tid; j < L; j += THREADS)
-    out[j] = (z[clampi(p.labels[(size_t)b * p.Lmax + j], 0, p.Vp1 - 1)] - lse) * kLog2e;
-  if (tid == 0) out[p.Lmax] = (z[p.blank] - lse) * kLog2e;
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int j = tid + r * THREADS;
+    if (j < L) out[j] = (zy[r] - lse) * kLog2e;
+    else if (j == L) out[p.Lmax] = (zy[r] - lse) * kLog2e;  // this thread's spare slot fetched the blank
+  }
   if (g) {
     const float inv = 1.f / sum;
     f32x4* gv = (f32x4*)(g + head);
