@@ -69,32 +69,48 @@ __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? l
 __host__ __device__ __forceinline__ int ctc_state_pitch(int Lmax) { return 2 * Lmax + 2; }
 
 // per sequence: links between the label positions that hold the same token.  The label is staged in LDS; one
-// wavefront per position looks for the nearest later position with the same token, 64 candidates at a time, and
-// a position that some earlier one points to is not a first occurrence.
+// wavefront per position looks for the nearest later position with the same token and for any earlier one, 256
+// candidates per round trip to LDS.  The positions of a sequence are dealt to gridDim.y workgroups; every entry
+// of next and first is written by the wavefront that owns the position, so the workgroups share nothing.
 __global__ __launch_bounds__(1024) void ctc_links_kernel(CtcParams p) {
   extern __shared__ int32_t ytok[];  // [Lmax]
   const int b = blockIdx.x, tid = threadIdx.x, n = blockDim.x;
-  const int lane = tid & 63, wave = tid >> 6, nwaves = n >> 6;
+  const int lane = tid & 63, nwaves = n >> 6;
+  const int wave = (tid >> 6) + nwaves * blockIdx.y, stride = nwaves * gridDim.y;
   const int L = clampi(p.label_len[b], 0, p.Lmax);
   int32_t* next = p.next + (size_t)b * p.Lmax;
   int32_t* first = p.first + (size_t)b * p.Lmax;
-  for (int j = tid; j < p.Lmax; j += n) {
-    ytok[j] = j < L ? p.labels[(size_t)b * p.Lmax + j] : -1;
-    next[j] = -1;
-    first[j] = j < L;
-  }
-  __syncthreads();  // also puts the defaults just stored before the updates below
-  for (int j = wave; j < L; j += nwaves) {
-    const int tok = ytok[j];
+  for (int j = tid; j < L; j += n) ytok[j] = p.labels[(size_t)b * p.Lmax + j];
+  __syncthreads();
+  for (int j = wave; j < p.Lmax; j += stride) {
     int found = -1;
-    for (int i0 = j + 1; i0 < L && found < 0; i0 += 64) {
-      const int i = i0 + lane;
-      const unsigned long long hits = __ballot(i < L && ytok[i] == tok);
-      if (hits) found = i0 + __ffsll((long long)hits) - 1;
+    bool earlier = false;
+    if (j < L) {
+      const int tok = ytok[j];
+      for (int i0 = j + 1; i0 < L && found < 0; i0 += 256) {
+        unsigned long long hits[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int i = i0 + 64 * r + lane;
+          hits[r] = __ballot(i < L && ytok[i] == tok);
+        }
+#pragma unroll
+        for (int r = 3; r >= 0; --r)
+          if (hits[r]) found = i0 + 64 * r + __ffsll((long long)hits[r]) - 1;  // the lowest group with a hit wins
+      }
+      for (int i0 = 0; i0 < j && !earlier; i0 += 256) {
+        unsigned long long any = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int i = i0 + 64 * r + lane;
+          any |= __ballot(i < j && ytok[i] == tok);
+        }
+        earlier = any != 0;
+      }
     }
-    if (found >= 0 && lane == 0) {
+    if (lane == 0) {
       next[j] = found;
-      first[found] = 0;
+      first[j] = (j < L && !earlier) ? 1 : 0;
     }
   }
 }
@@ -505,7 +521,8 @@ extern "C" int ctc_loss(ctcspec_ctx* ctx, const float* logits, const int32_t* la
   p.next = (int32_t*)(ws + w.next); p.first = (int32_t*)(ws + w.first);
   p.loss = loss; p.grad = grad;
   hipStream_t st = ctx->stream;
-  hipLaunchKernelGGL(ctc_links_kernel, dim3(B), dim3(Lmax > 256 ? 1024 : 256), Lmax * 4, st, p);
+  const int link_blocks = Lmax > 256 ? (Lmax + 127) / 128 : 1;  // eight positions per wavefront at the most
+  hipLaunchKernelGGL(ctc_links_kernel, dim3(B, link_blocks), dim3(Lmax > 256 ? 1024 : 256), Lmax * 4, st, p);
   CTCSPEC_HIP(ctx, hipGetLastError());
   const int nv = (Vp1 / 4 + kCtcRowThreads - 1) / kCtcRowThreads;  // 16-byte loads per thread
   const dim3 rows(T, B), row_threads(kCtcRowThreads);
