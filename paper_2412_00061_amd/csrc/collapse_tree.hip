@@ -547,81 +547,88 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
       block_bitonic_sort_desc(keys, P2);
     }
 
-    // Walk the sorted survivors.  Down to score tau_valid the list is exactly the global order (every
-    // raw candidate that good is a survivor); those positions are collapsed and first occurrences are
-    // found through a hash table of positions.
-    int log2_ts = 6;
-    while ((1 << log2_ts) < 2 * n_s) ++log2_ts;
-    const int TS = 1 << log2_ts;
-    for (int i = tid; i < TS; i += kThreads) table[i] = kEmptySlot;
-    for (int i = tid; i < n_s; i += kThreads) {
-      const unsigned long long key = keys[i];
-      unsigned long long ck = ~0ull;  // ~0: not walked (below tau_valid) or the empty draft
-      if (final_level || rank_key_value(key) >= tau_valid) {
-        const int idx = (int)rank_key_index(key);
-        const int a = n2 == 1 ? idx : (int)__umulhi((unsigned)idx, p.magic_n2), bb = idx - a * n2;  // idx / n2
-        int len;
-        const unsigned long long c =
-            collapse_key<RAW>(s, split_digits(a, pad1, k, magic), split_digits(bb, pad2, k, magic), T1, T2, k, &len);
-        ck = len ? c : ~0ull;
-      }
-      ckeys[i] = ck;
-    }
-    __syncthreads();
-    for (int i = tid; i < n_s; i += kThreads) {
-      const unsigned long long ck = ckeys[i];
-      if (ck == ~0ull) continue;
-      unsigned int slot = hash_slot(ck, log2_ts);
-      for (;;) {
-        unsigned int cur = table[slot];
-        if (cur == kEmptySlot) {
-          cur = atomicCAS(&table[slot], kEmptySlot, (unsigned)i);
-          if (cur == kEmptySlot) break;
+    // The walk is instantiated twice, once on the LDS lists and once on the lists in the global workspace: with
+    // one set of pointers that may be either, every access would be a flat instruction.
+    auto walk = [&](unsigned long long* keys, unsigned long long* ckeys, unsigned int* table) -> bool {
+      // Walk the sorted survivors.  Down to score tau_valid the list is exactly the global order (every
+      // raw candidate that good is a survivor); those positions are collapsed and first occurrences are
+      // found through a hash table of positions.
+      int log2_ts = 6;
+      while ((1 << log2_ts) < 2 * n_s) ++log2_ts;
+      const int TS = 1 << log2_ts;
+      for (int i = tid; i < TS; i += kThreads) table[i] = kEmptySlot;
+      for (int i = tid; i < n_s; i += kThreads) {
+        const unsigned long long key = keys[i];
+        unsigned long long ck = ~0ull;  // ~0: not walked (below tau_valid) or the empty draft
+        if (final_level || rank_key_value(key) >= tau_valid) {
+          const int idx = (int)rank_key_index(key);
+          const int a = n2 == 1 ? idx : (int)__umulhi((unsigned)idx, p.magic_n2), bb = idx - a * n2;  // idx / n2
+          int len;
+          const unsigned long long c =
+              collapse_key<RAW>(s, split_digits(a, pad1, k, magic), split_digits(bb, pad2, k, magic), T1, T2, k, &len);
+          ck = len ? c : ~0ull;
         }
-        if (ckeys[cur] == ck) { atomicMin(&table[slot], (unsigned)i); break; }
-        slot = (slot + 1) & (TS - 1);
+        ckeys[i] = ck;
       }
-    }
-    __syncthreads();
-    // distinct non-empty drafts in walk order; thread t owns positions [t*per, (t+1)*per)
-    const int per = (n_s + kThreads - 1) / kThreads;
-    const int i_begin = tid * per, i_end = min(n_s, (tid + 1) * per);
-    int first_cnt = 0;
-    unsigned int first_bits = 0u;  // flags of my first 32 positions, so that they are not looked up twice
-    for (int i = i_begin; i < i_end; ++i) {
-      const unsigned long long ck = ckeys[i];
-      if (ck == ~0ull) continue;
-      unsigned int slot = hash_slot(ck, log2_ts);
-      while (ckeys[table[slot]] != ck) slot = (slot + 1) & (TS - 1);
-      const bool is_first = table[slot] == (unsigned)i;
-      first_cnt += is_first ? 1 : 0;
-      if (is_first && i - i_begin < 32) first_bits |= 1u << (i - i_begin);
-    }
-    const int rank0 = block_exclusive_scan(first_cnt, s.red, &n_d);
-    if (n_d >= beam || final_level) {
-      int rank = rank0;
-      for (int i = i_begin; i < i_end && rank < beam; ++i) {
+      __syncthreads();
+      for (int i = tid; i < n_s; i += kThreads) {
         const unsigned long long ck = ckeys[i];
-        bool is_first;
-        if (i - i_begin < 32) {
-          is_first = (first_bits >> (i - i_begin)) & 1u;
-        } else {
-          if (ck == ~0ull) continue;
-          unsigned int slot = hash_slot(ck, log2_ts);
-          while (ckeys[table[slot]] != ck) slot = (slot + 1) & (TS - 1);
-          is_first = table[slot] == (unsigned)i;
+        if (ck == ~0ull) continue;
+        unsigned int slot = hash_slot(ck, log2_ts);
+        for (;;) {
+          unsigned int cur = table[slot];
+          if (cur == kEmptySlot) {
+            cur = atomicCAS(&table[slot], kEmptySlot, (unsigned)i);
+            if (cur == kEmptySlot) break;
+          }
+          if (ckeys[cur] == ck) { atomicMin(&table[slot], (unsigned)i); break; }
+          slot = (slot + 1) & (TS - 1);
         }
-        if (!is_first) continue;
-        int len = 0;
-#pragma unroll
-        for (int d = 0; d < 8; ++d) len += (((ck >> (7 * d)) & 0x7f) != kBlankCode) ? 1 : 0;
-        s.kept_ck[rank] = ck;
-        s.kept_len[rank] = len;
-        p.cand_score[(size_t)b * beam + rank] = rank_key_value(keys[i]);
-        ++rank;
       }
-      break;
-    }
+      __syncthreads();
+      // distinct non-empty drafts in walk order; thread t owns positions [t*per, (t+1)*per)
+      const int per = (n_s + kThreads - 1) / kThreads;
+      const int i_begin = tid * per, i_end = min(n_s, (tid + 1) * per);
+      int first_cnt = 0;
+      unsigned int first_bits = 0u;  // flags of my first 32 positions, so that they are not looked up twice
+      for (int i = i_begin; i < i_end; ++i) {
+        const unsigned long long ck = ckeys[i];
+        if (ck == ~0ull) continue;
+        unsigned int slot = hash_slot(ck, log2_ts);
+        while (ckeys[table[slot]] != ck) slot = (slot + 1) & (TS - 1);
+        const bool is_first = table[slot] == (unsigned)i;
+        first_cnt += is_first ? 1 : 0;
+        if (is_first && i - i_begin < 32) first_bits |= 1u << (i - i_begin);
+      }
+      const int rank0 = block_exclusive_scan(first_cnt, s.red, &n_d);
+      if (n_d >= beam || final_level) {
+        int rank = rank0;
+        for (int i = i_begin; i < i_end && rank < beam; ++i) {
+          const unsigned long long ck = ckeys[i];
+          bool is_first;
+          if (i - i_begin < 32) {
+            is_first = (first_bits >> (i - i_begin)) & 1u;
+          } else {
+            if (ck == ~0ull) continue;
+            unsigned int slot = hash_slot(ck, log2_ts);
+            while (ckeys[table[slot]] != ck) slot = (slot + 1) & (TS - 1);
+            is_first = table[slot] == (unsigned)i;
+          }
+          if (!is_first) continue;
+          int len = 0;
+  #pragma unroll
+          for (int d = 0; d < 8; ++d) len += (((ck >> (7 * d)) & 0x7f) != kBlankCode) ? 1 : 0;
+          s.kept_ck[rank] = ck;
+          s.kept_len[rank] = len;
+          p.cand_score[(size_t)b * beam + rank] = rank_key_value(keys[i]);
+          ++rank;
+        }
+        return true;
+      }
+      return false;
+    };
+    const bool done = in_lds ? walk(s.keys, s.ckeys, s.table) : walk(keys, ckeys, table);
+    if (done) break;
     M *= 4;
     __syncthreads();
   }
