@@ -108,6 +108,72 @@ __device__ void lmhead_block_epilogue(const LmHeadParams& p, const float* zbuf) 
   }
 }
 
+// The same epilogue for many columns: a lane per column instead of a wavefront per column.  Wavefront w scans
+// rows 16w .. 16w+15 of every column (lane = column, the 16 logits in registers, the k best keys kept sorted in
+// registers), leaves its (max, sum, keys) per column in LDS, and wavefront 0 merges the eight partials of each
+// column.  About 16 + 8 short steps per lane against eight columns in turn per wavefront, each with k 64-bit
+// wavefront reductions.  `part` is LDS behind zbuf: 8 x kMaxCols x (2 floats + KMAX keys).
+template <int KMAX>
+__device__ void lmhead_block_epilogue_wide(const LmHeadParams& p, const float* zbuf, unsigned char* part) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row_base = blockIdx.x * kRowsPerBlock;
+  static_assert(kMaxCols <= 64 && kRowsPerBlock == 16 * kMfmaWaves, "a lane per column, sixteen rows per wavefront");
+  if (p.logits_out) {
+    for (int idx = tid; idx < p.BT * kRowsPerBlock; idx += blockDim.x) {
+      int m = idx / kRowsPerBlock, r = idx % kRowsPerBlock;
+      if (row_base + r < p.Vp1) p.logits_out[(size_t)m * p.Vp1 + row_base + r] = zbuf[m * kZStride + r];
+    }
+  }
+  float* pm = (float*)part;                                        // [8][kMaxCols]
+  float* ps = pm + kMfmaWaves * kMaxCols;                          // [8][kMaxCols]
+  unsigned long long* pk = (unsigned long long*)(ps + kMfmaWaves * kMaxCols);  // [8][kMaxCols][KMAX]
+  const int m = lane;
+  if (m < p.BT) {
+    f32x4 z[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) z[q] = *(const f32x4*)(zbuf + m * kZStride + 16 * wave + 4 * q);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) mx = fmaxf(mx, fmaxf(fmaxf(z[q][0], z[q][1]), fmaxf(z[q][2], z[q][3])));
+    float e = 0.f;
+    KeyList<KMAX> list;
+    list.clear();
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int id = row_base + 16 * wave + 4 * q + i;
+        if (mx > -INFINITY) e += __expf(z[q][i] - mx);
+        list.insert(id < p.Vp1 ? rank_key(z[q][i], (unsigned)id) : 0ull);
+      }
+    pm[wave * kMaxCols + m] = mx;
+    ps[wave * kMaxCols + m] = e;
+#pragma unroll
+    for (int r = 0; r < KMAX; ++r) pk[(wave * kMaxCols + m) * KMAX + r] = list.v[r];
+  }
+  __syncthreads();
+  if (wave == 0 && m < p.BT) {
+    float m_run = -INFINITY, s_run = 0.f;
+    KeyList<KMAX> list;
+    list.clear();
+#pragma unroll
+    for (int w = 0; w < kMfmaWaves; ++w) {
+      const float wm = pm[w * kMaxCols + m], wsum = ps[w * kMaxCols + m];
+      if (wm > -INFINITY) {
+        const float mn = fmaxf(m_run, wm);
+        s_run = s_run * __expf(m_run - mn) + wsum * __expf(wm - mn);
+        m_run = mn;
+      }
+#pragma unroll
+      for (int r = 0; r < KMAX; ++r) list.insert(pk[(w * kMaxCols + m) * KMAX + r]);
+    }
+    const size_t slot = (size_t)blockIdx.x * kMaxCols + m;
+    p.pmax[slot] = m_run;
+    p.psum[slot] = s_run;
+    for (int r = 0; r < p.k; ++r) p.pkey[slot * kMaxTopk + r] = r < KMAX ? list.v[r] : 0ull;
+  }
+}
+
 // Merge of the per-workgroup partials: one wavefront per column.  Lane l owns workgroups l, l+64, ...;
 // all of a lane's partials are requested before any is used, so the kernel costs about one memory
 // round trip.
@@ -362,9 +428,15 @@ __global__ __launch_bounds__(64 * kTileWaves) void lmhead_bf16_tile_kernel(LmHea
       }
     }
   __syncthreads();
-  lmhead_block_epilogue(p, zbuf);
+  unsigned char* part = smem + kMaxCols * kZStride * 4;
+  if (p.BT <= 16) lmhead_block_epilogue(p, zbuf);  // a wavefront per column, at most two in turn
+  else if (p.k <= 1) lmhead_block_epilogue_wide<1>(p, zbuf, part);
+  else if (p.k <= 2) lmhead_block_epilogue_wide<2>(p, zbuf, part);
+  else if (p.k <= 4) lmhead_block_epilogue_wide<4>(p, zbuf, part);
+  else lmhead_block_epilogue_wide<8>(p, zbuf, part);
 }
-static_assert(kMaxCols <= 64 && kMaxCols * kZStride * 4 <= tile_lds_bytes<1>(), "one 64-column tile holds every column");
+static_assert(kMaxCols <= 64 && kMaxCols * kZStride * 4 + kMfmaWaves * kMaxCols * (8 + 8 * kMaxTopk) <= tile_lds_bytes<1>(),
+              "one 64-column tile holds every column and the epilogue's partials");
 
 static void launch_merge(const LmHeadParams& p, hipStream_t stream) {
   if (p.k <= 1) hipLaunchKernelGGL(lmhead_merge_kernel<1>, dim3(p.BT), dim3(64), 0, stream, p);
