@@ -409,8 +409,7 @@ __global__ __launch_bounds__(1024) void ctc_dp_kernel(CtcParams p) {
 }
 
 // One wavefront per frame: the occupancies gamma_t(s) = alpha_t(s) beta_t(s) / (p_t(z_s) P) of the label's tokens
-// and of the blank come off the softmax that ctc_row_kernel left in the gradient row.  Only these few entries of
-// the row are touched.
+// and of the blank come off the softmax in the gradient row.  Only these few entries of the row are touched.
 __global__ __launch_bounds__(kCtcFixThreads) void ctc_fix_kernel(CtcParams p) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * (kCtcFixThreads / 64) + (threadIdx.x >> 6), b = blockIdx.y;
@@ -448,7 +447,9 @@ __global__ __launch_bounds__(kCtcFixThreads) void ctc_fix_kernel(CtcParams p) {
   const float total = gb + go;
   const float inv = total > 0.f ? 1.f / total : 1.f;
   // the blank: all even states
-  if (lane == 0) g[p.blank] -= gb * inv;
+  // The entries are written, not updated: the softmax value that ctc_row_kernel left there is formed again from
+  // the log-probability at hand, which saves fetching a cache line per entry.
+  if (lane == 0) g[p.blank] = exp2f(lblank) - gb * inv;
   // the label's tokens: the lane of a token's first position adds the occupancies of all its positions (nearly
   // always just the one, so every lane forms its own position's occupancy first and the loads of several
   // positions are in flight together)
@@ -459,10 +460,11 @@ __global__ __launch_bounds__(kCtcFixThreads) void ctc_fix_kernel(CtcParams p) {
   for (int j = lane; j < L; j += 64) {
     const int is_first = fs[j];
     const int tok = clampi(y[j], 0, p.Vp1 - 1);
-    float tot = gamma(2 * j + 1, lp[j]);
+    const float l = lp[j];
+    float tot = gamma(2 * j + 1, l);
     if (is_first) {
       for (int i = nx[j]; i >= 0; i = nx[i]) tot += gamma(2 * i + 1, lp[i]);
-      if (tok != p.blank) g[tok] -= tot * inv;  // a label never holds the blank; ids come from the caller
+      if (tok != p.blank) g[tok] = exp2f(l) - tot * inv;  // a label never holds the blank; ids come from the caller
     }
   }
 }
