@@ -81,9 +81,11 @@ const char* ctcspec_last_error(const ctcspec_ctx* ctx);
 /* Bytes of device workspace the context holds. */
 size_t ctcspec_workspace_bytes(const ctcspec_ctx* ctx);
 
-/* Measurement aid.  With enable != 0, every following ctc_draft_topk call records a pair of HIP events
- * on the context's stream directly around its main kernel (the pass over the head weights, not the
- * small merge kernel).  ctcspec_draft_head_kernel_ms synchronises with the second event of the LAST
+/* Measurement aid.  With enable != 0, every following ctc_draft_topk call attaches a pair of HIP events
+ * to the launch of its main kernel on the context's stream (the pass over the head weights, not the
+ * small merge kernel): the events take that kernel's begin and end timestamps.  (The many-column and
+ * generic producers record the pair around the launch instead, which also spans the dispatch.)
+ * ctcspec_draft_head_kernel_ms synchronises with the second event of the LAST
  * such call and returns the elapsed milliseconds in *ms (host pointer).  CTCSPEC_EINVAL when profiling
  * is off or no call has been made since it was switched on. */
 int ctcspec_profile_draft_head(ctcspec_ctx* ctx, int enable);

@@ -18,6 +18,8 @@
 #include <type_traits>
 #include <utility>
 
+#include <hip/hip_ext.h>
+
 #include "gemm_tile.h"
 
 namespace ctcspec {
@@ -455,8 +457,10 @@ static int pick_kc(int BT, int D, int stages, int budget) {
   return 0;
 }
 
+// ev0/ev1, when given, are attached to the launch itself: they take the kernel's own begin and end timestamps (what a
+// kernel trace reports), without the dispatch work that a pair of events recorded around the launch also spans.
 template <int NT, int STAGES>
-static hipError_t launch_mfma(const LmHeadParams& p, int lds_bytes, hipStream_t stream) {
+static hipError_t launch_mfma(const LmHeadParams& p, int lds_bytes, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1) {
   auto kern = lmhead_bf16_mfma_kernel<NT, STAGES>;
   static int lds_allowed = 0;  // per instantiation; raising the limit is needed once per process
   if (lds_bytes > lds_allowed) {
@@ -464,7 +468,10 @@ static hipError_t launch_mfma(const LmHeadParams& p, int lds_bytes, hipStream_t 
     if (e != hipSuccess) return e;
     lds_allowed = lds_bytes;
   }
-  hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(64 * kMfmaWaves), lds_bytes, stream, p);
+  if (ev0 && ev1)
+    hipExtLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(64 * kMfmaWaves), lds_bytes, stream, ev0, ev1, 0, p);
+  else
+    hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(64 * kMfmaWaves), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
@@ -514,27 +521,24 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
       int lds = p.hs_bytes + kMfmaWaves * kWStageBytes;
       int nt = (p.BT + 15) / 16;
       hipError_t e;
-      if (ctx->lm_profile) CTCSPEC_HIP(ctx, hipEventRecord(ctx->lm_ev0, ctx->stream));
+      hipEvent_t ev0 = ctx->lm_profile ? ctx->lm_ev0 : nullptr, ev1 = ctx->lm_profile ? ctx->lm_ev1 : nullptr;
       if (stages == 4) {
         switch (nt) {
-          case 1: e = launch_mfma<1, 4>(p, lds, ctx->stream); break;
-          case 2: e = launch_mfma<2, 4>(p, lds, ctx->stream); break;
-          case 3: e = launch_mfma<3, 4>(p, lds, ctx->stream); break;
-          default: e = launch_mfma<4, 4>(p, lds, ctx->stream); break;
+          case 1: e = launch_mfma<1, 4>(p, lds, ctx->stream, ev0, ev1); break;
+          case 2: e = launch_mfma<2, 4>(p, lds, ctx->stream, ev0, ev1); break;
+          case 3: e = launch_mfma<3, 4>(p, lds, ctx->stream, ev0, ev1); break;
+          default: e = launch_mfma<4, 4>(p, lds, ctx->stream, ev0, ev1); break;
         }
       } else {
         switch (nt) {
-          case 1: e = launch_mfma<1, 2>(p, lds, ctx->stream); break;
-          case 2: e = launch_mfma<2, 2>(p, lds, ctx->stream); break;
-          case 3: e = launch_mfma<3, 2>(p, lds, ctx->stream); break;
-          default: e = launch_mfma<4, 2>(p, lds, ctx->stream); break;
+          case 1: e = launch_mfma<1, 2>(p, lds, ctx->stream, ev0, ev1); break;
+          case 2: e = launch_mfma<2, 2>(p, lds, ctx->stream, ev0, ev1); break;
+          case 3: e = launch_mfma<3, 2>(p, lds, ctx->stream, ev0, ev1); break;
+          default: e = launch_mfma<4, 2>(p, lds, ctx->stream, ev0, ev1); break;
         }
       }
       CTCSPEC_HIP(ctx, e);
-      if (ctx->lm_profile) {
-        CTCSPEC_HIP(ctx, hipEventRecord(ctx->lm_ev1, ctx->stream));
-        ctx->lm_profile_valid = 1;
-      }
+      if (ctx->lm_profile) ctx->lm_profile_valid = 1;
       launch_merge(p, ctx->stream);
       CTCSPEC_HIP(ctx, hipGetLastError());
       return CTCSPEC_OK;
