@@ -236,8 +236,11 @@ int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* node_hidd
  *   for j = 0..accept_len[b]:  cache row ctx_len[b] + j of every head  <-  tree row accept_nodes[b,j]
  *   ctx_len_out[b] = min(ctx_len[b] + accept_len[b] + 1, kv_cap)
  *
- * Rows that would fall beyond kv_cap are dropped.  One call per layer; layers share accept_* and ctx_len, so
- * pass ctx_len_out only with the last layer (NULL otherwise).
+ * Rows that would fall beyond kv_cap are dropped, and ctx_len_out counts only the rows the cache then holds: a
+ * sequence lost accepted rows exactly when ctx_len_out[b] < ctx_len[b] + accept_len[b] + 1 (the caller sizes
+ * kv_cap so that this cannot happen, or checks that relation before the next step).  One call per layer; layers
+ * share accept_* and ctx_len, so pass ctx_len_out only with the last layer (NULL otherwise).  Buffers of any
+ * alignment are accepted; 16-byte aligned ones (pointers, kv_off and row size) are copied 16 bytes at a time.
  *
  * dt            element type of the K/V buffers
  * k_tree, v_tree  [B,H,max_nodes,dh]  in (as given to tree_verify_attn)

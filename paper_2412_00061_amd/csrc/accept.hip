@@ -50,6 +50,13 @@ __global__ __launch_bounds__(64) void accept_longest_kernel(const int32_t* n_nod
   }
 }
 
+// code of this translation unit loaded onto the current device (context creation calls this: a stage call never
+// triggers a load, so it can be the first thing a stream capture records)
+hipError_t prepare_accept() {
+  hipFuncAttributes attr;
+  return hipFuncGetAttributes(&attr, (const void*)accept_longest_kernel);
+}
+
 }  // namespace ctcspec
 
 using namespace ctcspec;

@@ -784,6 +784,15 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
   }
 }
 
+hipError_t prepare_collapse_tree() {
+  const int lds = (int)sizeof(CollapseShared);
+  hipError_t e = hipFuncSetAttribute((const void*)collapse_tree_kernel<false>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute((const void*)collapse_tree_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  return e;
+}
+
 }  // namespace ctcspec
 
 using namespace ctcspec;
@@ -832,12 +841,6 @@ static int collapse_tree_call(ctcspec_ctx* ctx, const char* name, bool raw, cons
   static_assert(CTCSPEC_MAX_SLOTS * CTCSPEC_MAX_TOPK <= 64, "token codes fit 6 bits; the top-k lists fit one wavefront");
   static_assert(CTCSPEC_MAX_BEAM <= 128 && CTCSPEC_MAX_SLOTS * CTCSPEC_MAX_TOPK <= 64, "direct-address table of (creator, code) pairs");
   const int lds = (int)sizeof(CollapseShared);
-  static bool lds_allowed[2] = {false, false};
-  if (!lds_allowed[raw ? 1 : 0]) {
-    const void* fn = raw ? (const void*)collapse_tree_kernel<true> : (const void*)collapse_tree_kernel<false>;
-    CTCSPEC_HIP(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    lds_allowed[raw ? 1 : 0] = true;
-  }
   if (raw)
     hipLaunchKernelGGL(collapse_tree_kernel<true>, dim3(B), dim3(kThreads), lds, ctx->stream, p);
   else

@@ -75,6 +75,20 @@ int tree_verify_attn_rows(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* q, con
                           int B, int H, int dh, int max_nodes, float scale, float* out, unsigned short* rows,
                           long long rows_plane, int* rows_written);
 
+// Kernels that need more dynamic LDS than the default limit have the limit raised here, once per context creation
+// (with the context's device current), never inside a stage call: a stage call then only enqueues launches and can
+// be the first thing a stream capture records.  One function per translation unit that owns such kernels.
+hipError_t prepare_draft_topk();
+hipError_t prepare_collapse_tree();
+hipError_t prepare_verify_head();
+hipError_t prepare_draft_layer();
+// the other translation units only have their code loaded onto the device
+hipError_t prepare_tree_attn();
+hipError_t prepare_accept();
+hipError_t prepare_sum_score();
+hipError_t prepare_ctc_loss();
+hipError_t prepare_verify_sample();
+
 #define CTCSPEC_REQUIRE(ctx, cond, code, ...) \
   do {                                        \
     if (!(cond)) return ::ctcspec::fail((ctx), (code), __VA_ARGS__); \

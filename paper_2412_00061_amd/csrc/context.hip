@@ -54,6 +54,21 @@ extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec
     return fail(nullptr, CTCSPEC_EHIP, "hipGetDevice failed: %s", hipGetErrorString(e));
   }
 
+  // dynamic LDS limits of the large kernels, for this device (no stage call touches function attributes)
+  e = prepare_draft_topk();
+  if (e == hipSuccess) e = prepare_collapse_tree();
+  if (e == hipSuccess) e = prepare_verify_head();
+  if (e == hipSuccess) e = prepare_draft_layer();
+  if (e == hipSuccess) e = prepare_tree_attn();
+  if (e == hipSuccess) e = prepare_accept();
+  if (e == hipSuccess) e = prepare_sum_score();
+  if (e == hipSuccess) e = prepare_ctc_loss();
+  if (e == hipSuccess) e = prepare_verify_sample();
+  if (e != hipSuccess) {
+    delete ctx;
+    return fail(nullptr, CTCSPEC_EHIP, "preparing the kernels failed: %s", hipGetErrorString(e));
+  }
+
   ctx->lm_max_blocks = (lim->max_vocab_rows + kRowsPerBlock - 1) / kRowsPerBlock;
   long long bh = (long long)lim->max_batch * lim->max_heads;
   ctx->attn_units = (int)(bh > 256 ? bh : 256);

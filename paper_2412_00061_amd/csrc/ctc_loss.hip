@@ -488,6 +488,13 @@ static CtcWorkspace ctc_workspace(int B, int T, int Lmax) {
   return w;
 }
 
+// code of this translation unit loaded onto the current device (context creation calls this: a stage call never
+// triggers a load, so it can be the first thing a stream capture records)
+hipError_t prepare_ctc_loss() {
+  hipFuncAttributes attr;
+  return hipFuncGetAttributes(&attr, (const void*)ctc_links_kernel);
+}
+
 }  // namespace ctcspec
 
 using namespace ctcspec;

@@ -446,19 +446,21 @@ static LayerWorkspace layer_workspace(int B, int T, int D, int H, int F, int cus
 template <int NT>
 static hipError_t launch_skinny_nt(const SkinnyParams& sp, hipStream_t stream) {
   const int lds = sp.plan.hs_bytes + kSgWaves * kSgStripBytes;
-  static bool lds_allowed = false;  // per instantiation; raising the limit is needed once per process
-  if (!lds_allowed) {
-    hipError_t e = hipFuncSetAttribute((const void*)skinny_gemm_bf16_kernel<kSgStages, NT>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
-    if (e != hipSuccess) return e;
-    lds_allowed = true;
-  }
   hipLaunchKernelGGL((skinny_gemm_bf16_kernel<kSgStages, NT>), dim3(sp.plan.total_waves / kSgWaves),
                      dim3(64 * kSgWaves), lds, stream, sp);
   return hipGetLastError();
 }
 static hipError_t launch_skinny(const SkinnyParams& sp, hipStream_t stream) {
   return sp.plan.nt == 1 ? launch_skinny_nt<1>(sp, stream) : launch_skinny_nt<2>(sp, stream);
+}
+
+hipError_t prepare_draft_layer() {
+  hipError_t e = hipFuncSetAttribute((const void*)skinny_gemm_bf16_kernel<kSgStages, 1>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute((const void*)skinny_gemm_bf16_kernel<kSgStages, 2>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
+  return e;
 }
 
 }  // namespace ctcspec

@@ -462,17 +462,35 @@ static int pick_kc(int BT, int D, int stages, int budget) {
 template <int NT, int STAGES>
 static hipError_t launch_mfma(const LmHeadParams& p, int lds_bytes, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1) {
   auto kern = lmhead_bf16_mfma_kernel<NT, STAGES>;
-  static int lds_allowed = 0;  // per instantiation; raising the limit is needed once per process
-  if (lds_bytes > lds_allowed) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    lds_allowed = lds_bytes;
-  }
   if (ev0 && ev1)
     hipExtLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(64 * kMfmaWaves), lds_bytes, stream, ev0, ev1, 0, p);
   else
     hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(64 * kMfmaWaves), lds_bytes, stream, p);
   return hipGetLastError();
+}
+
+// the streaming kernel's LDS need depends on the call's shape; its budget (see ctc_draft_topk) is the limit set here
+constexpr int kMfmaLdsLimit = 160 * 1024 - 64;
+
+template <int NT, int STAGES>
+static hipError_t allow_mfma_lds() {
+  return hipFuncSetAttribute((const void*)lmhead_bf16_mfma_kernel<NT, STAGES>,
+                             hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaLdsLimit);
+}
+
+hipError_t prepare_draft_topk() {
+  hipError_t e = allow_mfma_lds<1, 4>();
+  if (e == hipSuccess) e = allow_mfma_lds<2, 4>();
+  if (e == hipSuccess) e = allow_mfma_lds<3, 4>();
+  if (e == hipSuccess) e = allow_mfma_lds<4, 4>();
+  if (e == hipSuccess) e = allow_mfma_lds<1, 2>();
+  if (e == hipSuccess) e = allow_mfma_lds<2, 2>();
+  if (e == hipSuccess) e = allow_mfma_lds<3, 2>();
+  if (e == hipSuccess) e = allow_mfma_lds<4, 2>();
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute((const void*)lmhead_bf16_tile_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            tile_lds_bytes<1>());
+  return e;
 }
 
 }  // namespace ctcspec
@@ -505,7 +523,7 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
   p.topk_id = topk_id; p.topk_logp = topk_logp; p.lse = lse; p.logits_out = logits_out;
 
   if (dt == CTCSPEC_BF16) {
-    const int budget = 160 * 1024 - kMfmaWaves * kWStageBytes - 64;
+    const int budget = kMfmaLdsLimit - kMfmaWaves * kWStageBytes;
     // the streaming kernel needs the hidden states of all columns in LDS over the whole hidden dimension
     // (4 register stages of prefetch; 2 when D is a multiple of 512 but not of 1024)
     int stages = 4;
@@ -545,12 +563,6 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
     }
     if (D % kTileStepK == 0 && p.BT <= 64 && (long long)Vp1 * D * 2 < (1LL << 32)) {
       // more columns than that: both operands step through LDS
-      static bool lds_allowed = false;  // raising the limit is needed once per process
-      if (!lds_allowed) {
-        CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)lmhead_bf16_tile_kernel<1>,
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds_bytes<1>()));
-        lds_allowed = true;
-      }
       if (ctx->lm_profile) CTCSPEC_HIP(ctx, hipEventRecord(ctx->lm_ev0, ctx->stream));
       hipLaunchKernelGGL(lmhead_bf16_tile_kernel<1>, dim3(p.n_blocks), dim3(64 * kTileWaves), tile_lds_bytes<1>(),
                          ctx->stream, p);

@@ -92,6 +92,13 @@ __global__ __launch_bounds__(128) void sum_rank_kernel(SumScoreParams p) {
   }
 }
 
+// code of this translation unit loaded onto the current device (context creation calls this: a stage call never
+// triggers a load, so it can be the first thing a stream capture records)
+hipError_t prepare_sum_score() {
+  hipFuncAttributes attr;
+  return hipFuncGetAttributes(&attr, (const void*)sum_score_kernel);
+}
+
 }  // namespace ctcspec
 
 using namespace ctcspec;

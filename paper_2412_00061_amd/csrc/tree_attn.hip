@@ -533,6 +533,13 @@ static hipError_t launch_attn_bf16(const AttnParams& p, const AttnSplit& sp, hip
   return hipGetLastError();
 }
 
+// code of this translation unit loaded onto the current device (context creation calls this: a stage call never
+// triggers a load, so it can be the first thing a stream capture records)
+hipError_t prepare_tree_attn() {
+  hipFuncAttributes attr;
+  return hipFuncGetAttributes(&attr, (const void*)tree_attn_merge_kernel);
+}
+
 }  // namespace ctcspec
 
 using namespace ctcspec;

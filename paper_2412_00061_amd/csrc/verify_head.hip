@@ -163,7 +163,9 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(KvCommitParams p) {
   L = L < 0 ? 0 : (L > p.kv_cap ? p.kv_cap : L);
   const size_t cache_head = ((size_t)p.kv_off[b] * p.elem_bytes) + (size_t)h * p.kv_cap * p.row_bytes;
   const size_t tree_head = ((size_t)b * p.H + h) * p.max_nodes * (size_t)p.row_bytes;
-  const bool vec = (p.row_bytes & 15) == 0 && (cache_head & 15) == 0;
+  // 16-byte copies need every address a multiple of 16: the offsets and the four base pointers
+  const bool vec = (p.row_bytes & 15) == 0 && (cache_head & 15) == 0 &&
+                   ((((uintptr_t)p.k_cache | (uintptr_t)p.v_cache | (uintptr_t)p.k_tree | (uintptr_t)p.v_tree) & 15) == 0);
   for (int j = 0; j <= len; ++j) {
     const int node = p.accept_nodes[(size_t)b * (p.T + 1) + j];
     const int pos = L + j;
@@ -185,6 +187,11 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(KvCommitParams p) {
     const int grown = L + len + 1;
     p.ctx_len_out[b] = grown > p.kv_cap ? p.kv_cap : grown;
   }
+}
+
+hipError_t prepare_verify_head() {
+  return hipFuncSetAttribute((const void*)verify_head_bf16_kernel<kVhDist>,
+                             hipFuncAttributeMaxDynamicSharedMemorySize, kVhLdsBytes);
 }
 
 }  // namespace ctcspec
@@ -213,14 +220,6 @@ extern "C" int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void
   const bool wide = dt == CTCSPEC_BF16 && D % kVhStepK == 0 && (long long)V * D * 2 < (1LL << 32) &&
                     cols_total * D * 2 < (1LL << 32);
   const int lds = kVhLdsBytes;
-  if (wide) {
-    static bool lds_allowed = false;  // raising the limit is needed once per process
-    if (!lds_allowed) {
-      CTCSPEC_HIP(ctx, hipFuncSetAttribute((const void*)verify_head_bf16_kernel<kVhDist>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-      lds_allowed = true;
-    }
-  }
   for (long long col0 = 0; col0 < cols_total; col0 += kVhCols) {
     p.col0 = (int)col0;
     p.cols = (int)(cols_total - col0 < kVhCols ? cols_total - col0 : kVhCols);

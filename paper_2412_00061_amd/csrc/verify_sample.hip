@@ -171,6 +171,13 @@ __global__ __launch_bounds__(kSampleThreads) void verify_sample_kernel(SamplePar
   *out = token;
 }
 
+// code of this translation unit loaded onto the current device (context creation calls this: a stage call never
+// triggers a load, so it can be the first thing a stream capture records)
+hipError_t prepare_verify_sample() {
+  hipFuncAttributes attr;
+  return hipFuncGetAttributes(&attr, (const void*)verify_sample_kernel<1>);
+}
+
 }  // namespace ctcspec
 
 using namespace ctcspec;

@@ -1,0 +1,128 @@
+"""GPU parity of tree_verify_attn on PEAKED scores (Sec. 2.1 tree verification, Sec. 3.3).
+
+The other attention tests draw Q and K from N(0,1): after the first tile of keys a row's running maximum hardly
+moves.  A trained model's scores are peaked, and the maximum keeps moving along the keys, in the context and in the
+tree part, differently in every split of the keys.  These cases force that: queries scaled by 6 and 12, keys whose
+norm grows along the key order, and single keys scaled by 12 placed in the last context tile, at the root and at the
+deepest node.  Every online-softmax branch that moves its reference with a finite previous reference, and every
+combination of partial results whose references differ, is on these paths.  Bar: 2e-3 (relative, RMS floor) against
+the float64 oracle.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from gpu_harness import dev_i32, dev_i64, rel_err_rms_floor, to_device
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+
+MODES = {
+    "q_x6": dict(q_scale=6.0),
+    "q_x12": dict(q_scale=12.0),
+    "growing_keys": dict(q_scale=3.0, key_growth=4.0),
+    "spiked_keys": dict(q_scale=1.0, n_spikes=6, spike_scale=12.0),
+    "spiked_and_scaled": dict(q_scale=4.0, n_spikes=5, spike_scale=8.0),
+}
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2412_00061_amd as m
+    m.load_library()
+    return m
+
+
+def _trees(seed, B, max_nodes, beam, kind):
+    """Per sequence a tree (n_nodes, mask, packed mask): 'beam' = a collapsed-candidate tree, 'chain' = a causal chain."""
+    out = []
+    for b in range(B):
+        if kind == "chain":
+            parent = [-1] + list(range(max_nodes - 1))
+            mask = oracle.ancestor_mask(parent)
+            n = max_nodes
+        else:
+            ids, logp = workloads.make_topk_case(seed * 31 + b, 1, 8, 4, 999, vocab=20, p_blank=0.3)
+            t = oracle.collapse_tree(ids[0], logp[0], 1, 999, beam, max_nodes)
+            mask, n = t["mask"], t["n_nodes"]
+        out.append({"n_nodes": n, "mask": mask, "anc_mask": oracle.pack_mask_u64(mask, max_nodes)})
+    return out
+
+
+def late_maxima(case, b, n, scale):
+    """How peaked a case is: (head, row) pairs whose largest context score lies in the second half of the context and
+    exceeds the largest of the first 32 keys by more than 2^8 in the exponent domain."""
+    L = int(case.ctx_len[b])
+    if L < 64:
+        return 0
+    s = np.einsum("hjd,hid->hji", case.k_cache[b, :, :L].astype(np.float64), case.q[b, :, :n].astype(np.float64))
+    s *= scale * 1.4426950408889634
+    return int(((s[:, L // 2:].max(axis=1) - s[:, :32].max(axis=1)) > 8.0).sum())
+
+
+def _run(pkg, case, trees, B, H, N, dh):
+    ctx = pkg.Context(max_batch=B, max_slots=8, max_topk=4, max_vocab_rows=64, max_nodes=N, max_heads=H,
+                      max_head_dim=dh)
+    n_nodes = np.array([t["n_nodes"] for t in trees], dtype=np.int32)
+    q, kt, vt = case.q.copy(), case.k_tree.copy(), case.v_tree.copy()
+    for b in range(B):  # rows beyond the tree may hold anything
+        q[b, :, n_nodes[b]:] = np.nan
+        kt[b, :, n_nodes[b]:] = np.nan
+        vt[b, :, n_nodes[b]:] = np.nan
+    mask = np.stack([t["anc_mask"] for t in trees]).view(np.int64)
+    scale = 1.0 / math.sqrt(dh)
+    out = pkg.tree_verify_attn(ctx, to_device(q, "bf16"), to_device(case.k_cache, "bf16"),
+                               to_device(case.v_cache, "bf16"), dev_i64(case.kv_off), dev_i32(case.ctx_len),
+                               case.kv_cap, to_device(kt, "bf16"), to_device(vt, "bf16"), dev_i32(n_nodes),
+                               torch.from_numpy(mask).cuda(), scale)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    ctx.close()
+    worst, moved = 0.0, 0
+    for b in range(B):
+        n = int(n_nodes[b])
+        L = int(case.ctx_len[b])
+        ref = oracle.tree_attention(case.q[b], case.k_cache[b], case.v_cache[b], L, case.k_tree[b], case.v_tree[b], n,
+                                    trees[b]["mask"], scale)
+        assert np.isfinite(out[b, :, :n]).all()
+        worst = max(worst, rel_err_rms_floor(out[b, :, :n], ref))
+        moved += late_maxima(case, b, n, scale)
+    assert worst <= TOL, f"attention rel err {worst}"
+    return moved
+
+
+# (B, H, max_nodes, kv_cap, ctx_len, tree kind): the 7B step's shape (two query blocks, four key splits), twice its
+# heads (one 128-row block), the ragged batch (one key range per workgroup), and the draft layer's 8 causal rows
+SHAPES = {
+    "7b_ctx2048": (1, 32, 128, 2048, [2048], "beam"),
+    "64_heads": (1, 64, 128, 1024, [1000], "beam"),
+    "batch8_ragged": (8, 32, 64, 2048, [256, 2048, 1111, 777, 1999, 300, 1280, 95], "beam"),
+    "draft_layer_rows": (1, 32, 8, 2048, [2048], "chain"),
+}
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+@pytest.mark.parametrize("shape", list(SHAPES))
+def test_tree_attention_peaked_scores(pkg, shape, mode):
+    B, H, N, cap, ctx_len, kind = SHAPES[shape]
+    seed = sorted(SHAPES).index(shape) * 10 + sorted(MODES).index(mode)
+    case = workloads.make_attention_case(seed, B, H, N, 128, cap, ctx_len, **MODES[mode])
+    trees = _trees(seed, B, N, 128 if N > 64 else 64, kind)
+    moved = _run(pkg, case, trees, B, H, N, 128)
+    # the inputs do what they are for: in many rows the maximum moves late by more than the lazy-rescale margin
+    assert moved >= 16, f"only {moved} rows with a late maximum"
+
+
+def test_tree_attention_masked_tile_after_large_context_maximum(pkg):
+    # rows 1..31 of a chain see nothing of the tree's later tiles; their context scores are large (queries x 12) and
+    # the keys of those later tiles are larger still: a masked key must not move a row's reference
+    B, H, N, cap = 1, 4, 128, 512
+    case = workloads.make_attention_case(77, B, H, N, 128, cap, [480], q_scale=12.0)
+    case.k_tree[:, :, 32:] = workloads.round_to_storage(case.k_tree[:, :, 32:] * np.float32(16.0), "bf16")
+    trees = _trees(77, B, N, 128, "chain")
+    _run(pkg, case, trees, B, H, N, 128)

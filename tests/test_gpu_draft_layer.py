@@ -6,9 +6,11 @@ attention step, whose queries, keys and values have the cache's storage type.  T
 half of the layer to 2e-3 (relative, RMS floor) on its own:
   * q, k_new, v_new against the oracle's first half, plus the storage rounding of bf16 (half an ulp: 2^-8);
   * the output against the oracle's second half run on the very q, k_new, v_new the kernel stored.
-End to end against the float64 oracle the storage rounding of q/k/v passes through the attention and the output
-projection about one to one: 2e-3 + 2^-8 there.  The bf16 output must be the rounding of the fp32 output bit
-for bit, and a second call must reproduce every output bit for bit.
+These two halves ARE the parity bar.  The end-to-end comparison against the float64 oracle that follows them is a
+derived bound, kept as a sanity check and not as the bar: the oracle keeps q/k/v in float64 where the method's
+cache stores bf16, and that storage rounding (half a bf16 ulp, 2^-8) passes through the attention and the output
+projection about one to one, so 2e-3 + 2^-8 is what the two halves together imply.  The bf16 output must be the
+rounding of the fp32 output bit for bit, and a second call must reproduce every output bit for bit.
 """
 import numpy as np
 import pytest
@@ -20,8 +22,9 @@ from gpu_harness import rel_err_rms_floor
 from workloads.device import dev_i32, dev_i64, to_device
 
 pytestmark = pytest.mark.gpu
-TOL = 2e-3
-TOL_BF16 = 2e-3 + 2.0 ** -8
+TOL = 2e-3                           # the parity bar, for each half of the layer
+TOL_BF16 = 2e-3 + 2.0 ** -8          # values that exist in bf16 only (q, k, v): the bar plus half a bf16 ulp
+E2E_DERIVED_BOUND = 2e-3 + 2.0 ** -8  # end to end: what the two halves imply (a sanity check, not the bar)
 
 
 @pytest.fixture(scope="module")
@@ -67,7 +70,7 @@ def _check(pkg, seed, B, T, D, H, F, ctx_len, cap):
         assert rel_err_rms_floor(y32[b], y_chained) <= TOL, (b, rel_err_rms_floor(y32[b], y_chained))
         y, _, _ = oracle.draft_layer(c.x[b], c.weights, int(c.pos0[b]), c.k_cache[b], c.v_cache[b],
                                      int(c.ctx_len[b]), H, c.eps, c.theta)
-        assert rel_err_rms_floor(y32[b], y) <= TOL_BF16, (b, rel_err_rms_floor(y32[b], y))
+        assert rel_err_rms_floor(y32[b], y) <= E2E_DERIVED_BOUND, (b, rel_err_rms_floor(y32[b], y))
     assert np.array_equal(ybf, workloads.round_to_storage(y32, "bf16"))
     # same bits on a second call (the partial tiles are added in a fixed order), with or without the fp32 copy
     for name in ("out", "k_new", "v_new"):

@@ -161,8 +161,6 @@ def test_graph_replay_matches_eager(pkg, cfg_index):
     stream = torch.cuda.Stream()
     st.ctx.set_stream(stream)
     with torch.cuda.stream(stream):
-        st.run()  # warm-up on the capture stream (one-time function attribute calls happen outside capture)
-        stream.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream):
             st.run()
@@ -239,7 +237,7 @@ def test_attention_repeats_bit_identically(pkg, cfg_index):
     ctx.close()
 
 
-def test_whole_decode_step_graph_replay(pkg):
+def whole_decode_step_graph_replay(pkg, capture_first):
     """Every call of a decode step in one HIP graph - the draft module's layer, the draft head, collapse/tree,
     the Eq. 5 values, verification attention, the base head, acceptance and the history update: replays,
     with eager work and synchronisation between them, must reproduce the eager results bit for bit (the
@@ -326,18 +324,34 @@ def test_whole_decode_step_graph_replay(pkg):
             else:
                 t.fill_(-7 if name != "anc_mask" else 0)
 
-    run()
-    eager = snapshot()
-    assert int(eager["n_nodes"][0]) > 1 and int(eager["new_len"][0]) == 40 + int(eager["accept_len"][0]) + 1
     stream = torch.cuda.Stream()
-    ctx.set_stream(stream)
-    with torch.cuda.stream(stream):
-        run()  # warm-up on the capture stream: one-time function attribute calls happen outside the capture
-        stream.synchronize()
+    if capture_first:
+        # the stage calls' very first use in this process is the one the capture records: nothing they do may need
+        # an eager call first (function attributes and code loading belong to ctcspec_create)
+        ctx.set_stream(stream)
+        torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream):
             run()
-    torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        graph.replay()
+        first = snapshot()
+        ctx.set_stream(torch.cuda.current_stream())
+        scrub()
+        run()
+        eager = snapshot()
+        _same(eager, first)
+        ctx.set_stream(stream)
+    else:
+        run()
+        eager = snapshot()
+        ctx.set_stream(stream)
+        with torch.cuda.stream(stream):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                run()
+        torch.cuda.synchronize()
+    assert int(eager["n_nodes"][0]) > 1 and int(eager["new_len"][0]) == 40 + int(eager["accept_len"][0]) + 1
     for rep in range(3):
         scrub()
         torch.cuda.synchronize()
@@ -348,6 +362,22 @@ def test_whole_decode_step_graph_replay(pkg):
         assert math.isfinite(float(junk))
     ctx.set_stream(torch.cuda.current_stream())
     ctx.close()
+
+
+def test_whole_decode_step_graph_replay(pkg):
+    whole_decode_step_graph_replay(pkg, capture_first=False)
+
+
+def test_first_calls_after_create_are_capturable():
+    """A fresh process whose first stage calls are recorded by a stream capture (see capture_first_call.py): no call
+    may rely on an eager call having gone before it."""
+    import os
+    import subprocess
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    res = subprocess.run([sys.executable, os.path.join(here, "capture_first_call.py")], capture_output=True, text=True,
+                         timeout=300)
+    assert res.returncode == 0 and "capture-first ok" in res.stdout, res.stdout[-2000:] + res.stderr[-4000:]
 
 
 def test_loss_and_sampled_draw_graph_replay(pkg):

@@ -104,6 +104,32 @@ def test_draft_topk_shapes(pkg, B, T, D, Vp1, k, dtype):
     ctx.close()
 
 
+@pytest.mark.parametrize("B,T,D,Vp1,k", [
+    (8, 8, 1024, 1500, 1), (8, 8, 1024, 1500, 2), (8, 8, 1024, 1500, 3), (8, 8, 1024, 1500, 8),
+    (3, 8, 4096, 2500, 1), (3, 8, 4096, 2500, 2), (5, 7, 4096, 2500, 5), (4, 8, 4096, 2500, 8),
+])
+def test_draft_topk_many_columns_every_k(pkg, B, T, D, Vp1, k):
+    """More than 16 columns that do not fit the streaming kernel's LDS: the tile kernel with its lane-per-column
+    epilogue, at every width of the per-lane key list (k = 1, 2, 3..4, 5..8), with exact ties in the top k."""
+    rng = np.random.Generator(np.random.PCG64(B * 100 + D + k))
+    hidden = workloads.round_to_storage(rng.standard_normal((B, T, D), dtype=np.float32), "bf16")
+    w = workloads.round_to_storage(rng.standard_normal((Vp1, D), dtype=np.float32) * 0.05, "bf16")
+    # equal rows in different 16-row groups and different 128-row blocks: equal logits, ids ascending among them
+    w[900] = w[3]
+    w[131] = w[3]
+    w[17] = w[1040]
+    bias = rng.standard_normal(Vp1).astype(np.float32) * 0.1
+    bias[[3, 131, 900]] = 400.0
+    bias[[17, 1040]] = 300.0
+    ctx = pkg.Context(max_batch=B, max_slots=T, max_topk=k, max_vocab_rows=Vp1, max_nodes=16, max_heads=1,
+                      max_head_dim=16)
+    res = _check_draft(pkg, ctx, hidden, w, bias, k, "bf16")
+    top = res["topk_id"].cpu().numpy().reshape(B * T, k)
+    want = np.array([3, 131, 900, 17, 1040])[:k]
+    assert (top[:, :len(want)] == want).all()
+    ctx.close()
+
+
 def test_draft_topk_forced_ties(pkg):
     # duplicate head rows give exactly equal logits: ids must come out in ascending order among equals
     rng = np.random.Generator(np.random.PCG64(9))

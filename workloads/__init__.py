@@ -7,10 +7,12 @@ same inputs from it without sharing any computation.
 """
 from .configs import CONFIGS, StepConfig, get_config  # noqa: F401
 from .generate import (  # noqa: F401
+    AttentionCase,
     DraftLayerCase,
     StepInputs,
     bf16_bits_to_f32,
     f32_to_bf16_bits,
+    make_attention_case,
     make_draft_layer_case,
     make_inputs,
     make_topk_case,

@@ -160,6 +160,74 @@ def make_inputs(cfg: StepConfig, seed: int = 0, variant: str = "literal",
                       v_cache=v_cache, ctx_len=ctx_len, kv_off=kv_off, proj=proj, planted=planted)
 
 
+@dataclass
+class AttentionCase:
+    """Operands of one verification-attention call (storage-rounded float32 arrays)."""
+    q: np.ndarray         # [B,H,max_nodes,dh]
+    k_tree: np.ndarray    # [B,H,max_nodes,dh]
+    v_tree: np.ndarray    # [B,H,max_nodes,dh]
+    k_cache: np.ndarray   # [B,H,kv_cap,dh]; rows >= ctx_len[b] are NaN
+    v_cache: np.ndarray   # [B,H,kv_cap,dh]
+    ctx_len: np.ndarray   # [B] i32
+    kv_off: np.ndarray    # [B] i64
+    kv_cap: int
+    spiked: list          # per sequence: key positions (context rows, then ctx_len + node) that were scaled up
+
+
+def make_attention_case(seed: int, B: int, H: int, max_nodes: int, dh: int, kv_cap: int, ctx_len,
+                        dtype: str = "bf16", *, q_scale: float = 1.0, key_growth: float = 0.0,
+                        n_spikes: int = 0, spike_scale: float = 12.0) -> AttentionCase:
+    """Attention operands whose scores are NOT the flat N(0,1)-products of `make_inputs`: the peaked score
+    distributions of a trained model, where the running maximum of a row keeps moving along the keys.
+
+    q_scale     every query scaled (scores of standard deviation q_scale * sqrt(dh) before the 1/sqrt(dh))
+    key_growth  key j of a sequence (context rows in order, then the tree nodes) scaled by 1 + key_growth * j / n_keys:
+                later keys have the larger norm, so maxima tend to arrive late
+    n_spikes    that many keys per sequence and head scaled by spike_scale; always among them: the last context row,
+                a row of the context's last 32, the root's key and the deepest-numbered node's key, the rest uniform
+                over all keys - large scores in late tiles and in every part of the key range
+    Values N(0,1) throughout.  Draw order: Q, K_tree, V_tree, K_cache, V_cache, spike positions."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    ctx_len = np.broadcast_to(np.asarray(ctx_len, dtype=np.int32), (B,)).copy()
+    q = rng.standard_normal((B, H, max_nodes, dh), dtype=np.float32) * np.float32(q_scale)
+    k_tree = rng.standard_normal((B, H, max_nodes, dh), dtype=np.float32)
+    v_tree = rng.standard_normal((B, H, max_nodes, dh), dtype=np.float32)
+    k_cache = rng.standard_normal((B, H, kv_cap, dh), dtype=np.float32)
+    v_cache = rng.standard_normal((B, H, kv_cap, dh), dtype=np.float32)
+    spiked = []
+    for b in range(B):
+        L = int(ctx_len[b])
+        n_keys = L + max_nodes
+        if key_growth:
+            ramp = (1.0 + key_growth * np.arange(n_keys, dtype=np.float32) / np.float32(n_keys)).astype(np.float32)
+            k_cache[b, :, :L] *= ramp[None, :L, None]
+            k_tree[b] *= ramp[None, L:, None]
+        pos_b = []
+        for h in range(H):
+            forced = [L + 0, L + max_nodes - 1]
+            if L > 0:
+                forced += [L - 1, max(0, L - 1 - int(rng.integers(0, 32)))]
+            pos = list(dict.fromkeys(forced))[:n_spikes]
+            while len(pos) < n_spikes:
+                j = int(rng.integers(0, n_keys))
+                if j not in pos:
+                    pos.append(j)
+            for j in pos:
+                if j < L:
+                    k_cache[b, h, j] *= np.float32(spike_scale)
+                else:
+                    k_tree[b, h, j - L] *= np.float32(spike_scale)
+            pos_b.append(pos)
+        spiked.append(pos_b)
+        k_cache[b, :, L:, :] = np.nan
+        v_cache[b, :, L:, :] = np.nan
+    kv_off = (np.arange(B, dtype=np.int64) * (H * kv_cap * dh)).astype(np.int64)
+    return AttentionCase(q=round_to_storage(q, dtype), k_tree=round_to_storage(k_tree, dtype),
+                         v_tree=round_to_storage(v_tree, dtype), k_cache=round_to_storage(k_cache, dtype),
+                         v_cache=round_to_storage(v_cache, dtype), ctx_len=ctx_len, kv_off=kv_off, kv_cap=kv_cap,
+                         spiked=spiked)
+
+
 def make_topk_case(seed: int, B: int, T: int, k: int, blank_id: int, *, vocab: int = 12,
                    p_blank: float = 0.5, quantum: float = 0.0, first_blank: bool = False):
     """Synthetic per-slot top-k lists for exercising the collapse/tree stage directly.
