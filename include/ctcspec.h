@@ -50,6 +50,7 @@ enum {
 #define CTCSPEC_MAX_NODES 128      /* tree nodes per sequence, root included */
 #define CTCSPEC_MAX_COLUMNS 64     /* B*T columns of one draft-head call */
 #define CTCSPEC_MAX_HEAD_DIM 128
+#define CTCSPEC_NOALLOC_MAX_VOCAB_ROWS 65536 /* V+1 of ctc_draft_topk_noalloc */
 
 /* Sizes the context's workspace is dimensioned for.  Calls that exceed them fail with
  * CTCSPEC_EUNSUPPORTED. */
@@ -75,7 +76,8 @@ void ctcspec_destroy(ctcspec_ctx* ctx);
 int ctcspec_set_stream(ctcspec_ctx* ctx, void* hip_stream);
 
 /* Static, NUL-terminated description of the last error on this context ("" if none).  With
- * ctx == NULL: the reason the last ctcspec_create failed in this thread. */
+ * ctx == NULL: the reason the last call without a context (ctcspec_create, ctc_draft_topk_noalloc) failed in this
+ * thread. */
 const char* ctcspec_last_error(const ctcspec_ctx* ctx);
 
 /* Bytes of device workspace the context holds. */
@@ -117,6 +119,26 @@ int ctcspec_draft_head_kernel_ms(ctcspec_ctx* ctx, float* ms);
 int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hidden, const void* w,
                    const float* bias, int B, int T, int D, int Vp1, int k, int32_t* topk_id,
                    float* topk_logp, float* lse, float* logits_out);
+
+/*
+ * ctc_draft_topk_noalloc - ctc_draft_topk for callers that cannot allocate device memory and therefore cannot create
+ * a context: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation,
+ * same kernels, same outputs bit for bit; it takes the stream instead of a context and keeps its partial results
+ * (per 128 vocabulary rows and column: max, sum of exponentials, k best keys) in a device array that is part of the
+ * library's own code object, so that no call of it, first or later, allocates or frees anything (neither through
+ * HIP nor through any other library).
+ *
+ * hip_stream   a hipStream_t (NULL = the default stream); host value
+ * every other argument as for ctc_draft_topk
+ * Limits: Vp1 <= CTCSPEC_NOALLOC_MAX_VOCAB_ROWS (larger heads are rejected with CTCSPEC_EUNSUPPORTED: use a context),
+ * B*T <= CTCSPEC_MAX_COLUMNS, k <= CTCSPEC_MAX_TOPK, T <= CTCSPEC_MAX_SLOTS.  The array (2.4 MB) exists once per GPU
+ * for the life of the process, and every call on a GPU uses it: calls that overlap on one GPU (two streams, two
+ * threads) race on it; calls in stream order are safe and need no clearing between them (every entry a call reads
+ * it has written first).  Errors are reported through ctcspec_last_error(NULL).
+ */
+int ctc_draft_topk_noalloc(void* hip_stream, ctcspec_dtype dt, const void* hidden, const void* w,
+                           const float* bias, int B, int T, int D, int Vp1, int k, int32_t* topk_id,
+                           float* topk_logp, float* lse, float* logits_out);
 
 /*
  * Stage 3 - CTC transform and token tree (paper Sec. 3.1 "CTC Transform Module", Sec. 3.3; collapse

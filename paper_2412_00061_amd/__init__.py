@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     accept_longest,
     ctc_collapse_tree,
     ctc_draft_topk,
+    ctc_draft_topk_noalloc,
     ctc_loss,
     verify_sample_tokens,
     ctc_loss_workspace_bytes,

@@ -17,6 +17,7 @@ EXPORTS = (
     "ctcspec_workspace_bytes", "ctcspec_profile_draft_head", "ctcspec_draft_head_kernel_ms", "ctc_draft_topk", "ctc_collapse_tree", "tree_verify_attn",
     "accept_longest", "verify_head_argmax", "kv_commit", "draft_layer_workspace_bytes", "draft_layer_forward",
     "ctc_sum_score", "ctc_raw_tree", "ctc_loss_workspace_bytes", "ctc_loss", "verify_sample_tokens",
+    "ctc_draft_topk_noalloc",
 )
 
 CTCSPEC_F32, CTCSPEC_BF16 = 0, 1
@@ -67,6 +68,8 @@ def load_library():
     lib.ctc_draft_topk.restype = c_int
     lib.ctc_draft_topk.argtypes = [c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int,
                                    c_int, c_int, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.ctc_draft_topk_noalloc.restype = c_int
+    lib.ctc_draft_topk_noalloc.argtypes = list(lib.ctc_draft_topk.argtypes)
     lib.ctc_collapse_tree.restype = c_int
     lib.ctc_collapse_tree.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int32,
                                       c_int, c_int] + [c_void_p] * 10
@@ -229,6 +232,27 @@ def ctc_draft_topk(ctx, hidden, w, bias, k, *, want_logits=False, out=None):
                                 _ptr(res["topk_logp"]), _ptr(res["lse"]), _ptr(res.get("logits")))
     ctx._check(rc, "ctc_draft_topk")
     return res
+
+
+def ctc_draft_topk_noalloc(stream, hidden, w, bias, k, *, out, want_logits=False):
+    """The same call without a context (the library's static scratch holds the partial results).  `stream`: a
+    torch.cuda.Stream or None; `out` must hold every output tensor (this binding allocates nothing either)."""
+    B, T, D = hidden.shape
+    Vp1 = w.shape[0]
+    if w.shape[1] != D or w.dtype != hidden.dtype:
+        raise CtcspecError("w must be [V+1, D] with hidden's dtype")
+    for name, shape, dtype in (("topk_id", (B, T, k), torch.int32), ("topk_logp", (B, T, k), torch.float32),
+                               ("lse", (B, T), torch.float32)) + ((("logits", (B, T, Vp1), torch.float32),) if want_logits else ()):
+        if name not in out or tuple(out[name].shape) != shape or out[name].dtype != dtype:
+            raise CtcspecError(f"out[{name!r}] must be a {dtype} tensor of shape {shape}")
+    lib = load_library()
+    rc = lib.ctc_draft_topk_noalloc(c_void_p(stream.cuda_stream if stream is not None else 0), _dtype_code(hidden),
+                                    _ptr(hidden), _ptr(w), _ptr(bias, torch.float32), B, T, D, Vp1, k,
+                                    _ptr(out["topk_id"]), _ptr(out["topk_logp"]), _ptr(out["lse"]),
+                                    _ptr(out["logits"]) if want_logits else None)
+    if rc != 0:
+        raise CtcspecError(f"ctc_draft_topk_noalloc failed ({rc}): {lib.ctcspec_last_error(None).decode()}")
+    return out
 
 
 def ctc_collapse_tree(ctx, topk_id, topk_logp, root_token, blank_id, beam, max_nodes, *, out=None):

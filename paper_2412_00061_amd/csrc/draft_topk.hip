@@ -15,6 +15,7 @@
 //                                operands stepping through LDS
 //   * lmhead_generic_kernel    - any dtype/shape within the limits, plain fp32 FMA
 // All hand the block over in LDS to the same epilogue.
+#include <mutex>
 #include <type_traits>
 #include <utility>
 
@@ -478,7 +479,8 @@ static hipError_t allow_mfma_lds() {
                              hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaLdsLimit);
 }
 
-hipError_t prepare_draft_topk() {
+// dynamic LDS limits of this file's kernels, on the current device
+static hipError_t allow_large_lds() {
   hipError_t e = allow_mfma_lds<1, 4>();
   if (e == hipSuccess) e = allow_mfma_lds<2, 4>();
   if (e == hipSuccess) e = allow_mfma_lds<3, 4>();
@@ -493,34 +495,80 @@ hipError_t prepare_draft_topk() {
   return e;
 }
 
+// ---- scratch of the entry point that allocates nothing ------------------------------------------------------------
+// The same partial results that ctc_draft_topk keeps in its context's workspace, in a device array of the library
+// itself: [256 bytes of zeros][pmax][psum][pkey] for up to kStaticMaxBlocks row blocks.  Every GPU the library
+// runs on holds its own copy (2.4 MB) at its own address until the process ends.
+constexpr int kStaticMaxBlocks = CTCSPEC_NOALLOC_MAX_VOCAB_ROWS / kRowsPerBlock;
+constexpr size_t kScratchZeros = 0;
+constexpr size_t kScratchPmax = 256;
+constexpr size_t kScratchPsum = kScratchPmax + (size_t)kStaticMaxBlocks * kMaxCols * sizeof(float);
+constexpr size_t kScratchPkey = kScratchPsum + (size_t)kStaticMaxBlocks * kMaxCols * sizeof(float);
+constexpr size_t kScratchBytes = kScratchPkey + (size_t)kStaticMaxBlocks * kMaxCols * kMaxTopk * sizeof(unsigned long long);
+static_assert(CTCSPEC_NOALLOC_MAX_VOCAB_ROWS % kRowsPerBlock == 0 && kScratchPkey % 256 == 0, "scratch layout");
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+// In host code `scratch` is only a handle for the runtime, not a device address: the address on each device comes
+// from hipGetSymbolAddress, once per device, and host code uses that pointer everywhere.
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static unsigned char* g_scratch_ptr[kMaxDevices];
+
+static hipError_t scratch_of_current_device(unsigned char** out, bool* first_use) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (first_use) *first_use = false;
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = (unsigned char*)ptr;
+    if (first_use) *first_use = true;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+hipError_t prepare_draft_topk() {
+  // set-up of the allocation-free entry point on this device: address of its scratch, zeros block cleared (the
+  // array starts out zeroed and no kernel writes that block; clearing it here costs nothing)
+  unsigned char* sp = nullptr;
+  hipError_t e = scratch_of_current_device(&sp, nullptr);
+  if (e == hipSuccess) e = hipMemset(sp + kScratchZeros, 0, 256);
+  if (e != hipSuccess) return e;
+  return allow_large_lds();
+}
+
 }  // namespace ctcspec
 
 using namespace ctcspec;
 
-extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hidden, const void* w,
-                              const float* bias, int B, int T, int D, int Vp1, int k, int32_t* topk_id,
-                              float* topk_logp, float* lse, float* logits_out) {
-  if (!ctx) return CTCSPEC_EINVAL;
-  CTCSPEC_REQUIRE(ctx, hidden && w && topk_id && topk_logp, CTCSPEC_EINVAL, "ctc_draft_topk: null pointer");
-  CTCSPEC_REQUIRE(ctx, dt == CTCSPEC_F32 || dt == CTCSPEC_BF16, CTCSPEC_EINVAL, "ctc_draft_topk: bad dtype");
-  CTCSPEC_REQUIRE(ctx, B > 0 && T > 0 && D > 0 && Vp1 > 0 && k > 0, CTCSPEC_EINVAL,
-                  "ctc_draft_topk: sizes must be positive");
-  CTCSPEC_REQUIRE(ctx, aligned16(hidden) && aligned16(w), CTCSPEC_EINVAL,
-                  "ctc_draft_topk: hidden and w must be 16-byte aligned");
-  CTCSPEC_REQUIRE(ctx, (long long)B * T <= kMaxCols, CTCSPEC_EUNSUPPORTED, "ctc_draft_topk: B*T=%lld > %d",
-                  (long long)B * T, kMaxCols);
-  CTCSPEC_REQUIRE(ctx, B <= ctx->lim.max_batch && T <= ctx->lim.max_slots && k <= ctx->lim.max_topk &&
-                           Vp1 <= ctx->lim.max_vocab_rows,
-                  CTCSPEC_EUNSUPPORTED, "ctc_draft_topk: shape exceeds the context's limits");
-  CTCSPEC_REQUIRE(ctx, k <= Vp1, CTCSPEC_EINVAL, "ctc_draft_topk: k=%d > vocabulary rows %d", k, Vp1);
+// Everything ctc_draft_topk does after its argument checks: producer kernel, then the merge kernel.  `err` receives
+// error texts (NULL: the thread's context-less error slot); ev0/ev1 non-null: time the producer kernel; *timed is
+// set when they were used.
+struct LmScratch {
+  float* pmax;
+  float* psum;
+  unsigned long long* pkey;
+  const void* zeros;
+};
 
+static int draft_topk_launch(ctcspec_ctx* err, hipStream_t stream, const LmScratch& sc, hipEvent_t ev0, hipEvent_t ev1,
+                             int* timed, ctcspec_dtype dt, const void* hidden, const void* w, const float* bias, int B,
+                             int T, int D, int Vp1, int k, int32_t* topk_id, float* topk_logp, float* lse,
+                             float* logits_out) {
   LmHeadParams p;
   p.hidden = hidden; p.w = w; p.bias = bias;
   p.BT = B * T; p.D = D; p.Vp1 = Vp1; p.k = k;
-  p.KC = 0; p.hs_bytes = 0; p.hs_magic = 0; p.zeros = ctx->zeros;
+  p.KC = 0; p.hs_bytes = 0; p.hs_magic = 0; p.zeros = sc.zeros;
   p.n_blocks = (Vp1 + kRowsPerBlock - 1) / kRowsPerBlock;
-  p.pmax = ctx->lm_pmax; p.psum = ctx->lm_psum; p.pkey = ctx->lm_pkey;
+  p.pmax = sc.pmax; p.psum = sc.psum; p.pkey = sc.pkey;
   p.topk_id = topk_id; p.topk_logp = topk_logp; p.lse = lse; p.logits_out = logits_out;
+  const bool timing = ev0 && ev1;
 
   if (dt == CTCSPEC_BF16) {
     const int budget = kMfmaLdsLimit - kMfmaWaves * kWStageBytes;
@@ -539,48 +587,104 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
       int lds = p.hs_bytes + kMfmaWaves * kWStageBytes;
       int nt = (p.BT + 15) / 16;
       hipError_t e;
-      hipEvent_t ev0 = ctx->lm_profile ? ctx->lm_ev0 : nullptr, ev1 = ctx->lm_profile ? ctx->lm_ev1 : nullptr;
       if (stages == 4) {
         switch (nt) {
-          case 1: e = launch_mfma<1, 4>(p, lds, ctx->stream, ev0, ev1); break;
-          case 2: e = launch_mfma<2, 4>(p, lds, ctx->stream, ev0, ev1); break;
-          case 3: e = launch_mfma<3, 4>(p, lds, ctx->stream, ev0, ev1); break;
-          default: e = launch_mfma<4, 4>(p, lds, ctx->stream, ev0, ev1); break;
+          case 1: e = launch_mfma<1, 4>(p, lds, stream, ev0, ev1); break;
+          case 2: e = launch_mfma<2, 4>(p, lds, stream, ev0, ev1); break;
+          case 3: e = launch_mfma<3, 4>(p, lds, stream, ev0, ev1); break;
+          default: e = launch_mfma<4, 4>(p, lds, stream, ev0, ev1); break;
         }
       } else {
         switch (nt) {
-          case 1: e = launch_mfma<1, 2>(p, lds, ctx->stream, ev0, ev1); break;
-          case 2: e = launch_mfma<2, 2>(p, lds, ctx->stream, ev0, ev1); break;
-          case 3: e = launch_mfma<3, 2>(p, lds, ctx->stream, ev0, ev1); break;
-          default: e = launch_mfma<4, 2>(p, lds, ctx->stream, ev0, ev1); break;
+          case 1: e = launch_mfma<1, 2>(p, lds, stream, ev0, ev1); break;
+          case 2: e = launch_mfma<2, 2>(p, lds, stream, ev0, ev1); break;
+          case 3: e = launch_mfma<3, 2>(p, lds, stream, ev0, ev1); break;
+          default: e = launch_mfma<4, 2>(p, lds, stream, ev0, ev1); break;
         }
       }
-      CTCSPEC_HIP(ctx, e);
-      if (ctx->lm_profile) ctx->lm_profile_valid = 1;
-      launch_merge(p, ctx->stream);
-      CTCSPEC_HIP(ctx, hipGetLastError());
+      CTCSPEC_HIP(err, e);
+      if (timing && timed) *timed = 1;
+      launch_merge(p, stream);
+      CTCSPEC_HIP(err, hipGetLastError());
       return CTCSPEC_OK;
     }
     if (D % kTileStepK == 0 && p.BT <= 64 && (long long)Vp1 * D * 2 < (1LL << 32)) {
       // more columns than that: both operands step through LDS
-      if (ctx->lm_profile) CTCSPEC_HIP(ctx, hipEventRecord(ctx->lm_ev0, ctx->stream));
+      if (timing) CTCSPEC_HIP(err, hipEventRecord(ev0, stream));
       hipLaunchKernelGGL(lmhead_bf16_tile_kernel<1>, dim3(p.n_blocks), dim3(64 * kTileWaves), tile_lds_bytes<1>(),
-                         ctx->stream, p);
-      CTCSPEC_HIP(ctx, hipGetLastError());
-      if (ctx->lm_profile) {
-        CTCSPEC_HIP(ctx, hipEventRecord(ctx->lm_ev1, ctx->stream));
-        ctx->lm_profile_valid = 1;
+                         stream, p);
+      CTCSPEC_HIP(err, hipGetLastError());
+      if (timing) {
+        CTCSPEC_HIP(err, hipEventRecord(ev1, stream));
+        if (timed) *timed = 1;
       }
-      launch_merge(p, ctx->stream);
-      CTCSPEC_HIP(ctx, hipGetLastError());
+      launch_merge(p, stream);
+      CTCSPEC_HIP(err, hipGetLastError());
       return CTCSPEC_OK;
     }
-    hipLaunchKernelGGL(lmhead_generic_kernel<unsigned short>, dim3(p.n_blocks), dim3(256), 0, ctx->stream, p);
+    hipLaunchKernelGGL(lmhead_generic_kernel<unsigned short>, dim3(p.n_blocks), dim3(256), 0, stream, p);
   } else {
-    hipLaunchKernelGGL(lmhead_generic_kernel<float>, dim3(p.n_blocks), dim3(256), 0, ctx->stream, p);
+    hipLaunchKernelGGL(lmhead_generic_kernel<float>, dim3(p.n_blocks), dim3(256), 0, stream, p);
   }
-  CTCSPEC_HIP(ctx, hipGetLastError());
-  launch_merge(p, ctx->stream);
-  CTCSPEC_HIP(ctx, hipGetLastError());
+  CTCSPEC_HIP(err, hipGetLastError());
+  launch_merge(p, stream);
+  CTCSPEC_HIP(err, hipGetLastError());
   return CTCSPEC_OK;
+}
+
+// argument checks shared by the two entry points (`name` prefixes the messages)
+static int draft_topk_check(ctcspec_ctx* err, const char* name, ctcspec_dtype dt, const void* hidden, const void* w,
+                            int B, int T, int D, int Vp1, int k, const int32_t* topk_id, const float* topk_logp) {
+  CTCSPEC_REQUIRE(err, hidden && w && topk_id && topk_logp, CTCSPEC_EINVAL, "%s: null pointer", name);
+  CTCSPEC_REQUIRE(err, dt == CTCSPEC_F32 || dt == CTCSPEC_BF16, CTCSPEC_EINVAL, "%s: bad dtype", name);
+  CTCSPEC_REQUIRE(err, B > 0 && T > 0 && D > 0 && Vp1 > 0 && k > 0, CTCSPEC_EINVAL, "%s: sizes must be positive", name);
+  CTCSPEC_REQUIRE(err, aligned16(hidden) && aligned16(w), CTCSPEC_EINVAL, "%s: hidden and w must be 16-byte aligned",
+                  name);
+  CTCSPEC_REQUIRE(err, (long long)B * T <= kMaxCols, CTCSPEC_EUNSUPPORTED, "%s: B*T=%lld > %d", name, (long long)B * T,
+                  kMaxCols);
+  CTCSPEC_REQUIRE(err, k <= Vp1, CTCSPEC_EINVAL, "%s: k=%d > vocabulary rows %d", name, k, Vp1);
+  return CTCSPEC_OK;
+}
+
+extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hidden, const void* w,
+                              const float* bias, int B, int T, int D, int Vp1, int k, int32_t* topk_id,
+                              float* topk_logp, float* lse, float* logits_out) {
+  if (!ctx) return CTCSPEC_EINVAL;
+  const int rc = draft_topk_check(ctx, "ctc_draft_topk", dt, hidden, w, B, T, D, Vp1, k, topk_id, topk_logp);
+  if (rc != CTCSPEC_OK) return rc;
+  CTCSPEC_REQUIRE(ctx, B <= ctx->lim.max_batch && T <= ctx->lim.max_slots && k <= ctx->lim.max_topk &&
+                           Vp1 <= ctx->lim.max_vocab_rows,
+                  CTCSPEC_EUNSUPPORTED, "ctc_draft_topk: shape exceeds the context's limits");
+  const LmScratch sc = {ctx->lm_pmax, ctx->lm_psum, ctx->lm_pkey, ctx->zeros};
+  return draft_topk_launch(ctx, ctx->stream, sc, ctx->lm_profile ? ctx->lm_ev0 : nullptr,
+                           ctx->lm_profile ? ctx->lm_ev1 : nullptr, &ctx->lm_profile_valid, dt, hidden, w, bias, B, T, D,
+                           Vp1, k, topk_id, topk_logp, lse, logits_out);
+}
+
+extern "C" int ctc_draft_topk_noalloc(void* hip_stream, ctcspec_dtype dt, const void* hidden, const void* w,
+                                      const float* bias, int B, int T, int D, int Vp1, int k, int32_t* topk_id,
+                                      float* topk_logp, float* lse, float* logits_out) {
+  const char* name = "ctc_draft_topk_noalloc";
+  const int rc = draft_topk_check(nullptr, name, dt, hidden, w, B, T, D, Vp1, k, topk_id, topk_logp);
+  if (rc != CTCSPEC_OK) return rc;
+  CTCSPEC_REQUIRE(nullptr, Vp1 <= CTCSPEC_NOALLOC_MAX_VOCAB_ROWS, CTCSPEC_EUNSUPPORTED,
+                  "%s: %d vocabulary rows exceed the %d that the library's static scratch holds partial results for "
+                  "(use ctc_draft_topk with a context)",
+                  name, Vp1, CTCSPEC_NOALLOC_MAX_VOCAB_ROWS);
+  CTCSPEC_REQUIRE(nullptr, k <= CTCSPEC_MAX_TOPK && T <= CTCSPEC_MAX_SLOTS, CTCSPEC_EUNSUPPORTED,
+                  "%s: k <= %d and T <= %d required", name, CTCSPEC_MAX_TOPK, CTCSPEC_MAX_SLOTS);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  unsigned char* sp = nullptr;
+  bool first_use = false;
+  CTCSPEC_HIP(nullptr, scratch_of_current_device(&sp, &first_use));
+  if (first_use) {
+    // No context was ever created on this device, so the dynamic LDS limits were never raised: do it now (host-side
+    // attribute calls, no allocation).  The zeros block needs nothing: the array starts out zeroed and no kernel
+    // writes that block.
+    CTCSPEC_HIP(nullptr, allow_large_lds());
+  }
+  const LmScratch sc = {(float*)(sp + kScratchPmax), (float*)(sp + kScratchPsum),
+                        (unsigned long long*)(sp + kScratchPkey), sp + kScratchZeros};
+  return draft_topk_launch(nullptr, stream, sc, nullptr, nullptr, nullptr, dt, hidden, w, bias, B, T, D, Vp1, k, topk_id,
+                           topk_logp, lse, logits_out);
 }
