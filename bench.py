@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--kv-sets", type=int, default=32)
     ap.add_argument("--graph", action="store_true", help="replay the steps from a captured HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--deferred-merge", action="store_true",
+                    help="leave the merge of the draft head's partial results to the collapse/tree kernel's prologue "
+                         "(ctcspec_defer_topk_merge) instead of launching the merge kernel right behind the head")
     ap.add_argument("--attn-layers", type=int, default=-1,
                     help="layers of the full-depth variant line (attention called once per layer on its own "
                          "K/V/Q buffers); default: heads of the config (32 at 7B, 40 at 13B); 0: skip")
@@ -147,6 +150,7 @@ def main():
     torch.cuda.set_device(0)
     x = workloads.make_inputs(cfg, args.seed, args.variant)
     ctx = lib.Context.for_config(cfg)
+    ctx.defer_topk_merge(args.deferred_merge)
     B, T, k, N, H, dh = cfg.B, cfg.T, cfg.k, cfg.max_nodes, cfg.H, cfg.dh
     scale = 1.0 / math.sqrt(dh)
     dt = CTCSPEC_BF16 if cfg.dtype == "bf16" else CTCSPEC_F32
@@ -588,7 +592,9 @@ def main():
                                f"beam={cfg.beam} max_nodes={N} H={H} dh={dh} ctx={x.ctx_len.tolist()}",
                    "variant": args.variant, "seed": args.seed, "n_nodes": n_nodes.tolist(),
                    "accepted_plus_bonus": (accepted + 1).tolist(),
-                   "w_copies": len(d_w), "kv_sets": len(sets), "launch": "hip_graph" if graph is not None else "eager"},
+                   "w_copies": len(d_w), "kv_sets": len(sets), "launch": "hip_graph" if graph is not None else "eager",
+                   "draft_head_merge": "deferred to the collapse/tree kernel's prologue" if args.deferred_merge else
+                                       "in its own kernel"},
         "us_per_step": us_per_step,
         "step_algorithmic_bytes": total_b,
         "step_hbm_gbps": total_b / (us_per_step * 1e-6) / 1e9,

@@ -83,6 +83,18 @@ const char* ctcspec_last_error(const ctcspec_ctx* ctx);
 /* Bytes of device workspace the context holds. */
 size_t ctcspec_workspace_bytes(const ctcspec_ctx* ctx);
 
+/* Deferred merge of the draft head.  ctc_draft_topk runs one pass over the head weights that leaves a partial
+ * result per 128 vocabulary rows, and a small second kernel that merges them into topk_id / topk_logp / lse.  With
+ * enable != 0 that second kernel is not launched: the three outputs stay OWED until the next call on this context -
+ *   - ctc_collapse_tree given exactly those topk_id / topk_logp buffers (same B*T, k <= 4) merges the partials in the
+ *     prologue of its own kernel and writes the three outputs as well: one dispatch and one trip through memory
+ *     fewer per decoding step, same bits;
+ *   - any other library call on the context, ctcspec_set_stream and ctcspec_flush launch the merge kernel first.
+ * A caller that reads the three outputs from the stream with code of its own right after ctc_draft_topk must call
+ * ctcspec_flush first, or leave the mode off (the default).  ctcspec_destroy drops an unsettled debt. */
+int ctcspec_defer_topk_merge(ctcspec_ctx* ctx, int enable);
+int ctcspec_flush(ctcspec_ctx* ctx);
+
 /* Measurement aid.  With enable != 0, every following ctc_draft_topk call attaches a pair of HIP events
  * to the launch of its main kernel on the context's stream (the pass over the head weights, not the
  * small merge kernel): the events take that kernel's begin and end timestamps.  (The many-column and

@@ -17,7 +17,7 @@ EXPORTS = (
     "ctcspec_workspace_bytes", "ctcspec_profile_draft_head", "ctcspec_draft_head_kernel_ms", "ctc_draft_topk", "ctc_collapse_tree", "tree_verify_attn",
     "accept_longest", "verify_head_argmax", "kv_commit", "draft_layer_workspace_bytes", "draft_layer_forward",
     "ctc_sum_score", "ctc_raw_tree", "ctc_loss_workspace_bytes", "ctc_loss", "verify_sample_tokens",
-    "ctc_draft_topk_noalloc",
+    "ctc_draft_topk_noalloc", "ctcspec_defer_topk_merge", "ctcspec_flush",
 )
 
 CTCSPEC_F32, CTCSPEC_BF16 = 0, 1
@@ -61,6 +61,10 @@ def load_library():
     lib.ctcspec_last_error.argtypes = [c_void_p]
     lib.ctcspec_workspace_bytes.restype = c_size_t
     lib.ctcspec_workspace_bytes.argtypes = [c_void_p]
+    lib.ctcspec_defer_topk_merge.restype = c_int
+    lib.ctcspec_defer_topk_merge.argtypes = [c_void_p, c_int]
+    lib.ctcspec_flush.restype = c_int
+    lib.ctcspec_flush.argtypes = [c_void_p]
     lib.ctcspec_profile_draft_head.restype = c_int
     lib.ctcspec_profile_draft_head.argtypes = [c_void_p, c_int]
     lib.ctcspec_draft_head_kernel_ms.restype = c_int
@@ -150,6 +154,13 @@ class Context:
 
     def workspace_bytes(self) -> int:
         return int(self.lib.ctcspec_workspace_bytes(self.handle))
+
+    def defer_topk_merge(self, enable: bool):
+        """Leave the merge of the draft head's partial results to the next ctc_collapse_tree call (see ctcspec.h)."""
+        self._check(self.lib.ctcspec_defer_topk_merge(self.handle, 1 if enable else 0), "ctcspec_defer_topk_merge")
+
+    def flush(self):
+        self._check(self.lib.ctcspec_flush(self.handle), "ctcspec_flush")
 
     def profile_draft_head(self, enable: bool):
         self._check(self.lib.ctcspec_profile_draft_head(self.handle, 1 if enable else 0), "ctcspec_profile_draft_head")

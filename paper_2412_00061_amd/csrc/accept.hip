@@ -66,6 +66,7 @@ extern "C" int accept_longest(ctcspec_ctx* ctx, const int32_t* n_nodes, const in
                               const int32_t* target_argmax, int B, int T, int max_nodes, int32_t* accept_len,
                               int32_t* accept_nodes, int32_t* accept_tokens, int32_t* next_token) {
   if (!ctx) return CTCSPEC_EINVAL;
+  if (const int owed = flush_deferred(ctx)) return owed;
   (void)node_depth;  // the walk needs parents and tokens only; depth is accepted for symmetry with stage 3
   CTCSPEC_REQUIRE(ctx,
                   n_nodes && node_token && node_parent && target_argmax && accept_len && accept_nodes &&

@@ -24,7 +24,7 @@
 // otherwise (mass ties, or nearly every raw candidate needed).
 #include <type_traits>
 
-#include "common.h"
+#include "topk_merge.h"
 
 namespace ctcspec {
 
@@ -54,6 +54,14 @@ struct CollapseParams {
   unsigned long long* anc_mask;
   int32_t* node_removed;  // raw layout only
   unsigned char* ws;  // per-sequence global workspace base
+  // deferred merge of the draft head (MK > 0): its per-workgroup partials in, the lists that ctc_draft_topk owes out
+  const float* lm_pmax;
+  const float* lm_psum;
+  const unsigned long long* lm_pkey;
+  int lm_blocks, lm_stride;
+  int32_t* topk_id_out;
+  float* topk_logp_out;
+  float* lse_out;
 };
 
 struct CollapseShared {
@@ -355,7 +363,10 @@ __device__ __forceinline__ unsigned long long collapse_key(const CollapseShared&
   return key;
 }
 
-template <bool RAW>
+// MK > 0: the top-k lists do not exist yet - the draft head left only its per-workgroup partials, and this kernel's
+// wavefronts merge them first (two columns each, at most MK keys per list), write the lists out for the caller and
+// go on from LDS: one dispatch and one trip through memory fewer than a merge kernel in between.
+template <bool RAW, int MK>
 __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   CollapseShared& s = *reinterpret_cast<CollapseShared*>(smem_raw);
@@ -370,32 +381,68 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
   // the tree table is cleared by everybody while the first wavefront's loads are in flight
   int id = -1;
   float lp = 0.f;
-  if (wave == 0 && lane < TK) {
+  if constexpr (MK > 0) {
+    static_assert(CTCSPEC_MAX_SLOTS <= 2 * kWaves, "two columns per wavefront cover every slot");
+    const int col[2] = {wave < T ? b * T + wave : -1, wave + kWaves < T ? b * T + wave + kWaves : -1};
+    float lse[2];
+    unsigned long long best[2][MK];
+    merge_topk_columns<MK, 2>(p.lm_pmax, p.lm_psum, p.lm_pkey, p.lm_stride, p.lm_blocks, k, col, lse, best);
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      if (col[c] < 0) continue;
+      if (lane == 0 && p.lse_out) p.lse_out[col[c]] = lse[c];
+      if (lane < k) {
+        unsigned long long key = 0ull;
+#pragma unroll
+        for (int r = 0; r < MK; ++r) key = lane == r ? best[c][r] : key;
+        const int tok = (int)rank_key_index(key);
+        const float logp = rank_key_value(key) - lse[c];
+        p.topk_id_out[(size_t)col[c] * k + lane] = tok;
+        p.topk_logp_out[(size_t)col[c] * k + lane] = logp;
+        const int t = col[c] - b * T;
+        s.ids[t * k + lane] = tok;
+        s.logp[t * k + lane] = logp;
+      }
+    }
+  } else if (wave == 0 && lane < TK) {
     id = p.topk_id[(size_t)b * TK + lane];
     lp = p.topk_logp[(size_t)b * TK + lane];
   }
   for (int i = tid; i < 128 * 64 / 4; i += kThreads) reinterpret_cast<u32x4*>(s.tree_table)[i] = u32x4{0u, 0u, 0u, 0u};
+  if constexpr (MK > 0) {
+    __syncthreads();  // the merged lists are in LDS
+  } else if (wave == 0) {
+    if (lane < TK) {
+      s.ids[lane] = id;
+      s.logp[lane] = lp;
+    }
+    // the same wavefront reads the lists back below: its LDS operations execute in order, the compiler must not
+    // reorder them either
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    __builtin_amdgcn_wave_barrier();
+  }
   if (wave == 0) {
-    int cd = lane;  // code = position of the first entry with the same token id
+    // local token code = position of the first entry with the same token id.  Every lane scans the lists in LDS
+    // (all lanes read the same address: a broadcast), reads batched eight at a time - as a chain of readlane steps
+    // this phase cost as much as the sort after it.
+    if (MK > 0 && lane < TK) id = s.ids[lane];
+    int cd = lane;
+#pragma unroll 8
     for (int j = 0; j < TK; ++j) {
-      const int idj = __builtin_amdgcn_readlane(id, j);
-      if (idj == id && j < cd) cd = j;
+      const int idj = s.ids[j];
+      cd = (idj == id && j < cd) ? j : cd;
     }
     // delta bounds |fl(X+Y) - exact score|: both are sums of the same T terms, each addition off by
     // at most 2^-24 of a partial sum, partial sums bounded by A = sum_t max_j |logp[t,j]|.
     // 14 * 2^-24 * A would do; 16 * 2^-23 * A leaves room for rounding of the thresholds themselves.
+    float mx = 0.f;  // lane t < T: max_j |logp[t,j]|
+    if (lane < T)
+      for (int j = 0; j < k; ++j) mx = fmaxf(mx, fabsf(s.logp[lane * k + j]));
     float A = 0.f;
-    for (int t = 0; t < T; ++t) {
-      float mx = 0.f;
-      for (int j = 0; j < k; ++j)
-        mx = fmaxf(mx, fabsf(__uint_as_float(readlane_u32(__float_as_uint(lp), t * k + j))));
-      A += mx;
-    }
-    if (lane < TK) {
-      s.ids[lane] = id;
-      s.logp[lane] = lp;
-      s.code[lane] = (!RAW && id == p.blank_id) ? kBlankCode : cd;
-    }
+#pragma unroll
+    for (int t = 0; t < CTCSPEC_MAX_SLOTS; ++t)
+      if (t < T) A += __uint_as_float(readlane_u32(__float_as_uint(mx), t));
+    if (lane < TK) s.code[lane] = (!RAW && id == p.blank_id) ? kBlankCode : cd;
     if (lane == 0) s.delta = A * (16.0f / 8388608.0f);
     if (RAW) {
       const unsigned long long has = __ballot(lane < TK && id == p.blank_id);
@@ -784,12 +831,18 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
   }
 }
 
+// the deferred merge is built into the kernel for lists of up to this many keys (the workloads' k = 4)
+constexpr int kFusedMergeK = 4;
+
 hipError_t prepare_collapse_tree() {
   const int lds = (int)sizeof(CollapseShared);
-  hipError_t e = hipFuncSetAttribute((const void*)collapse_tree_kernel<false>,
+  hipError_t e = hipFuncSetAttribute((const void*)collapse_tree_kernel<false, 0>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess)
-    e = hipFuncSetAttribute((const void*)collapse_tree_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    e = hipFuncSetAttribute((const void*)collapse_tree_kernel<true, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute((const void*)collapse_tree_kernel<false, kFusedMergeK>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   return e;
 }
 
@@ -841,10 +894,31 @@ static int collapse_tree_call(ctcspec_ctx* ctx, const char* name, bool raw, cons
   static_assert(CTCSPEC_MAX_SLOTS * CTCSPEC_MAX_TOPK <= 64, "token codes fit 6 bits; the top-k lists fit one wavefront");
   static_assert(CTCSPEC_MAX_BEAM <= 128 && CTCSPEC_MAX_SLOTS * CTCSPEC_MAX_TOPK <= 64, "direct-address table of (creator, code) pairs");
   const int lds = (int)sizeof(CollapseShared);
-  if (raw)
-    hipLaunchKernelGGL(collapse_tree_kernel<true>, dim3(B), dim3(kThreads), lds, ctx->stream, p);
-  else
-    hipLaunchKernelGGL(collapse_tree_kernel<false>, dim3(B), dim3(kThreads), lds, ctx->stream, p);
+  // A deferred ctc_draft_topk call may still owe its lists.  If they are the very lists given here, this launch
+  // settles the debt itself (the kernel merges the draft head's partials first and writes the lists out);
+  // otherwise the merge kernel runs now.
+  bool fused = false;
+  if (ctx->lm_pending) {
+    if (!raw && ctx->lm_owed.topk_id == topk_id && ctx->lm_owed.topk_logp == topk_logp && ctx->lm_owed.BT == B * T &&
+        ctx->lm_owed.k == k && k <= kFusedMergeK) {
+      fused = true;
+      ctx->lm_pending = 0;
+    } else if (const int owed = flush_deferred(ctx)) {
+      return owed;
+    }
+  }
+  p.lm_pmax = nullptr; p.lm_psum = nullptr; p.lm_pkey = nullptr; p.lm_blocks = 0; p.lm_stride = 0;
+  p.topk_id_out = nullptr; p.topk_logp_out = nullptr; p.lse_out = nullptr;
+  if (fused) {
+    p.lm_pmax = ctx->lm_pmax; p.lm_psum = ctx->lm_psum; p.lm_pkey = ctx->lm_pkey; p.lm_blocks = ctx->lm_owed.n_blocks;
+    p.lm_stride = ctx->lm_max_blocks;
+    p.topk_id_out = ctx->lm_owed.topk_id; p.topk_logp_out = ctx->lm_owed.topk_logp; p.lse_out = ctx->lm_owed.lse;
+    hipLaunchKernelGGL((collapse_tree_kernel<false, kFusedMergeK>), dim3(B), dim3(kThreads), lds, ctx->stream, p);
+  } else if (raw) {
+    hipLaunchKernelGGL((collapse_tree_kernel<true, 0>), dim3(B), dim3(kThreads), lds, ctx->stream, p);
+  } else {
+    hipLaunchKernelGGL((collapse_tree_kernel<false, 0>), dim3(B), dim3(kThreads), lds, ctx->stream, p);
+  }
   CTCSPEC_HIP(ctx, hipGetLastError());
   return CTCSPEC_OK;
 }

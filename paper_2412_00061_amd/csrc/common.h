@@ -43,9 +43,20 @@ struct ctcspec_ctx {
   size_t ws_bytes;
   // draft head
   int lm_max_blocks;
-  float* lm_pmax;               // [lm_max_blocks][kMaxCols]
-  float* lm_psum;               // [lm_max_blocks][kMaxCols]
-  unsigned long long* lm_pkey;  // [lm_max_blocks][kMaxCols][kMaxTopk]
+  // column-major, so that the merge reads each column's partials as contiguous runs over the workgroups
+  float* lm_pmax;               // [kMaxCols][lm_max_blocks]
+  float* lm_psum;               // [kMaxCols][lm_max_blocks]
+  unsigned long long* lm_pkey;  // [kMaxCols][kMaxTopk][lm_max_blocks]
+  // deferred merge (ctcspec_defer_topk_merge): a ctc_draft_topk call has left its per-workgroup partials in the
+  // workspace and owes the caller these outputs; the next call on the context settles the debt first
+  int lm_defer;
+  int lm_pending;
+  struct {
+    int BT, k, n_blocks;
+    int32_t* topk_id;
+    float* topk_logp;
+    float* lse;
+  } lm_owed;
   // optional timing of the draft-head kernel
   int lm_profile;               // events are recorded around the main kernel when non-zero
   int lm_profile_valid;
@@ -65,6 +76,10 @@ struct ctcspec_ctx {
 namespace ctcspec {
 
 int fail(ctcspec_ctx* ctx, int code, const char* fmt, ...);
+
+// Launches the merge kernel that a deferred ctc_draft_topk call still owes, if any.  Every entry point other than
+// ctc_collapse_tree calls this first; ctc_collapse_tree does so unless the owed lists are the very ones it is given.
+int flush_deferred(ctcspec_ctx* ctx);
 
 // tree_verify_attn with an optional second output form for callers inside the library: when `rows` is given and
 // the launch uses key splits, the merged result is written as rows [B*max_nodes][H*128] of two-bf16 values

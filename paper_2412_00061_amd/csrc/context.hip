@@ -147,8 +147,21 @@ extern "C" void ctcspec_destroy(ctcspec_ctx* ctx) {
   delete ctx;
 }
 
+extern "C" int ctcspec_defer_topk_merge(ctcspec_ctx* ctx, int enable) {
+  if (!ctx) return CTCSPEC_EINVAL;
+  if (const int owed = flush_deferred(ctx)) return owed;
+  ctx->lm_defer = enable ? 1 : 0;
+  return CTCSPEC_OK;
+}
+
+extern "C" int ctcspec_flush(ctcspec_ctx* ctx) {
+  if (!ctx) return CTCSPEC_EINVAL;
+  return flush_deferred(ctx);
+}
+
 extern "C" int ctcspec_set_stream(ctcspec_ctx* ctx, void* hip_stream) {
   if (!ctx) return CTCSPEC_EINVAL;
+  if (const int owed = flush_deferred(ctx)) return owed;  // on the stream the partials were produced on
   ctx->stream = (hipStream_t)hip_stream;
   return CTCSPEC_OK;
 }

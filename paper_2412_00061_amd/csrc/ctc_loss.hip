@@ -508,6 +508,7 @@ extern "C" int ctc_loss(ctcspec_ctx* ctx, const float* logits, const int32_t* la
                         const int32_t* frame_len, int B, int T, int Vp1, int Lmax, int32_t blank_id, void* workspace,
                         size_t workspace_bytes, float* loss, float* grad) {
   if (!ctx) return CTCSPEC_EINVAL;
+  if (const int owed = flush_deferred(ctx)) return owed;
   CTCSPEC_REQUIRE(ctx, logits && labels && label_len && frame_len && workspace && loss, CTCSPEC_EINVAL,
                   "ctc_loss: null pointer");
   CTCSPEC_REQUIRE(ctx, B > 0 && T > 0 && Vp1 > 0 && Lmax > 0, CTCSPEC_EINVAL, "ctc_loss: sizes must be positive");

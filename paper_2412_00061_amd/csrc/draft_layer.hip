@@ -478,6 +478,7 @@ extern "C" int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
                                    int T, int D, int H, int F, float rms_eps, float rope_theta, void* workspace,
                                    size_t workspace_bytes, void* q_out, void* k_new, void* v_new, void* out, float* out_f32) {
   if (!ctx) return CTCSPEC_EINVAL;
+  if (const int owed = flush_deferred(ctx)) return owed;
   CTCSPEC_REQUIRE(ctx, x && w && pos0 && k_cache && v_cache && kv_off && ctx_len && workspace && k_new && v_new && out,
                   CTCSPEC_EINVAL, "draft_layer_forward: null pointer");
   CTCSPEC_REQUIRE(ctx, w->ln1 && w->wqkv && w->wo && w->ln2 && w->wgu && w->wd, CTCSPEC_EINVAL,

@@ -22,6 +22,7 @@
 #include <hip/hip_ext.h>
 
 #include "gemm_tile.h"
+#include "topk_merge.h"
 
 namespace ctcspec {
 
@@ -40,37 +41,14 @@ struct LmHeadParams {
   unsigned int hs_magic;  // mfma kernel: ceil(2^32 / (KC / 8)), for index / (KC / 8) by multiplication
   int n_blocks;
   const void* zeros;  // tile kernel: 256 bytes of zeros
-  float* pmax;
-  float* psum;
-  unsigned long long* pkey;
+  float* pmax;              // [kMaxCols][pstride]
+  float* psum;              // [kMaxCols][pstride]
+  unsigned long long* pkey; // [kMaxCols][kMaxTopk][pstride]
+  int pstride;              // workgroups the partial arrays have room for
   int32_t* topk_id;
   float* topk_logp;
   float* lse;
   float* logits_out;
-};
-
-// Sorted (descending) register list of the best keys seen by one lane.
-template <int KMAX>
-struct KeyList {
-  unsigned long long v[KMAX];
-  __device__ __forceinline__ void clear() {
-#pragma unroll
-    for (int i = 0; i < KMAX; ++i) v[i] = 0ull;
-  }
-  __device__ __forceinline__ void insert(unsigned long long key) {
-#pragma unroll
-    for (int i = 0; i < KMAX; ++i) {
-      unsigned long long hi = key > v[i] ? key : v[i];
-      unsigned long long lo = key > v[i] ? v[i] : key;
-      v[i] = hi;
-      key = lo;
-    }
-  }
-  __device__ __forceinline__ void pop() {
-#pragma unroll
-    for (int i = 0; i + 1 < KMAX; ++i) v[i] = v[i + 1];
-    v[KMAX - 1] = 0ull;
-  }
 };
 
 // Epilogue shared by both producers.  zbuf holds the block's logits column-major:
@@ -101,10 +79,10 @@ __device__ void lmhead_block_epilogue(const LmHeadParams& p, const float* zbuf) 
     unsigned long long a = id0 < p.Vp1 ? rank_key(z0, (unsigned)id0) : 0ull;
     unsigned long long b = id1 < p.Vp1 ? rank_key(z1, (unsigned)id1) : 0ull;
     if (b > a) { unsigned long long t = a; a = b; b = t; }
-    size_t slot = (size_t)blockIdx.x * kMaxCols + m;
+    const size_t slot = (size_t)m * p.pstride + blockIdx.x;
     for (int r = 0; r < k; ++r) {
       unsigned long long best = wave_max_u64(a);
-      if (lane == 0) p.pkey[slot * kMaxTopk + r] = best;
+      if (lane == 0) p.pkey[((size_t)m * kMaxTopk + r) * p.pstride + blockIdx.x] = best;
       if (a == best) { a = b; b = 0ull; }
     }
     if (lane == 0) { p.pmax[slot] = mx; p.psum[slot] = s; }
@@ -170,58 +148,29 @@ __device__ void lmhead_block_epilogue_wide(const LmHeadParams& p, const float* z
 #pragma unroll
       for (int r = 0; r < KMAX; ++r) list.insert(pk[(w * kMaxCols + m) * KMAX + r]);
     }
-    const size_t slot = (size_t)blockIdx.x * kMaxCols + m;
+    const size_t slot = (size_t)m * p.pstride + blockIdx.x;
     p.pmax[slot] = m_run;
     p.psum[slot] = s_run;
-    for (int r = 0; r < p.k; ++r) p.pkey[slot * kMaxTopk + r] = r < KMAX ? list.v[r] : 0ull;
+    for (int r = 0; r < p.k; ++r)
+      p.pkey[((size_t)m * kMaxTopk + r) * p.pstride + blockIdx.x] = r < KMAX ? list.v[r] : 0ull;
   }
 }
 
-// Merge of the per-workgroup partials: one wavefront per column.  Lane l owns workgroups l, l+64, ...;
-// all of a lane's partials are requested before any is used, so the kernel costs about one memory
-// round trip.
+// Merge of the per-workgroup partials: one wavefront per column (the merge itself: topk_merge.h).
 template <int KMAX>
 __global__ __launch_bounds__(64) void lmhead_merge_kernel(LmHeadParams p) {
-  const int m = blockIdx.x, lane = threadIdx.x;
-  const int nb = p.n_blocks, k = p.k;
-  float m_run = -INFINITY, s_run = 0.f;
-  KeyList<KMAX> list;
-  list.clear();
-  for (int b0 = 0; b0 < nb; b0 += 256) {
-    float pm[4], ps[4];
-    unsigned long long pk[4][KMAX];
+  const int lane = threadIdx.x, k = p.k;
+  const int col[1] = {(int)blockIdx.x};
+  float lse[1];
+  unsigned long long best[1][KMAX];
+  merge_topk_columns<KMAX, 1>(p.pmax, p.psum, p.pkey, p.pstride, p.n_blocks, k, col, lse, best);
+  if (lane == 0 && p.lse) p.lse[col[0]] = lse[0];
+  if (lane < k) {
+    unsigned long long key = 0ull;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int b = b0 + u * 64 + lane;
-      const bool ok = b < nb;
-      const size_t slot = (size_t)(ok ? b : 0) * kMaxCols + m;
-      pm[u] = ok ? p.pmax[slot] : -INFINITY;
-      ps[u] = ok ? p.psum[slot] : 0.f;
-#pragma unroll
-      for (int r = 0; r < KMAX; ++r) pk[u][r] = (ok && r < k) ? p.pkey[slot * kMaxTopk + r] : 0ull;
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (pm[u] > -INFINITY) {
-        const float mn = fmaxf(m_run, pm[u]);
-        s_run = s_run * __expf(m_run - mn) + ps[u] * __expf(pm[u] - mn);
-        m_run = mn;
-      }
-#pragma unroll
-      for (int r = 0; r < KMAX; ++r) list.insert(pk[u][r]);
-    }
-  }
-  const float mx = wave_max_f32(m_run);
-  const float s = wave_sum_f32(m_run > -INFINITY ? s_run * __expf(m_run - mx) : 0.f);
-  const float lse = mx + __logf(s);
-  if (lane == 0 && p.lse) p.lse[m] = lse;
-  for (int r = 0; r < k; ++r) {
-    const unsigned long long best = wave_max_u64(list.v[0]);
-    if (list.v[0] == best) list.pop();
-    if (lane == 0) {
-      p.topk_id[m * k + r] = (int32_t)rank_key_index(best);
-      p.topk_logp[m * k + r] = rank_key_value(best) - lse;
-    }
+    for (int r = 0; r < KMAX; ++r) key = lane == r ? best[0][r] : key;
+    p.topk_id[col[0] * k + lane] = (int32_t)rank_key_index(key);
+    p.topk_logp[col[0] * k + lane] = rank_key_value(key) - lse[0];
   }
 }
 
@@ -448,6 +397,18 @@ static void launch_merge(const LmHeadParams& p, hipStream_t stream) {
   else hipLaunchKernelGGL(lmhead_merge_kernel<8>, dim3(p.BT), dim3(64), 0, stream, p);
 }
 
+int flush_deferred(ctcspec_ctx* ctx) {
+  if (!ctx->lm_pending) return CTCSPEC_OK;
+  ctx->lm_pending = 0;
+  LmHeadParams p = {};
+  p.BT = ctx->lm_owed.BT; p.k = ctx->lm_owed.k; p.n_blocks = ctx->lm_owed.n_blocks;
+  p.pmax = ctx->lm_pmax; p.psum = ctx->lm_psum; p.pkey = ctx->lm_pkey; p.pstride = ctx->lm_max_blocks;
+  p.topk_id = ctx->lm_owed.topk_id; p.topk_logp = ctx->lm_owed.topk_logp; p.lse = ctx->lm_owed.lse;
+  launch_merge(p, ctx->stream);
+  CTCSPEC_HIP(ctx, hipGetLastError());
+  return CTCSPEC_OK;
+}
+
 static int pick_kc(int BT, int D, int stages, int budget) {
   const int unit = 256 * stages;
   if (D % unit != 0) return 0;
@@ -497,7 +458,7 @@ static hipError_t allow_large_lds() {
 
 // ---- scratch of the entry point that allocates nothing ------------------------------------------------------------
 // The same partial results that ctc_draft_topk keeps in its context's workspace, in a device array of the library
-// itself: [256 bytes of zeros][pmax][psum][pkey] for up to kStaticMaxBlocks row blocks.  Every GPU the library
+// itself: [256 bytes of zeros][pmax][psum][pkey], the three laid out as in the context for kStaticMaxBlocks row blocks.  Every GPU the library
 // runs on holds its own copy (2.4 MB) at its own address until the process ends.
 constexpr int kStaticMaxBlocks = CTCSPEC_NOALLOC_MAX_VOCAB_ROWS / kRowsPerBlock;
 constexpr size_t kScratchZeros = 0;
@@ -554,11 +515,12 @@ struct LmScratch {
   float* pmax;
   float* psum;
   unsigned long long* pkey;
+  int pstride;
   const void* zeros;
 };
 
 static int draft_topk_launch(ctcspec_ctx* err, hipStream_t stream, const LmScratch& sc, hipEvent_t ev0, hipEvent_t ev1,
-                             int* timed, ctcspec_dtype dt, const void* hidden, const void* w, const float* bias, int B,
+                             int* timed, bool defer, ctcspec_dtype dt, const void* hidden, const void* w, const float* bias, int B,
                              int T, int D, int Vp1, int k, int32_t* topk_id, float* topk_logp, float* lse,
                              float* logits_out) {
   LmHeadParams p;
@@ -566,9 +528,22 @@ static int draft_topk_launch(ctcspec_ctx* err, hipStream_t stream, const LmScrat
   p.BT = B * T; p.D = D; p.Vp1 = Vp1; p.k = k;
   p.KC = 0; p.hs_bytes = 0; p.hs_magic = 0; p.zeros = sc.zeros;
   p.n_blocks = (Vp1 + kRowsPerBlock - 1) / kRowsPerBlock;
-  p.pmax = sc.pmax; p.psum = sc.psum; p.pkey = sc.pkey;
+  p.pmax = sc.pmax; p.psum = sc.psum; p.pkey = sc.pkey; p.pstride = sc.pstride;
   p.topk_id = topk_id; p.topk_logp = topk_logp; p.lse = lse; p.logits_out = logits_out;
   const bool timing = ev0 && ev1;
+  // defer: leave the partials and record what is owed (err is the context then); the collapse/tree kernel or
+  // flush_deferred does the merge
+  auto finish = [&]() -> int {
+    if (defer) {
+      err->lm_owed.BT = p.BT; err->lm_owed.k = p.k; err->lm_owed.n_blocks = p.n_blocks;
+      err->lm_owed.topk_id = topk_id; err->lm_owed.topk_logp = topk_logp; err->lm_owed.lse = lse;
+      err->lm_pending = 1;
+      return CTCSPEC_OK;
+    }
+    launch_merge(p, stream);
+    CTCSPEC_HIP(err, hipGetLastError());
+    return CTCSPEC_OK;
+  };
 
   if (dt == CTCSPEC_BF16) {
     const int budget = kMfmaLdsLimit - kMfmaWaves * kWStageBytes;
@@ -604,9 +579,7 @@ static int draft_topk_launch(ctcspec_ctx* err, hipStream_t stream, const LmScrat
       }
       CTCSPEC_HIP(err, e);
       if (timing && timed) *timed = 1;
-      launch_merge(p, stream);
-      CTCSPEC_HIP(err, hipGetLastError());
-      return CTCSPEC_OK;
+      return finish();
     }
     if (D % kTileStepK == 0 && p.BT <= 64 && (long long)Vp1 * D * 2 < (1LL << 32)) {
       // more columns than that: both operands step through LDS
@@ -618,18 +591,14 @@ static int draft_topk_launch(ctcspec_ctx* err, hipStream_t stream, const LmScrat
         CTCSPEC_HIP(err, hipEventRecord(ev1, stream));
         if (timed) *timed = 1;
       }
-      launch_merge(p, stream);
-      CTCSPEC_HIP(err, hipGetLastError());
-      return CTCSPEC_OK;
+      return finish();
     }
     hipLaunchKernelGGL(lmhead_generic_kernel<unsigned short>, dim3(p.n_blocks), dim3(256), 0, stream, p);
   } else {
     hipLaunchKernelGGL(lmhead_generic_kernel<float>, dim3(p.n_blocks), dim3(256), 0, stream, p);
   }
   CTCSPEC_HIP(err, hipGetLastError());
-  launch_merge(p, stream);
-  CTCSPEC_HIP(err, hipGetLastError());
-  return CTCSPEC_OK;
+  return finish();
 }
 
 // argument checks shared by the two entry points (`name` prefixes the messages)
@@ -650,15 +619,16 @@ extern "C" int ctc_draft_topk(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* hi
                               const float* bias, int B, int T, int D, int Vp1, int k, int32_t* topk_id,
                               float* topk_logp, float* lse, float* logits_out) {
   if (!ctx) return CTCSPEC_EINVAL;
+  if (const int owed = flush_deferred(ctx)) return owed;  // the partials are about to be overwritten
   const int rc = draft_topk_check(ctx, "ctc_draft_topk", dt, hidden, w, B, T, D, Vp1, k, topk_id, topk_logp);
   if (rc != CTCSPEC_OK) return rc;
   CTCSPEC_REQUIRE(ctx, B <= ctx->lim.max_batch && T <= ctx->lim.max_slots && k <= ctx->lim.max_topk &&
                            Vp1 <= ctx->lim.max_vocab_rows,
                   CTCSPEC_EUNSUPPORTED, "ctc_draft_topk: shape exceeds the context's limits");
-  const LmScratch sc = {ctx->lm_pmax, ctx->lm_psum, ctx->lm_pkey, ctx->zeros};
+  const LmScratch sc = {ctx->lm_pmax, ctx->lm_psum, ctx->lm_pkey, ctx->lm_max_blocks, ctx->zeros};
   return draft_topk_launch(ctx, ctx->stream, sc, ctx->lm_profile ? ctx->lm_ev0 : nullptr,
-                           ctx->lm_profile ? ctx->lm_ev1 : nullptr, &ctx->lm_profile_valid, dt, hidden, w, bias, B, T, D,
-                           Vp1, k, topk_id, topk_logp, lse, logits_out);
+                           ctx->lm_profile ? ctx->lm_ev1 : nullptr, &ctx->lm_profile_valid, ctx->lm_defer != 0, dt, hidden, w,
+                           bias, B, T, D, Vp1, k, topk_id, topk_logp, lse, logits_out);
 }
 
 extern "C" int ctc_draft_topk_noalloc(void* hip_stream, ctcspec_dtype dt, const void* hidden, const void* w,
@@ -684,7 +654,7 @@ extern "C" int ctc_draft_topk_noalloc(void* hip_stream, ctcspec_dtype dt, const 
     CTCSPEC_HIP(nullptr, allow_large_lds());
   }
   const LmScratch sc = {(float*)(sp + kScratchPmax), (float*)(sp + kScratchPsum),
-                        (unsigned long long*)(sp + kScratchPkey), sp + kScratchZeros};
-  return draft_topk_launch(nullptr, stream, sc, nullptr, nullptr, nullptr, dt, hidden, w, bias, B, T, D, Vp1, k, topk_id,
+                        (unsigned long long*)(sp + kScratchPkey), kStaticMaxBlocks, sp + kScratchZeros};
+  return draft_topk_launch(nullptr, stream, sc, nullptr, nullptr, nullptr, false, dt, hidden, w, bias, B, T, D, Vp1, k, topk_id,
                            topk_logp, lse, logits_out);
 }

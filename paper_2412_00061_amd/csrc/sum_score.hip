@@ -107,6 +107,7 @@ extern "C" int ctc_sum_score(ctcspec_ctx* ctx, const float* logits, const float*
                              const int32_t* cand_len, const int32_t* n_cand, int B, int T, int Vp1, int32_t blank_id,
                              int beam, float* cand_logp_sum, int32_t* cand_rank_sum) {
   if (!ctx) return CTCSPEC_EINVAL;
+  if (const int owed = flush_deferred(ctx)) return owed;
   CTCSPEC_REQUIRE(ctx, logits && lse && cand_tokens && cand_len && n_cand && cand_logp_sum && cand_rank_sum,
                   CTCSPEC_EINVAL, "ctc_sum_score: null pointer");
   CTCSPEC_REQUIRE(ctx, B > 0 && T > 0 && Vp1 > 0 && beam > 0, CTCSPEC_EINVAL, "ctc_sum_score: sizes must be positive");

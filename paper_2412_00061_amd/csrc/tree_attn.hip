@@ -161,11 +161,10 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
-__device__ __forceinline__ float max3_f32(float a, float b, float c) {
-  float r;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-  return r;
-}
+// (Plain fmaxf on purpose.  As an inline-asm v_max3_f32 this read accumulators of the MFMAs issued right before it,
+// and the compiler counts no wait states for inline asm: with the scores consumed straight out of the last product
+// the maximum was taken over values that had not landed yet.)
+__device__ __forceinline__ float max3_f32(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 // max / sum over the four lanes l, l^16, l^32, l^48 (the lanes that hold the same query column).
 // (v_permlane16_swap / v_permlane32_swap would do this inside the vector ALU, and did in an earlier
 // version - with results that changed from run to run in the last bits: the value read right after a
@@ -551,6 +550,7 @@ int ctcspec::tree_verify_attn_rows(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
                                    float* out, unsigned short* rows, long long rows_plane, int* rows_written) {
   if (rows_written) *rows_written = 0;
   if (!ctx) return CTCSPEC_EINVAL;
+  if (const int owed = flush_deferred(ctx)) return owed;
   CTCSPEC_REQUIRE(ctx, q && k_cache && v_cache && kv_off && ctx_len && k_tree && v_tree && n_nodes && anc_mask && out,
                   CTCSPEC_EINVAL, "tree_verify_attn: null pointer");
   CTCSPEC_REQUIRE(ctx, dt == CTCSPEC_F32 || dt == CTCSPEC_BF16, CTCSPEC_EINVAL, "tree_verify_attn: bad dtype");

@@ -202,6 +202,7 @@ extern "C" int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void
                                   const int32_t* n_nodes, int B, int max_nodes, int D, int V,
                                   int32_t* target_argmax, float* logits_out) {
   if (!ctx) return CTCSPEC_EINVAL;
+  if (const int owed = flush_deferred(ctx)) return owed;
   CTCSPEC_REQUIRE(ctx, node_hidden && w_base && n_nodes && target_argmax, CTCSPEC_EINVAL,
                   "verify_head_argmax: null pointer");
   CTCSPEC_REQUIRE(ctx, dt == CTCSPEC_F32 || dt == CTCSPEC_BF16, CTCSPEC_EINVAL, "verify_head_argmax: bad dtype");
@@ -244,6 +245,7 @@ extern "C" int kv_commit(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* k_tree,
                          const int32_t* ctx_len, int kv_cap, int B, int H, int dh, int max_nodes, void* k_cache,
                          void* v_cache, int32_t* ctx_len_out) {
   if (!ctx) return CTCSPEC_EINVAL;
+  if (const int owed = flush_deferred(ctx)) return owed;
   CTCSPEC_REQUIRE(ctx, k_tree && v_tree && accept_len && accept_nodes && kv_off && ctx_len && k_cache && v_cache,
                   CTCSPEC_EINVAL, "kv_commit: null pointer");
   CTCSPEC_REQUIRE(ctx, dt == CTCSPEC_F32 || dt == CTCSPEC_BF16, CTCSPEC_EINVAL, "kv_commit: bad dtype");

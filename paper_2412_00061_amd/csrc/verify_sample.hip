@@ -185,6 +185,7 @@ using namespace ctcspec;
 extern "C" int verify_sample_tokens(ctcspec_ctx* ctx, const float* logits, const int32_t* n_nodes, const float* uniforms,
                                     float temperature, int B, int max_nodes, int V, int32_t* target_sampled) {
   if (!ctx) return CTCSPEC_EINVAL;
+  if (const int owed = flush_deferred(ctx)) return owed;
   CTCSPEC_REQUIRE(ctx, logits && n_nodes && uniforms && target_sampled, CTCSPEC_EINVAL, "verify_sample_tokens: null pointer");
   CTCSPEC_REQUIRE(ctx, B > 0 && max_nodes > 0 && V > 0, CTCSPEC_EINVAL, "verify_sample_tokens: sizes must be positive");
   CTCSPEC_REQUIRE(ctx, temperature > 0.f && temperature < INFINITY, CTCSPEC_EINVAL,

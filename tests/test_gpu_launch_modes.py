@@ -446,3 +446,120 @@ def test_loss_and_sampled_draw_graph_replay(pkg):
         assert math.isfinite(float(junk))
     ctx.set_stream(torch.cuda.current_stream())
     ctx.close()
+
+
+# ------------------------------------------------------------------------------ deferred merge of the draft head
+def _draft_and_tree(pkg, ctx, st, k, beam, N):
+    cfg = st.cfg
+    d_hidden, d_w, d_bias, d_root = st.keep[:4]
+    s12 = pkg.ctc_draft_topk(ctx, d_hidden, d_w, d_bias, k)
+    s3 = pkg.ctc_collapse_tree(ctx, s12["topk_id"], s12["topk_logp"], d_root, cfg.blank_id, beam, N)
+    torch.cuda.synchronize()
+    return {**{n: t.cpu().numpy() for n, t in s12.items()}, **{n: t.cpu().numpy() for n, t in s3.items()}}
+
+
+@pytest.mark.parametrize("cfg_index,variant", [(0, "ar1"), (2, "literal"), (2, "structured"), (4, "structured")])
+def test_deferred_merge_gives_the_same_bits(pkg, cfg_index, variant):
+    """ctc_draft_topk with its merge left to ctc_collapse_tree's kernel: every output of both calls must equal the
+    two-kernel path bit for bit (the merge is the same code in both places)."""
+    st = _Step(pkg, cfg_index, variant=variant)
+    cfg, ctx = st.cfg, st.ctx
+    plain = _draft_and_tree(pkg, ctx, st, cfg.k, cfg.beam, cfg.max_nodes)
+    ctx.defer_topk_merge(True)
+    fused = _draft_and_tree(pkg, ctx, st, cfg.k, cfg.beam, cfg.max_nodes)
+    again = _draft_and_tree(pkg, ctx, st, cfg.k, cfg.beam, cfg.max_nodes)
+    ctx.defer_topk_merge(False)
+    for name in plain:
+        assert np.array_equal(plain[name].view(np.uint8), fused[name].view(np.uint8)), name
+        assert np.array_equal(plain[name].view(np.uint8), again[name].view(np.uint8)), name
+    ctx.close()
+
+
+def test_deferred_merge_is_settled_by_whatever_comes_next(pkg):
+    """The owed lists appear whatever the next call is: ctcspec_flush, another stage call, a collapse call on other
+    buffers or with a list length the built-in merge does not cover, a second draft call, a stream change."""
+    st = _Step(pkg, 1)
+    cfg, ctx = st.cfg, st.ctx
+    d_hidden, d_w, d_bias, d_root = st.keep[:4]
+    want = pkg.ctc_draft_topk(ctx, d_hidden, d_w, d_bias, cfg.k)
+    torch.cuda.synchronize()
+    ctx.defer_topk_merge(True)
+
+    def owed(k=cfg.k):
+        out = {"topk_id": torch.full((cfg.B, cfg.T, k), -7, dtype=torch.int32, device="cuda"),
+               "topk_logp": torch.full((cfg.B, cfg.T, k), float("nan"), device="cuda"),
+               "lse": torch.full((cfg.B, cfg.T), float("nan"), device="cuda")}
+        return pkg.ctc_draft_topk(ctx, d_hidden, d_w, d_bias, k, out=out)
+
+    def settled(got, ref=want):
+        torch.cuda.synchronize()
+        for name in ref:
+            assert torch.equal(got[name].view(torch.int32), ref[name].view(torch.int32)), name
+
+    got = owed()
+    ctx.flush()
+    settled(got)
+    got = owed()
+    pkg.accept_longest(ctx, st.out["n_nodes"].fill_(1), st.out["node_token"], st.out["node_parent"], st.out["node_depth"],
+                       st.targets, cfg.T)
+    settled(got)
+    got = owed()
+    ids2, lp2 = want["topk_id"].clone(), want["topk_logp"].clone()  # a collapse call on other buffers
+    pkg.ctc_collapse_tree(ctx, ids2, lp2, d_root, cfg.blank_id, cfg.beam, cfg.max_nodes)
+    settled(got)
+    got = owed()
+    pkg.ctc_raw_tree(ctx, got["topk_id"], got["topk_logp"], d_root, cfg.blank_id, cfg.beam, cfg.max_nodes)
+    settled(got)
+    # lists of five keys: the collapse kernel's built-in merge stops at four, so it launches the merge kernel first
+    rng = np.random.Generator(np.random.PCG64(5))
+    h5 = to_device(workloads.round_to_storage(rng.standard_normal((1, 4, 512), dtype=np.float32), "bf16"), "bf16")
+    w5 = to_device(workloads.round_to_storage(rng.standard_normal((300, 512), dtype=np.float32) * 0.05, "bf16"), "bf16")
+    ctx5 = pkg.Context(max_batch=1, max_slots=4, max_topk=5, max_vocab_rows=300, max_nodes=32, max_heads=1,
+                       max_head_dim=16)
+    want5 = pkg.ctc_draft_topk(ctx5, h5, w5, None, 5)
+    tree5 = pkg.ctc_collapse_tree(ctx5, want5["topk_id"], want5["topk_logp"], d_root, 299, 16, 32)
+    ctx5.defer_topk_merge(True)
+    got5 = pkg.ctc_draft_topk(ctx5, h5, w5, None, 5)
+    got_tree5 = pkg.ctc_collapse_tree(ctx5, got5["topk_id"], got5["topk_logp"], d_root, 299, 16, 32)
+    settled(got5, want5)
+    for name in tree5:
+        assert torch.equal(tree5[name], got_tree5[name]), name
+    ctx5.close()
+    first = owed()
+    second = owed()  # the second call's partials overwrite the first's: the first must have been merged before
+    ctx.flush()
+    settled(first)
+    settled(second)
+    got = owed()
+    other = torch.cuda.Stream()
+    ctx.set_stream(other)  # settles on the stream the partials were produced on
+    other.synchronize()
+    settled(got)
+    ctx.set_stream(torch.cuda.current_stream())
+    ctx.defer_topk_merge(False)
+    ctx.close()
+
+
+def test_deferred_merge_graph_replay(pkg):
+    """The step with the deferred merge, captured and replayed: the same results as eager calls without it."""
+    st = _Step(pkg, 2)
+    st.run()
+    st.plant_targets()
+    st.run()
+    eager = st.snapshot()
+    stream = torch.cuda.Stream()
+    st.ctx.defer_topk_merge(True)
+    st.ctx.set_stream(stream)
+    with torch.cuda.stream(stream):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            st.run()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        st.scrub()
+        torch.cuda.synchronize()
+        graph.replay()
+        _same(eager, st.snapshot())
+    st.ctx.set_stream(torch.cuda.current_stream())
+    st.ctx.defer_topk_merge(False)
+    st.ctx.close()
