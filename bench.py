@@ -47,7 +47,7 @@ def parse_args():
                          "(ctcspec_defer_topk_merge) instead of launching the merge kernel right behind the head")
     ap.add_argument("--attn-layers", type=int, default=-1,
                     help="layers of the full-depth variant line (attention called once per layer on its own "
-                         "K/V/Q buffers); default: heads of the config (32 at 7B, 40 at 13B); 0: skip")
+                         "K/V/Q buffers); default: the layer count of the config (32 at 7B, 40 at 13B); 0: skip")
     ap.add_argument("--full-depth-steps", type=int, default=24)
     ap.add_argument("--no-closed-step", action="store_true")
     ap.add_argument("--no-draft-layer", action="store_true")
@@ -59,7 +59,8 @@ def parse_args():
                     help="training positions of the ctc_loss line, each with T frames over V+1 symbols")
     ap.add_argument("--draft-layer-ffn", type=int, default=0,
                     help="feed-forward width of the draft module's layer (0: the base family's, 43/16 of D)")
-    ap.add_argument("--cpu-steps", type=int, default=12)
+    ap.add_argument("--cpu-steps", type=int, default=6, help="oracle steps timed with all BLAS threads")
+    ap.add_argument("--cpu-steps-one-thread", type=int, default=2, help="oracle steps timed with one BLAS thread")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run ten 256 MiB device copies (known traffic, for scaling rocprofv3 HBM counters)")
     return ap.parse_args()
@@ -102,36 +103,63 @@ def read_kernel_trace_us():
     return None
 
 
-def cpu_baseline(cfg, x, n_steps):
-    """Time the float64 oracle, as it stands, on this host for n_steps whole steps of the same workload."""
+def cpu_baseline(cfg, x, n_steps, n_steps_one_thread):
+    """Time the float64 oracle, as it stands, on this host: n_steps whole steps of the same workload with all the cores
+    its BLAS takes, then n_steps_one_thread with the BLAS held to one thread; per stage and in total."""
     import oracle
     try:
-        from threadpoolctl import threadpool_info
+        from threadpoolctl import threadpool_info, threadpool_limits
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
+        threadpool_limits = None
         threads = os.cpu_count() or 1
     scale = 1.0 / math.sqrt(cfg.dh)
-    best, nodes, total = None, 0, 0.0
-    for _ in range(n_steps):
-        t0 = time.perf_counter()
+    stages = ("ctc_draft_topk", "ctc_collapse_tree", "tree_verify_attn", "accept_longest")
+
+    def one_step():
+        t = [time.perf_counter()]
         d = oracle.draft_topk(x.hidden, x.w, x.bias, cfg.k)
-        nodes = 0
-        for b in range(cfg.B):
-            tree = oracle.collapse_tree(d["topk_id"][b], d["topk_logp"][b].astype(np.float32),
-                                        int(x.root_token[b]), cfg.blank_id, cfg.beam, cfg.max_nodes)
-            n = tree["n_nodes"]
-            o = oracle.tree_attention(x.q[b], x.k_cache[b], x.v_cache[b], int(x.ctx_len[b]), x.k_tree[b],
-                                      x.v_tree[b], n, tree["mask"], scale)
-            target = np.full(n, -1, dtype=np.int32)
-            oracle.accept_longest(tree["node_token"], tree["node_parent"], n, target, cfg.T)
-            nodes += n
+        t.append(time.perf_counter())
+        trees = [oracle.collapse_tree(d["topk_id"][b], d["topk_logp"][b].astype(np.float32), int(x.root_token[b]),
+                                      cfg.blank_id, cfg.beam, cfg.max_nodes) for b in range(cfg.B)]
+        t.append(time.perf_counter())
+        for b, tree in enumerate(trees):
+            o = oracle.tree_attention(x.q[b], x.k_cache[b], x.v_cache[b], int(x.ctx_len[b]), x.k_tree[b], x.v_tree[b],
+                                      tree["n_nodes"], tree["mask"], scale)
             del o
-        dt = time.perf_counter() - t0
-        best = dt if best is None else min(best, dt)
-        total += dt
-    return {"value": nodes * n_steps / total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{n_steps} whole step(s) of the same workload and seed, {total:.1f} s of CPU work; "
-                      f"{total / n_steps * 1e3:.0f} ms per step on average, {best * 1e3:.0f} ms the best"}
+        t.append(time.perf_counter())
+        for tree in trees:
+            n = tree["n_nodes"]
+            oracle.accept_longest(tree["node_token"], tree["node_parent"], n, np.full(n, -1, dtype=np.int32), cfg.T)
+        t.append(time.perf_counter())
+        return np.diff(t), sum(tree["n_nodes"] for tree in trees)
+
+    def run(n):
+        rows, nodes = [], 0
+        for _ in range(n):
+            dt, nodes = one_step()
+            rows.append(dt)
+        rows = np.array(rows)
+        return rows, nodes
+
+    rows, nodes = run(n_steps)
+    total = float(rows.sum())
+    out = {"value": nodes * n_steps / total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+           "sample": f"{n_steps} whole step(s) of the same workload and seed with {threads} BLAS thread(s), "
+                     f"{total:.1f} s of CPU work; {total / n_steps * 1e3:.0f} ms per step on average, "
+                     f"{rows.sum(axis=1).min() * 1e3:.0f} ms the best",
+           "host_cpus": os.cpu_count(),
+           "per_stage_ms_best": {"threads": int(threads),
+                                 **{name: float(rows[:, i].min() * 1e3) for i, name in enumerate(stages)},
+                                 "step": float(rows.sum(axis=1).min() * 1e3)}}
+    if n_steps_one_thread > 0 and threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            rows1, _ = run(n_steps_one_thread)
+        out["per_stage_ms_best_one_thread"] = {"threads": 1,
+                                               **{name: float(rows1[:, i].min() * 1e3) for i, name in enumerate(stages)},
+                                               "step": float(rows1.sum(axis=1).min() * 1e3)}
+        out["sample"] += f"; then {n_steps_one_thread} step(s) with the BLAS held to one thread, {rows1.sum():.1f} s"
+    return out
 
 
 def main():
@@ -281,12 +309,31 @@ def main():
     torch.cuda.synchronize()
     head_kernel_us = np.array(head_kernel_us)
 
+    # the read-only streaming probe on the same weight copies, in the same run: what this GPU delivers to a kernel
+    # that only reads the matrix (events around each launch, on the launch stream)
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    w_bytes = d_w[0].numel() * d_w[0].element_size()
+    probe_calls = [lib.prepared(ctx, "ctcspec_stream_probe", w, w_bytes, sink) for w in d_w]
+    for i in range(6):
+        probe_calls[i % len(probe_calls)]()
+    torch.cuda.synchronize()
+    n_pr = 48
+    pr_ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_pr + 1)]
+    pr_ev[0].record()
+    for i in range(n_pr):
+        probe_calls[i % len(probe_calls)]()
+        pr_ev[i + 1].record()
+    torch.cuda.synchronize()
+    probe_us = float(np.median([pr_ev[i].elapsed_time(pr_ev[i + 1]) * 1e3 for i in range(n_pr)]))
+    probe_bytes = w_bytes // (128 * 1024) * (128 * 1024)
+    probe_gbps = probe_bytes / (probe_us * 1e-6) / 1e9
+
     # step time from the events of the second pass (first event to last event of each step)
     step_ev = np.array([e[0].elapsed_time(e[4]) * 1e3 for e in evs])
 
     # full-depth variant: the same step with the verification attention of EVERY layer of the base model,
     # each layer on its own K/V cache and Q/K_tree/V_tree (buffer set l for layer l), still one stream
-    n_layers = args.attn_layers if args.attn_layers >= 0 else (H if cfg.dtype == "bf16" else 0)
+    n_layers = args.attn_layers if args.attn_layers >= 0 else (cfg.n_layers if cfg.dtype == "bf16" else 0)
     full_depth = None
     if n_layers > 0:
         attn_calls = []
@@ -616,6 +663,10 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": read_traffic_summary(), "algorithmic_bytes_per_launch": head_b,
                      "launch_us": head_us, "launch_us_median": float(np.median(head_kernel_us)),
+                     # the same matrix through the read-only streaming probe, same run (launch to launch by events,
+                     # so about 2 us of dispatch are inside): the achievable rate beside the nominal peak
+                     "stream_probe_gbps": probe_gbps, "stream_probe_us": probe_us,
+                     "frac_of_stream_probe": achieved / probe_gbps,
                      # the same kernel in the committed rocprofv3 trace (7B shape): begin-to-end by the profiler's
                      # clock, without the dispatch time that an event pair around one launch also spans
                      "kernel_trace_avg_us": read_kernel_trace_us() if cfg.name == "7b_ctx2048" else None,
@@ -628,7 +679,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, x, args.cpu_steps)
+        result["cpu_baseline"] = cpu_baseline(cfg, x, args.cpu_steps, args.cpu_steps_one_thread)
     print(json.dumps(result))
     ctx.close()
     return 0

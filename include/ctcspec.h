@@ -105,6 +105,12 @@ int ctcspec_flush(ctcspec_ctx* ctx);
 int ctcspec_profile_draft_head(ctcspec_ctx* ctx, int enable);
 int ctcspec_draft_head_kernel_ms(ctcspec_ctx* ctx, float* ms);
 
+/* Measurement aid.  Reads the first floor(bytes / 131072) * 131072 bytes at src (device, 16-byte aligned) once, with
+ * coalesced 16-byte loads and nothing else, on the context's stream: the rate this GPU delivers to a kernel that
+ * streams a matrix, against which the HBM-bound kernels' rates can be set beside the nominal peak.  sink: one device
+ * word that is (practically) never written.  Timing is the caller's (events on the stream). */
+int ctcspec_stream_probe(ctcspec_ctx* ctx, const void* src, size_t bytes, uint32_t* sink);
+
 /*
  * Stage 1+2 - draft head.  For every draft slot, project its hidden state through the LM head of
  * the augmented vocabulary (tokens plus blank), take the log-softmax over all V+1 entries and keep

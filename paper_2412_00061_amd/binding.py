@@ -17,7 +17,7 @@ EXPORTS = (
     "ctcspec_workspace_bytes", "ctcspec_profile_draft_head", "ctcspec_draft_head_kernel_ms", "ctc_draft_topk", "ctc_collapse_tree", "tree_verify_attn",
     "accept_longest", "verify_head_argmax", "kv_commit", "draft_layer_workspace_bytes", "draft_layer_forward",
     "ctc_sum_score", "ctc_raw_tree", "ctc_loss_workspace_bytes", "ctc_loss", "verify_sample_tokens",
-    "ctc_draft_topk_noalloc", "ctcspec_defer_topk_merge", "ctcspec_flush",
+    "ctc_draft_topk_noalloc", "ctcspec_defer_topk_merge", "ctcspec_flush", "ctcspec_stream_probe",
 )
 
 CTCSPEC_F32, CTCSPEC_BF16 = 0, 1
@@ -65,6 +65,8 @@ def load_library():
     lib.ctcspec_defer_topk_merge.argtypes = [c_void_p, c_int]
     lib.ctcspec_flush.restype = c_int
     lib.ctcspec_flush.argtypes = [c_void_p]
+    lib.ctcspec_stream_probe.restype = c_int
+    lib.ctcspec_stream_probe.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p]
     lib.ctcspec_profile_draft_head.restype = c_int
     lib.ctcspec_profile_draft_head.argtypes = [c_void_p, c_int]
     lib.ctcspec_draft_head_kernel_ms.restype = c_int

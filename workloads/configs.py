@@ -26,6 +26,7 @@ class StepConfig:
     dtype: str        # storage dtype of hidden/W/Q/K/V: "f32" or "bf16"
     blank_bias: float  # additive logit bias of the blank row
     rms_norm: bool    # draft hidden states normalised to unit RMS per row
+    n_layers: int = 0  # attention layers of the base model the shape is borrowed from (0: none stated)
 
     @property
     def Vp1(self) -> int:
@@ -44,13 +45,13 @@ CONFIGS = (
     StepConfig("tiny", B=1, D=64, V=100, T=4, k=2, beam=16, max_nodes=128, H=4, dh=16,
                ctx=(32, 32), kv_cap=32, dtype="f32", blank_bias=1.5, rms_norm=False),
     StepConfig("7b_ctx512", B=1, D=4096, V=32000, T=8, k=4, beam=64, max_nodes=128, H=32, dh=128,
-               ctx=(512, 512), kv_cap=512, dtype="bf16", blank_bias=1.0, rms_norm=True),
+               ctx=(512, 512), kv_cap=512, dtype="bf16", blank_bias=1.0, rms_norm=True, n_layers=32),
     StepConfig("7b_ctx2048", B=1, D=4096, V=32000, T=8, k=4, beam=128, max_nodes=128, H=32, dh=128,
-               ctx=(2048, 2048), kv_cap=2048, dtype="bf16", blank_bias=1.0, rms_norm=True),
+               ctx=(2048, 2048), kv_cap=2048, dtype="bf16", blank_bias=1.0, rms_norm=True, n_layers=32),
     StepConfig("13b_ctx2048", B=1, D=5120, V=32000, T=8, k=4, beam=128, max_nodes=128, H=40, dh=128,
-               ctx=(2048, 2048), kv_cap=2048, dtype="bf16", blank_bias=1.0, rms_norm=True),
+               ctx=(2048, 2048), kv_cap=2048, dtype="bf16", blank_bias=1.0, rms_norm=True, n_layers=40),
     StepConfig("7b_batch8_ragged", B=8, D=4096, V=32000, T=8, k=4, beam=64, max_nodes=64, H=32, dh=128,
-               ctx=(256, 2048), kv_cap=2048, dtype="bf16", blank_bias=1.0, rms_norm=True),
+               ctx=(256, 2048), kv_cap=2048, dtype="bf16", blank_bias=1.0, rms_norm=True, n_layers=32),
 )
 
 
