@@ -402,7 +402,7 @@ def main():
             commit_calls[i % len(sets)]()
         torch.cuda.synchronize()
         vh_us = float(np.median([cs_ev[2 * i].elapsed_time(cs_ev[2 * i + 1]) * 1e3 for i in range(n_cs)]))
-        vh_bytes = cfg.V * cfg.D * 2 * ((B * N + 127) // 128) + B * N * cfg.D * 2 + B * N * 4
+        vh_bytes = cfg.V * cfg.D * 2 + B * N * cfg.D * 2 + B * N * 4  # one pass over the weights for any number of nodes
         closed = {"calls": "ctc_draft_topk, ctc_collapse_tree, tree_verify_attn, verify_head_argmax, accept_longest, "
                            "kv_commit", "steps": n_cs, "us_per_step": cs_us,
                   "verify_head_argmax_us_median": vh_us, "verify_head_algorithmic_bytes": vh_bytes,

@@ -260,7 +260,8 @@ int accept_longest(ctcspec_ctx* ctx, const int32_t* n_nodes, const int32_t* node
  * target_argmax [B,max_nodes] int32 out
  * logits_out    [B,max_nodes,V] float out, may be NULL; when given, receives exactly the z values the
  *               argmax used (for parity checks; costs extra HBM writes)
- * The weights are streamed once per 128 nodes (B*max_nodes / 128 passes, rounded up).
+ * One pass over the weights in HBM whatever the number of nodes: blocks of 128 node columns that share a block of
+ * weight rows are scheduled next to each other on one XCD, so that all but the first find the rows in its L2.
  * Limits: B, max_nodes, V within the context's limits (V <= max_vocab_rows).
  */
 int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void* node_hidden, const void* w_base,

@@ -63,7 +63,8 @@ struct ctcspec_ctx {
   hipEvent_t lm_ev0, lm_ev1;
   // verifier head
   const void* zeros;            // 256 bytes of zeros
-  unsigned long long* vh_pkey;  // [lm_max_blocks][kVerifyCols] best (logit, id) key per row block and column
+  int vh_col_blocks;            // column blocks of kVerifyCols the limits allow: ceil(max_batch * max_nodes / 128)
+  unsigned long long* vh_pkey;  // [vh_col_blocks][lm_max_blocks][kVerifyCols] best (logit, id) key per row block and column
   // collapse / tree
   unsigned char* collapse_ws;   // [max_batch][kCollapseWsBytesPerSeq]
   // attention

@@ -122,7 +122,8 @@ extern "C" int ctcspec_create(ctcspec_ctx** out, void* hip_stream, const ctcspec
   size_t o_pmax = carve((size_t)ctx->lm_max_blocks * kMaxCols * sizeof(float));
   size_t o_psum = carve((size_t)ctx->lm_max_blocks * kMaxCols * sizeof(float));
   size_t o_pkey = carve((size_t)ctx->lm_max_blocks * kMaxCols * kMaxTopk * sizeof(unsigned long long));
-  size_t o_vh = carve((size_t)ctx->lm_max_blocks * kVerifyCols * sizeof(unsigned long long));
+  ctx->vh_col_blocks = (int)(((long long)lim->max_batch * lim->max_nodes + kVerifyCols - 1) / kVerifyCols);
+  size_t o_vh = carve((size_t)ctx->vh_col_blocks * ctx->lm_max_blocks * kVerifyCols * sizeof(unsigned long long));
   size_t o_zero = carve(256);
   size_t o_coll = carve((size_t)lim->max_batch * kCollapseWsBytesPerSeq);
   // attention partials: one slot of 128 query rows per (sequence, head, key split)

@@ -4,7 +4,8 @@
 // The head is the same stream over a [V, D] weight matrix as the draft head, but with up to 128 columns
 // (one per tree node) instead of 8, and all that is kept of a column is its best (logit, id) key:
 //   * verify_head_bf16_kernel    - bf16, D a multiple of 128: MFMA, 128 vocabulary rows x 128 columns
-//                                  per workgroup, weights read once per block of 128 columns
+//                                  per workgroup; all column blocks in one launch, those of a row block side by
+//                                  side on one XCD (the weights come from HBM once)
 //   * verify_head_generic_kernel - any dtype/shape: plain fp32 FMA, one atomic max per (row block, column)
 //   * verify_head_merge_kernel   - best key over the row blocks -> token id, -1 for rows without a node
 #include "gemm_tile.h"
@@ -21,12 +22,14 @@ static_assert(kVhCols == 128 && kRowsPerBlock == 128, "tile shape");
 static_assert(kVhCols * kVhZStride * 4 <= kVhLdsBytes, "logit block fits the staging area");
 
 struct VerifyHeadParams {
-  const void* hidden;   // [cols_total][D], this pass starts at column col0
+  const void* hidden;   // [cols_total][D]
   const void* w;        // [V][D]
-  int col0, cols;       // columns of this pass (cols <= kVhCols)
+  int col0, cols;       // generic kernels: columns of this launch (cols <= kVhCols), a whole column block
+  int cols_total;       // all columns of the call; the bf16 kernel covers them in one launch, block by block
+  int col_blocks;       // ceil(cols_total / kVhCols)
   int D, V;
   int n_blocks;         // row blocks of 128
-  unsigned long long* pkey;  // [n_blocks][kVhCols] best key per (row block, column of the pass)
+  unsigned long long* pkey;  // [col_blocks][n_blocks][kVhCols] best key per (column block, row block, column)
   float* logits_out;    // [cols_total][V] or null
   const void* zeros;    // 256 bytes of zeros
   const int32_t* n_nodes;  // [B]
@@ -43,10 +46,20 @@ __global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyH
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wr = wave >> 2, wc = wave & 3;
   const int c = lane & 15, g = lane >> 4;
-  const int row_base = blockIdx.x * kRowsPerBlock;
+  // Workgroup -> (row block, column block).  Workgroups are dealt to the 8 XCDs round robin, and each XCD has its
+  // own L2: the column blocks of one row block get workgroup numbers that differ by multiples of 8 and are
+  // neighbours in dispatch order, so they run on the same XCD at about the same time and the weight tile that the
+  // first of them pulls from HBM serves the others from that L2 - one pass over the weights in HBM for any number
+  // of columns.  (One column block: row block = workgroup number.)
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int cb = slot % p.col_blocks, rb = (slot / p.col_blocks) * 8 + xcd;
+  if (rb >= p.n_blocks) return;
+  const int col0 = cb * kVhCols;
+  const int cols = p.cols_total - col0 < kVhCols ? p.cols_total - col0 : kVhCols;
+  const int row_base = rb * kRowsPerBlock;
   GemmTileArgs t;
-  t.w = p.w; t.hidden = (const unsigned char*)p.hidden + (size_t)p.col0 * p.D * 2; t.zeros = p.zeros;
-  t.D = p.D; t.V = p.V; t.cols = p.cols; t.row_base = row_base;
+  t.w = p.w; t.hidden = (const unsigned char*)p.hidden + (size_t)col0 * p.D * 2; t.zeros = p.zeros;
+  t.D = p.D; t.V = p.V; t.cols = cols; t.row_base = row_base;
   f32x4 acc[4][2];
   gemm_tile_128<DIST, 2>(t, smem, acc);
 
@@ -61,9 +74,9 @@ __global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyH
       for (int ct = 0; ct < 2; ++ct)
         *(f32x4*)(zbuf + (wc * 32 + ct * 16 + c) * kVhZStride + wr * 64 + rt * 16 + g * 4) = acc[rt][ct];
     __syncthreads();
-    for (int idx = tid; idx < p.cols * kRowsPerBlock; idx += NTHREADS) {
+    for (int idx = tid; idx < cols * kRowsPerBlock; idx += NTHREADS) {
       const int m = idx / kRowsPerBlock, r = idx % kRowsPerBlock;
-      if (row_base + r < p.V) p.logits_out[(size_t)(p.col0 + m) * p.V + row_base + r] = zbuf[m * kVhZStride + r];
+      if (row_base + r < p.V) p.logits_out[(size_t)(col0 + m) * p.V + row_base + r] = zbuf[m * kVhZStride + r];
     }
     __syncthreads();
   }
@@ -88,15 +101,16 @@ __global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyH
     if (g == 0) kbuf[wr * kVhCols + wc * 32 + ct * 16 + c] = best;
   }
   __syncthreads();
-  if (tid < p.cols) {
+  if (tid < cols) {
     const unsigned long long k0 = kbuf[tid], k1 = kbuf[kVhCols + tid];
-    p.pkey[(size_t)blockIdx.x * kVhCols + tid] = k0 > k1 ? k0 : k1;
+    p.pkey[((size_t)cb * p.n_blocks + rb) * kVhCols + tid] = k0 > k1 ? k0 : k1;
   }
 }
 
 // ---- generic kernel: thread -> (row, column), the row block's best key per column by atomic max -----------
 __global__ __launch_bounds__(256) void verify_head_clear_kernel(VerifyHeadParams p) {
-  for (int i = blockIdx.x * 256 + threadIdx.x; i < p.n_blocks * kVhCols; i += gridDim.x * 256) p.pkey[i] = 0ull;
+  unsigned long long* pk = p.pkey + (size_t)(p.col0 / kVhCols) * p.n_blocks * kVhCols;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < p.n_blocks * kVhCols; i += gridDim.x * 256) pk[i] = 0ull;
 }
 template <typename T>
 __global__ __launch_bounds__(256) void verify_head_generic_kernel(VerifyHeadParams p) {
@@ -111,27 +125,28 @@ __global__ __launch_bounds__(256) void verify_head_generic_kernel(VerifyHeadPara
     float z = 0.f;
     for (int d = 0; d < p.D; ++d) z = fmaf(load_as_float(hp + d), load_as_float(wr + d), z);
     if (p.logits_out) p.logits_out[(size_t)(p.col0 + m) * p.V + row] = z;
-    atomicMax(&p.pkey[(size_t)blockIdx.x * kVhCols + m], rank_key(z, (unsigned)row));
+    atomicMax(&p.pkey[((size_t)(p.col0 / kVhCols) * p.n_blocks + blockIdx.x) * kVhCols + m], rank_key(z, (unsigned)row));
   }
 }
 
 // best key over the row blocks: one wavefront per column; rows of the node table without a node get -1
 __global__ __launch_bounds__(64) void verify_head_merge_kernel(VerifyHeadParams p) {
-  const int m = blockIdx.x, lane = threadIdx.x;
+  const int col = p.col0 + blockIdx.x, lane = threadIdx.x;  // column of the call
+  const int m = col % kVhCols;
+  const unsigned long long* pk = p.pkey + (size_t)(col / kVhCols) * p.n_blocks * kVhCols;
   unsigned long long best = 0ull;
   for (int b0 = 0; b0 < p.n_blocks; b0 += 256) {
     unsigned long long x[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int b = b0 + u * 64 + lane;
-      x[u] = b < p.n_blocks ? p.pkey[(size_t)b * kVhCols + m] : 0ull;
+      x[u] = b < p.n_blocks ? pk[(size_t)b * kVhCols + m] : 0ull;
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) best = x[u] > best ? x[u] : best;
   }
   best = wave_max_u64(best);
   if (lane == 0) {
-    const int col = p.col0 + m;
     const int b = col / p.max_nodes, i = col - b * p.max_nodes;
     int n = p.n_nodes[b];
     n = n < 0 ? 0 : (n > p.max_nodes ? p.max_nodes : n);
@@ -220,19 +235,31 @@ extern "C" int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void
   const long long cols_total = (long long)B * max_nodes;
   const bool wide = dt == CTCSPEC_BF16 && D % kVhStepK == 0 && (long long)V * D * 2 < (1LL << 32) &&
                     cols_total * D * 2 < (1LL << 32);
-  const int lds = kVhLdsBytes;
+  p.cols_total = (int)cols_total;
+  p.col_blocks = (int)((cols_total + kVhCols - 1) / kVhCols);
+  CTCSPEC_REQUIRE(ctx, p.col_blocks <= ctx->vh_col_blocks, CTCSPEC_EUNSUPPORTED,
+                  "verify_head_argmax: %lld columns exceed the context's workspace", cols_total);
+  if (wide) {
+    // one launch for every column block (the kernel's workgroup numbering keeps a row block's column blocks on
+    // one XCD), one merge launch over all columns
+    p.col0 = 0; p.cols = 0;
+    const long long grid = (long long)((p.n_blocks + 7) / 8) * 8 * p.col_blocks;
+    CTCSPEC_REQUIRE(ctx, grid <= 0x7fffffffLL, CTCSPEC_EUNSUPPORTED, "verify_head_argmax: grid too large");
+    hipLaunchKernelGGL(verify_head_bf16_kernel<kVhDist>, dim3((unsigned)grid), dim3(64 * kVhWaves), kVhLdsBytes,
+                       ctx->stream, p);
+    CTCSPEC_HIP(ctx, hipGetLastError());
+    hipLaunchKernelGGL(verify_head_merge_kernel, dim3((unsigned)cols_total), dim3(64), 0, ctx->stream, p);
+    CTCSPEC_HIP(ctx, hipGetLastError());
+    return CTCSPEC_OK;
+  }
   for (long long col0 = 0; col0 < cols_total; col0 += kVhCols) {
     p.col0 = (int)col0;
     p.cols = (int)(cols_total - col0 < kVhCols ? cols_total - col0 : kVhCols);
-    if (wide) {
-      hipLaunchKernelGGL(verify_head_bf16_kernel<kVhDist>, dim3(p.n_blocks), dim3(64 * kVhWaves), lds, ctx->stream, p);
-    } else {
-      hipLaunchKernelGGL(verify_head_clear_kernel, dim3(64), dim3(256), 0, ctx->stream, p);
-      if (dt == CTCSPEC_BF16)
-        hipLaunchKernelGGL(verify_head_generic_kernel<unsigned short>, dim3(p.n_blocks), dim3(256), 0, ctx->stream, p);
-      else
-        hipLaunchKernelGGL(verify_head_generic_kernel<float>, dim3(p.n_blocks), dim3(256), 0, ctx->stream, p);
-    }
+    hipLaunchKernelGGL(verify_head_clear_kernel, dim3(64), dim3(256), 0, ctx->stream, p);
+    if (dt == CTCSPEC_BF16)
+      hipLaunchKernelGGL(verify_head_generic_kernel<unsigned short>, dim3(p.n_blocks), dim3(256), 0, ctx->stream, p);
+    else
+      hipLaunchKernelGGL(verify_head_generic_kernel<float>, dim3(p.n_blocks), dim3(256), 0, ctx->stream, p);
     CTCSPEC_HIP(ctx, hipGetLastError());
     hipLaunchKernelGGL(verify_head_merge_kernel, dim3(p.cols), dim3(64), 0, ctx->stream, p);
     CTCSPEC_HIP(ctx, hipGetLastError());
