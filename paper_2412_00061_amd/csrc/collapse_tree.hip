@@ -28,7 +28,7 @@
 
 namespace ctcspec {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 256;  // (512 was measured: 3 us slower - the phases are chains of barriers and LDS round trips)
 constexpr int kWaves = kThreads / 64;
 constexpr int kHalfMax = 512;   // k^ceil(T/2) <= 8^3
 constexpr int kLdsCap = 4096;   // sorted candidates kept in LDS
@@ -461,16 +461,17 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
   const float delta = s.delta;
 
   // ---- half sums X (slots < T1) and Y (the rest), each sorted descending ---------------------------
-  // wavefronts 0,1 sort X, wavefronts 2,3 sort Y: key slot gi belongs to X for gi < 128*E
+  // the lower half of the wavefronts sorts X, the upper half Y: key slot gi belongs to X for gi < kHalfThreads*E
   {
+    constexpr int kHalfThreads = kThreads / 2;
     auto sort_halves = [&](auto e_tag) {
       constexpr int E = decltype(e_tag)::value;
       unsigned long long v[E];
 #pragma unroll
       for (int e = 0; e < E; ++e) {
         const int gi = tid * E + e;
-        const bool is_x = gi < 128 * E;
-        const int a = is_x ? gi : gi - 128 * E;
+        const bool is_x = gi < kHalfThreads * E;
+        const int a = is_x ? gi : gi - kHalfThreads * E;
         unsigned long long key = 0ull;
         if (a < (is_x ? n1 : n2)) {
           const Digits4 d = split_digits(a, is_x ? pad1 : pad2, k, magic);
@@ -478,19 +479,20 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
         }
         v[e] = key;
       }
-      block_sort_desc_fast<E, 2>(v, s.ckeys, s.keys, ror4_is_up);
+      block_sort_desc_fast<E, kWaves / 2>(v, s.ckeys, s.keys, ror4_is_up);
       for (int i = tid; i < n1; i += kThreads) {
         s.Xv[i] = rank_key_value(s.keys[i]);
         s.Xi[i] = (int)rank_key_index(s.keys[i]);
       }
       for (int i = tid; i < n2; i += kThreads) {
-        s.Yv[i] = rank_key_value(s.keys[128 * E + i]);
-        s.Yi[i] = (int)rank_key_index(s.keys[128 * E + i]);
+        s.Yv[i] = rank_key_value(s.keys[kHalfThreads * E + i]);
+        s.Yi[i] = (int)rank_key_index(s.keys[kHalfThreads * E + i]);
       }
     };
     const int nmax = n1 > n2 ? n1 : n2;
-    if (nmax <= 128) sort_halves(std::integral_constant<int, 1>{});
-    else if (nmax <= 256) sort_halves(std::integral_constant<int, 2>{});
+    static_assert(kHalfMax <= 4 * kHalfThreads, "four half sums per thread cover every half");
+    if (nmax <= kHalfThreads) sort_halves(std::integral_constant<int, 1>{});
+    else if (nmax <= 2 * kHalfThreads) sort_halves(std::integral_constant<int, 2>{});
     else sort_halves(std::integral_constant<int, 4>{});
     __syncthreads();
   }
@@ -688,6 +690,16 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
   int32_t* node_depth = p.node_depth + (size_t)b * max_nodes;
   unsigned long long* mask = p.anc_mask + (size_t)b * max_nodes * W;
 
+  // The nodes a draft creates are scattered over the node arrays: they are collected in LDS (the hash table of the
+  // walk is dead by now) and leave in one coalesced sweep at the end - as scattered global stores of one wavefront,
+  // up to 64 separate words per instruction, they took half of the tree phase.
+  int* st_tok = reinterpret_cast<int*>(s.table);
+  int* st_par = st_tok + CTCSPEC_MAX_NODES;
+  int* st_dep = st_par + CTCSPEC_MAX_NODES;
+  int* st_rem = st_dep + CTCSPEC_MAX_NODES;
+  unsigned long long* st_mask = reinterpret_cast<unsigned long long*>(st_rem + CTCSPEC_MAX_NODES);  // [nodes][2]
+  static_assert(CTCSPEC_MAX_NODES * (4 * 4 + 2 * 8) <= sizeof(CollapseShared::table) && CTCSPEC_MAX_NODES % 2 == 0,
+                "node staging fits the hash table's LDS");
   if (wave == 0) {
     // ---- prefix tree, by one wavefront; lane l owns drafts l and l+64 --------------------------
     // A node is a distinct draft prefix; it is created by the first (best-ranked) draft that has it.
@@ -714,13 +726,17 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
       // compiler from moving the reads up (the hardware executes a wavefront's LDS operations in order)
       __atomic_signal_fence(__ATOMIC_SEQ_CST);
       __builtin_amdgcn_wave_barrier();
+      // both winners are read back in one round trip (the keys always lie inside the table, so the reads need no
+      // condition; a draft that has ended ignores what it reads)
+      unsigned int won[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+        won[u] = __hip_atomic_load(&s.tree_table[key[u]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        if (d <= len[u]) {
-          const unsigned int won = __hip_atomic_load(&s.tree_table[key[u]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-          fprev[u] = 127 - (int)(won & 0xffu);
-          creators[u] |= (unsigned long long)fprev[u] << (8 * (d - 1));
-        }
+        const bool on = d <= len[u];
+        fprev[u] = on ? 127 - (int)(won[u] & 0xffu) : fprev[u];
+        creators[u] |= on ? (unsigned long long)fprev[u] << (8 * (d - 1)) : 0ull;
       }
     }
     // m = number of leading levels whose node another draft created; my tokens beyond m create nodes,
@@ -754,43 +770,50 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
       p.n_cand[b] = n_c;
       p.n_nodes[b] = n_nodes;
     }
+    // Every draft walks its path once: node id, token, ancestors of each level.  All LDS lookups of both drafts are
+    // requested up front and the walk is free of branches (node ids grow along a path, so "this level's node
+    // exists" already implies it for the levels above): as a loop with an early exit per level it waited for one
+    // LDS round trip per level.
+    int path_node[2][8], path_tok[2][8];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int c = lane + 64 * u;
-      if (c >= n_c) continue;
-      int par = 0, leaf = -1;
-      unsigned long long m0 = 1ull, m1 = 0ull;  // ancestors so far: the root
-      // node id of every level of my path: all lookups are requested before the first is used
-      int path_node[8];
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int d = 0; d < 8; ++d) {
         const int f = d < len[u] ? (int)((creators[u] >> (8 * d)) & 0xff) : 0;
-        path_node[d] = s.kept_base[f] + (d - s.kept_m[f]);
+        path_node[u][d] = s.kept_base[f] + (d - s.kept_m[f]);
+        path_tok[u][d] = s.ids[(int)((ck[u] >> (7 * d)) & 0x7f) & 63];
       }
 #pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int c = lane + 64 * u;
+      int par = 0, leaf = 0;
+      bool whole = true;  // every level of the draft has its node (none cut by the node cap)
+      unsigned long long m0 = 1ull, m1 = 0ull;  // ancestors so far: the root
+#pragma unroll
       for (int d = 0; d < 8; ++d) {
-        if (d >= len[u]) break;
         const int f = (int)((creators[u] >> (8 * d)) & 0xff);
-        const int node = path_node[d];
-        if (node >= max_nodes) { leaf = -1; break; }
+        const int node = path_node[u][d];
+        const bool level = c < n_c && d < len[u];
+        const bool exists = level && node < max_nodes;
+        whole = whole && (!level || exists);
         // raw layout: a blank, or a token equal to the raw token right before it, is removed by the CTC transform -
         // it sees its own prefix but nothing below it sees it
         const int code = (int)((ck[u] >> (7 * d)) & 0x7f);
         const bool removed = RAW && (code == s.blank_code || (d > 0 && code == (int)((ck[u] >> (7 * (d - 1))) & 0x7f)));
-        const unsigned long long b0 = node < 64 ? 1ull << node : 0ull, b1 = node < 64 ? 0ull : 1ull << (node - 64);
-        if (f == c) {
-          node_token[node] = s.ids[code];
-          node_parent[node] = par;
-          node_depth[node] = d + 1;
-          mask[(size_t)node * W] = m0 | b0;
-          if (W > 1) mask[(size_t)node * W + 1] = m1 | b1;
-          if (RAW) p.node_removed[(size_t)b * max_nodes + node] = removed ? 1 : 0;
+        const unsigned long long b0 = node < 64 ? 1ull << (node & 63) : 0ull, b1 = node < 64 ? 0ull : 1ull << (node & 63);
+        if (exists && f == c) {
+          st_tok[node] = path_tok[u][d];
+          st_par[node] = par;
+          st_dep[node] = d + 1;
+          st_mask[2 * node] = m0 | b0;
+          st_mask[2 * node + 1] = m1 | b1;
+          if (RAW) st_rem[node] = removed ? 1 : 0;
         }
-        if (!removed) { m0 |= b0; m1 |= b1; }
-        par = node;
-        leaf = node;
+        if (exists && !removed) { m0 |= b0; m1 |= b1; }
+        par = exists ? node : par;
+        leaf = exists ? node : leaf;
       }
-      p.cand_leaf[(size_t)b * beam + c] = leaf;
+      if (c < n_c) p.cand_leaf[(size_t)b * beam + c] = (whole && len[u] > 0) ? leaf : -1;
     }
   } else {
     // ---- draft arrays, by the other wavefronts ----------------------------------------------------
@@ -820,7 +843,14 @@ __global__ __launch_bounds__(kThreads) void collapse_tree_kernel(CollapseParams 
       mask[0] = 1ull;
       if (W > 1) mask[1] = 0ull;
       if (RAW) p.node_removed[(size_t)b * max_nodes] = 0;
-    } else if (i >= n_nodes) {
+    } else if (i < n_nodes) {
+      node_token[i] = st_tok[i];
+      node_parent[i] = st_par[i];
+      node_depth[i] = st_dep[i];
+      mask[(size_t)i * W] = st_mask[2 * i];
+      if (W > 1) mask[(size_t)i * W + 1] = st_mask[2 * i + 1];
+      if (RAW) p.node_removed[(size_t)b * max_nodes + i] = st_rem[i];
+    } else {
       if (RAW) p.node_removed[(size_t)b * max_nodes + i] = -1;
       node_token[i] = -1;
       node_parent[i] = -1;
