@@ -59,8 +59,8 @@ def parse_args():
                     help="training positions of the ctc_loss line, each with T frames over V+1 symbols")
     ap.add_argument("--draft-layer-ffn", type=int, default=0,
                     help="feed-forward width of the draft module's layer (0: the base family's, 43/16 of D)")
-    ap.add_argument("--cpu-steps", type=int, default=6, help="oracle steps timed with all BLAS threads")
-    ap.add_argument("--cpu-steps-one-thread", type=int, default=2, help="oracle steps timed with one BLAS thread")
+    ap.add_argument("--cpu-steps", type=int, default=12, help="oracle steps timed with all BLAS threads")
+    ap.add_argument("--cpu-steps-one-thread", type=int, default=4, help="oracle steps timed with one BLAS thread")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run ten 256 MiB device copies (known traffic, for scaling rocprofv3 HBM counters)")
     return ap.parse_args()
