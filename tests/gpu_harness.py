@@ -22,6 +22,19 @@ def rel_err_rms_floor(got: np.ndarray, ref: np.ndarray) -> float:
     return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), max(rms, 1e-30))))
 
 
+def rel_err_plain_above_rms(got: np.ndarray, ref: np.ndarray) -> float:
+    """max_i |g_i - o_i| / |o_i| over the entries with |o_i| >= rms(o): the plain relative error where it is defined.
+    It can never exceed rel_err_rms_floor (on these entries the two denominators are the same); the tests assert it
+    next to the floored metric so that the plain 2e-3 figure is visible as such."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = float(np.sqrt(np.mean(ref ** 2)))
+    big = np.abs(ref) >= max(rms, 1e-30)
+    if not big.any():
+        return 0.0
+    return float(np.max(np.abs(got - ref)[big] / np.abs(ref)[big]))
+
+
 def oracle_stage3(topk_id, topk_logp, root_token, cfg_blank, beam, max_nodes):
     """Run the oracle's collapse/tree stage for every sequence of a batch on (GPU-produced) top-k lists."""
     return [oracle.collapse_tree(topk_id[b], np.asarray(topk_logp[b], dtype=np.float32), int(root_token[b]),
