@@ -50,6 +50,11 @@ struct SkinnyParams {
   int plane_cols, col0;
   const void* zeros;  // 256 bytes
   float* part;        // [total_waves][kSgAcc][nt][16 columns][16 rows]
+  // first pass of the layer (FIRST): x is the layer's input [plane_cols][K] bf16 as given, the kernel multiplies it
+  // by gain [K] bf16 while staging it (the products are exact as two bf16 numbers) and the first workgroup of every
+  // k group leaves the sums of x^2 over each 256 elements in ss_out [plane_cols][K / 256]
+  const void* gain;
+  float* ss_out;
   SkinnyPlan plan;
 };
 
@@ -59,7 +64,9 @@ typedef __attribute__((address_space(1))) u32x4 GlobalVec4;  // a pointer made f
 // c of the pass is MFMA column c (high parts) and column cols + c (low parts), and the two products are added
 // when the partial tiles are.  The weights are bf16 as stored, so the products lose nothing to a rounding of
 // the activations.
-template <int STAGES, int NT>
+__device__ __forceinline__ unsigned short float_to_bf16_bits(float f);
+
+template <int STAGES, int NT, bool FIRST>
 __global__ __launch_bounds__(64 * kSgWaves) void skinny_gemm_bf16_kernel(SkinnyParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -85,19 +92,31 @@ __global__ __launch_bounds__(64 * kSgWaves) void skinny_gemm_bf16_kernel(SkinnyP
   unsigned char* wst = smem + pl.hs_bytes + wave * kSgStripBytes;
 
   // ---- activation slice of the group -> LDS (loads unconditional, indices clamped) -----------------------
+  // FIRST: a piece of the input and the matching piece of the gain per (column, 16 bytes); both planes of the
+  // slice are made from them when the pieces are written to LDS.  Half as many (column, piece) pairs, the same
+  // number of loads.
   const int per_row = Cg * 32;  // 16-byte pieces per column
-  const int hs_total = vcols * per_row;
+  const int hs_total = (FIRST ? pl.cols : vcols) * per_row;
+  constexpr int kLoads = FIRST ? kSgHsPieces / 2 : kSgHsPieces;
   u32x4 hreg[kSgHsPieces];
-  int hs_dst[kSgHsPieces];
+  int hs_dst[kLoads];
+  int ss_dst[kLoads];  // FIRST: where the piece's 32-lane group leaves its sum of squares, -1: nowhere
 #pragma unroll
-  for (int u = 0; u < kSgHsPieces; ++u) {
+  for (int u = 0; u < kLoads; ++u) {
     const int idx = tid + u * 64 * kSgWaves;
     const int cl = idx < hs_total ? idx : hs_total - 1;
     const int m = cl / per_row, q = cl - m * per_row;
-    const int plane = m >= pl.cols ? 1 : 0, col = m - plane * pl.cols;
     hs_dst[u] = idx < hs_total ? m * HSS + q * 16 : -1;
-    hreg[u] = *(const u32x4*)((const unsigned char*)p.x +
-                              ((size_t)plane * p.plane_cols + p.col0 + col) * pl.K * 2 + (size_t)chunk_begin * 512 + q * 16);
+    if constexpr (FIRST) {
+      hreg[2 * u] = *(const u32x4*)((const unsigned char*)p.x + (size_t)(p.col0 + m) * pl.K * 2 +
+                                    (size_t)chunk_begin * 512 + q * 16);
+      hreg[2 * u + 1] = *(const u32x4*)((const unsigned char*)p.gain + (size_t)chunk_begin * 512 + q * 16);
+      ss_dst[u] = idx < hs_total ? (p.col0 + m) * (pl.K / 256) + chunk_begin + (q >> 5) : -1;
+    } else {
+      const int plane = m >= pl.cols ? 1 : 0, col = m - plane * pl.cols;
+      hreg[u] = *(const u32x4*)((const unsigned char*)p.x +
+                                ((size_t)plane * p.plane_cols + p.col0 + col) * pl.K * 2 + (size_t)chunk_begin * 512 + q * 16);
+    }
   }
   __builtin_amdgcn_sched_barrier(0);
 
@@ -175,9 +194,42 @@ __global__ __launch_bounds__(64 * kSgWaves) void skinny_gemm_bf16_kernel(SkinnyP
   for_each_stage([&](auto st) __attribute__((always_inline)) {
     if constexpr (decltype(st)::value < STAGES - 1) request(decltype(st)::value, st);
   });
+  if constexpr (FIRST) {
+    const bool leaves_sums = (int)blockIdx.x * kSgWaves == wave_begin;  // the k group's first workgroup
 #pragma unroll
-  for (int u = 0; u < kSgHsPieces; ++u)
-    if (hs_dst[u] >= 0) *(u32x4*)(hs + hs_dst[u]) = hreg[u];
+    for (int u = 0; u < kLoads; ++u) {
+      const u32x4 xv = hreg[2 * u], gv = hreg[2 * u + 1];
+      u32x4 hi, lo;
+      float ss = 0.f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        // two bf16 numbers per word: the low half is the earlier element
+        const float x0 = __uint_as_float(xv[e] << 16), x1 = __uint_as_float(xv[e] & 0xffff0000u);
+        const float v0 = x0 * __uint_as_float(gv[e] << 16), v1 = x1 * __uint_as_float(gv[e] & 0xffff0000u);
+        const unsigned int h0 = float_to_bf16_bits(v0), h1 = float_to_bf16_bits(v1);
+        const unsigned int l0 = float_to_bf16_bits(v0 - __uint_as_float(h0 << 16));
+        const unsigned int l1 = float_to_bf16_bits(v1 - __uint_as_float(h1 << 16));
+        hi[e] = h0 | (h1 << 16);
+        lo[e] = l0 | (l1 << 16);
+        ss = fmaf(x1, x1, fmaf(x0, x0, ss));
+      }
+      if (hs_dst[u] >= 0) {
+        *(u32x4*)(hs + hs_dst[u]) = hi;
+        *(u32x4*)(hs + hs_dst[u] + pl.cols * HSS) = lo;
+      }
+      if (leaves_sums) {
+        // 256 elements are 32 consecutive pieces = the lanes of half a wavefront (a group is all live or all
+        // clamped: the slice is a whole number of such groups); fixed order, the same bits on every run
+#pragma unroll
+        for (int o = 16; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+        if ((lane & 31) == 0 && ss_dst[u] >= 0) p.ss_out[ss_dst[u]] = ss;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int u = 0; u < kLoads; ++u)
+      if (hs_dst[u] >= 0) *(u32x4*)(hs + hs_dst[u]) = hreg[u];
+  }
   lds_barrier();
   for (int i0 = 0; i0 < n; i0 += STAGES) {
     for_each_stage([&](auto st) __attribute__((always_inline)) {
@@ -245,7 +297,6 @@ struct LayerParams {
   float eps, log2_theta;
   // workspace
   // activations that feed a matrix product are [2][B*T][K] bf16: high parts, then low parts
-  unsigned short* xn;          // [2][B*T][D] normalised input
   unsigned short* q;           // [B][H][T][dh]
   float* attn;                 // [B][H][T][dh] attention output
   unsigned short* arows;       // [2][B*T][D] attention output, heads side by side
@@ -275,29 +326,17 @@ __device__ __forceinline__ float inv_rms(const float* __restrict__ ss, int col, 
   return 1.0f / sqrtf(t / (float)D + eps);
 }
 
-// x * ln1 (as two bf16 numbers) and the partial sums of x^2; one block per (column, 256 elements).  Block 0 also
-// writes the row counts and the causal mask that the attention call takes.
-__global__ __launch_bounds__(256) void dl_scale_in_kernel(LayerParams p) {
-  __shared__ float red[4];
-  const int nseg = p.D / 256;
-  const int col = blockIdx.x / nseg, seg = blockIdx.x - col * nseg, tid = threadIdx.x;
-  const size_t o = (size_t)col * p.D + seg * 256 + tid;
-  const float v = bf16_bits_to_float(p.x[o]);
-  store_split(p.xn, (size_t)p.B * p.T * p.D, o, v * bf16_bits_to_float(p.ln1[seg * 256 + tid]));
-  const float ss = block_sum_256(v * v, red);
-  if (tid == 0) p.ss1[blockIdx.x] = ss;
-  if (blockIdx.x == 0) {
-    for (int i = tid; i < p.B; i += 256) p.n_rows[i] = p.T;
-    for (int i = tid; i < p.B * p.T; i += 256) {
+// q, k, v of the pass's columns: sum of the partial tiles times the norm's scalar (the first pass took x * gain and
+// left the sums of x^2), rotary embedding on q and k, bf16, head-major layout
+__global__ __launch_bounds__(256) void dl_qkv_finish_kernel(LayerParams p, SkinnyPlan pl) {
+  if (blockIdx.x == 0 && p.col0 == 0) {
+    // the row counts and the causal mask that the attention call takes
+    for (int i = threadIdx.x; i < p.B; i += 256) p.n_rows[i] = p.T;
+    for (int i = threadIdx.x; i < p.B * p.T; i += 256) {
       const int t = i % p.T;
       p.causal[i] = t >= 63 ? ~0ull : ((2ull << t) - 1ull);
     }
   }
-}
-
-// q, k, v of the pass's columns: sum of the partial tiles times the norm's scalar, rotary embedding on q and k,
-// bf16, head-major layout
-__global__ __launch_bounds__(256) void dl_qkv_finish_kernel(LayerParams p, SkinnyPlan pl) {
   const int half = p.dh / 2;
   const int per_col = 3 * p.H * half;
   for (int idx = blockIdx.x * 256 + threadIdx.x; idx < p.cols * per_col; idx += gridDim.x * 256) {
@@ -418,14 +457,14 @@ static bool make_plan(SkinnyPlan& pl, int N, int K, int cols, int cus) {
 }
 
 struct LayerWorkspace {
-  size_t xn, q, attn, arows, h1, xn2, act, n_rows, causal, ss1, ss2, part, total;
+  size_t q, attn, arows, h1, xn2, act, n_rows, causal, ss1, ss2, part, total;
 };
 static LayerWorkspace layer_workspace(int B, int T, int D, int H, int F, int cus) {
   LayerWorkspace w;
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t at = off; off = (off + bytes + 255) / 256 * 256; return at; };
   const size_t BT = (size_t)B * T;
-  w.xn = carve(BT * D * 4); w.q = carve(BT * D * 2); w.attn = carve(BT * D * 4); w.arows = carve(BT * D * 4);
+  w.q = carve(BT * D * 2); w.attn = carve(BT * D * 4); w.arows = carve(BT * D * 4);
   w.h1 = carve(BT * D * 4); w.xn2 = carve(BT * D * 4); w.act = carve(BT * F * 4);
   w.n_rows = carve((size_t)B * 4); w.causal = carve(BT * 8);
   w.ss1 = carve(BT * (D / 256 + 1) * 4); w.ss2 = carve(BT * (D / 256 + 1) * 4);
@@ -443,24 +482,29 @@ static LayerWorkspace layer_workspace(int B, int T, int D, int H, int F, int cus
   return w;
 }
 
-template <int NT>
+template <int NT, bool FIRST>
 static hipError_t launch_skinny_nt(const SkinnyParams& sp, hipStream_t stream) {
   const int lds = sp.plan.hs_bytes + kSgWaves * kSgStripBytes;
-  hipLaunchKernelGGL((skinny_gemm_bf16_kernel<kSgStages, NT>), dim3(sp.plan.total_waves / kSgWaves),
+  hipLaunchKernelGGL((skinny_gemm_bf16_kernel<kSgStages, NT, FIRST>), dim3(sp.plan.total_waves / kSgWaves),
                      dim3(64 * kSgWaves), lds, stream, sp);
   return hipGetLastError();
 }
-static hipError_t launch_skinny(const SkinnyParams& sp, hipStream_t stream) {
-  return sp.plan.nt == 1 ? launch_skinny_nt<1>(sp, stream) : launch_skinny_nt<2>(sp, stream);
+// first: the layer's first pass (sp.gain and sp.ss_out set, sp.x the input as given)
+static hipError_t launch_skinny(const SkinnyParams& sp, bool first, hipStream_t stream) {
+  if (first) return sp.plan.nt == 1 ? launch_skinny_nt<1, true>(sp, stream) : launch_skinny_nt<2, true>(sp, stream);
+  return sp.plan.nt == 1 ? launch_skinny_nt<1, false>(sp, stream) : launch_skinny_nt<2, false>(sp, stream);
 }
 
 hipError_t prepare_draft_layer() {
-  hipError_t e = hipFuncSetAttribute((const void*)skinny_gemm_bf16_kernel<kSgStages, 1>,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
-  if (e == hipSuccess)
-    e = hipFuncSetAttribute((const void*)skinny_gemm_bf16_kernel<kSgStages, 2>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
-  return e;
+  const void* kernels[] = {(const void*)skinny_gemm_bf16_kernel<kSgStages, 1, false>,
+                           (const void*)skinny_gemm_bf16_kernel<kSgStages, 2, false>,
+                           (const void*)skinny_gemm_bf16_kernel<kSgStages, 1, true>,
+                           (const void*)skinny_gemm_bf16_kernel<kSgStages, 2, true>};
+  for (const void* k : kernels) {
+    const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace ctcspec
@@ -494,7 +538,7 @@ extern "C" int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
                            D / H <= ctx->lim.max_head_dim,
                   CTCSPEC_EUNSUPPORTED, "draft_layer_forward: shape exceeds the context's limits");
   CTCSPEC_REQUIRE(ctx, rms_eps >= 0.f && rope_theta > 1.f, CTCSPEC_EINVAL, "draft_layer_forward: bad eps or theta");
-  const void* ptrs[] = {x, w->wqkv, w->wo, w->wgu, w->wd, workspace, q_out, k_new, v_new, out, k_cache, v_cache};
+  const void* ptrs[] = {x, w->ln1, w->wqkv, w->wo, w->wgu, w->wd, workspace, q_out, k_new, v_new, out, k_cache, v_cache};
   for (const void* q : ptrs)
     CTCSPEC_REQUIRE(ctx, aligned16(q), CTCSPEC_EINVAL, "draft_layer_forward: pointers must be 16-byte aligned");
   const int cus = device_cus();
@@ -507,7 +551,7 @@ extern "C" int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
   p.x = (const unsigned short*)x; p.ln1 = (const unsigned short*)w->ln1; p.ln2 = (const unsigned short*)w->ln2;
   p.pos0 = pos0; p.B = B; p.T = T; p.D = D; p.H = H; p.dh = D / H; p.F = F;
   p.eps = rms_eps; p.log2_theta = log2f(rope_theta);
-  p.xn = (unsigned short*)(ws + lw.xn); p.q = q_out ? (unsigned short*)q_out : (unsigned short*)(ws + lw.q); p.attn = (float*)(ws + lw.attn);
+  p.q = q_out ? (unsigned short*)q_out : (unsigned short*)(ws + lw.q); p.attn = (float*)(ws + lw.attn);
   p.arows = (unsigned short*)(ws + lw.arows); p.h1 = (float*)(ws + lw.h1); p.xn2 = (unsigned short*)(ws + lw.xn2);
   p.act = (unsigned short*)(ws + lw.act); p.n_rows = (int32_t*)(ws + lw.n_rows);
   p.causal = (unsigned long long*)(ws + lw.causal); p.ss1 = (float*)(ws + lw.ss1); p.ss2 = (float*)(ws + lw.ss2);
@@ -517,14 +561,16 @@ extern "C" int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
   hipStream_t st = ctx->stream;
 
   // one pass over a weight matrix per block of 16 columns, each followed by the kernel that consumes the tiles
-  auto gemm_passes = [&](const void* wmat, int N, int K, const unsigned short* xin, auto&& finish) -> int {
+  auto gemm_passes = [&](const void* wmat, int N, int K, const unsigned short* xin, bool first, auto&& finish) -> int {
     for (int col0 = 0; col0 < BT; col0 += kSgMaxCols) {
       SkinnyParams sp;
+      sp.gain = first ? (const void*)p.ln1 : nullptr;
+      sp.ss_out = first ? p.ss1 : nullptr;
       const int cols = BT - col0 < kSgMaxCols ? BT - col0 : kSgMaxCols;
       CTCSPEC_REQUIRE(ctx, make_plan(sp.plan, N, K, cols, cus), CTCSPEC_EUNSUPPORTED,
                       "draft_layer_forward: a %d x %d matrix does not fit the streaming kernel", N, K);
       sp.w = wmat; sp.x = xin; sp.plane_cols = BT; sp.col0 = col0; sp.zeros = ctx->zeros; sp.part = (float*)(ws + lw.part);
-      CTCSPEC_HIP(ctx, launch_skinny(sp, st));
+      CTCSPEC_HIP(ctx, launch_skinny(sp, first, st));
       p.col0 = col0; p.cols = cols;
       finish(sp.plan);
       CTCSPEC_HIP(ctx, hipGetLastError());
@@ -533,9 +579,7 @@ extern "C" int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
   };
   auto blocks_for = [](long long n) { long long b = (n + 255) / 256; return (unsigned)(b > 1024 ? 1024 : (b < 1 ? 1 : b)); };
 
-  hipLaunchKernelGGL(dl_scale_in_kernel, dim3(BT * (D / 256)), dim3(256), 0, st, p);
-  CTCSPEC_HIP(ctx, hipGetLastError());
-  int rc = gemm_passes(w->wqkv, 3 * D, D, p.xn, [&](const SkinnyPlan& pl) {
+  int rc = gemm_passes(w->wqkv, 3 * D, D, p.x, true, [&](const SkinnyPlan& pl) {
     hipLaunchKernelGGL(dl_qkv_finish_kernel, dim3(blocks_for((long long)p.cols * 3 * H * (p.dh / 2))), dim3(256), 0, st, p, pl);
   });
   if (rc != CTCSPEC_OK) return rc;
@@ -548,15 +592,15 @@ extern "C" int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
     hipLaunchKernelGGL(dl_attn_rows_kernel, dim3(blocks_for((long long)BT * D)), dim3(256), 0, st, p);
     CTCSPEC_HIP(ctx, hipGetLastError());
   }
-  rc = gemm_passes(w->wo, D, D, p.arows, [&](const SkinnyPlan& pl) {
+  rc = gemm_passes(w->wo, D, D, p.arows, false, [&](const SkinnyPlan& pl) {
     hipLaunchKernelGGL(dl_oproj_finish_kernel, dim3(p.cols * (D / 256)), dim3(256), 0, st, p, pl);
   });
   if (rc != CTCSPEC_OK) return rc;
-  rc = gemm_passes(w->wgu, 2 * F, D, p.xn2, [&](const SkinnyPlan& pl) {
+  rc = gemm_passes(w->wgu, 2 * F, D, p.xn2, false, [&](const SkinnyPlan& pl) {
     hipLaunchKernelGGL(dl_gate_finish_kernel, dim3(blocks_for((long long)p.cols * F)), dim3(256), 0, st, p, pl);
   });
   if (rc != CTCSPEC_OK) return rc;
-  rc = gemm_passes(w->wd, D, F, p.act, [&](const SkinnyPlan& pl) {
+  rc = gemm_passes(w->wd, D, F, p.act, false, [&](const SkinnyPlan& pl) {
     hipLaunchKernelGGL(dl_down_finish_kernel, dim3(blocks_for((long long)p.cols * D)), dim3(256), 0, st, p, pl);
   });
   return rc;
