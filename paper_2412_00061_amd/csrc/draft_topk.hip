@@ -361,7 +361,8 @@ __global__ __launch_bounds__(64 * kTileWaves) void lmhead_bf16_tile_kernel(LmHea
   GemmTileArgs t;
   t.w = p.w; t.hidden = p.hidden; t.zeros = p.zeros; t.D = p.D; t.V = p.Vp1; t.cols = p.BT; t.row_base = row_base;
   f32x4 acc[4][CT];
-  gemm_tile_128<kLmTileDist, CT>(t, smem, acc);
+  static_assert(CT == 1, "the 128 x 64 tile");
+  gemm_tile<kLmTileDist, Tile128x64>(t, smem, acc);
   // (the loop's last barrier has every wavefront done with the LDS tiles)
   float* zbuf = (float*)smem;
 #pragma unroll
@@ -387,7 +388,7 @@ __global__ __launch_bounds__(64 * kTileWaves) void lmhead_bf16_tile_kernel(LmHea
   else if (p.k <= 4) lmhead_block_epilogue_wide<4>(p, zbuf, part);
   else lmhead_block_epilogue_wide<8>(p, zbuf, part);
 }
-static_assert(kMaxCols <= 64 && kMaxCols * kZStride * 4 + kMfmaWaves * kMaxCols * (8 + 8 * kMaxTopk) <= tile_lds_bytes<1>(),
+static_assert(kMaxCols <= 64 && kMaxCols * kZStride * 4 + kMfmaWaves * kMaxCols * (8 + 8 * kMaxTopk) <= Tile128x64::LDS_BYTES,
               "one 64-column tile holds every column and the epilogue's partials");
 
 static void launch_merge(const LmHeadParams& p, hipStream_t stream) {
@@ -452,7 +453,7 @@ static hipError_t allow_large_lds() {
   if (e == hipSuccess) e = allow_mfma_lds<4, 2>();
   if (e == hipSuccess)
     e = hipFuncSetAttribute((const void*)lmhead_bf16_tile_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            tile_lds_bytes<1>());
+                            Tile128x64::LDS_BYTES);
   return e;
 }
 
@@ -584,7 +585,7 @@ static int draft_topk_launch(ctcspec_ctx* err, hipStream_t stream, const LmScrat
     if (D % kTileStepK == 0 && p.BT <= 64 && (long long)Vp1 * D * 2 < (1LL << 32)) {
       // more columns than that: both operands step through LDS
       if (timing) CTCSPEC_HIP(err, hipEventRecord(ev0, stream));
-      hipLaunchKernelGGL(lmhead_bf16_tile_kernel<1>, dim3(p.n_blocks), dim3(64 * kTileWaves), tile_lds_bytes<1>(),
+      hipLaunchKernelGGL(lmhead_bf16_tile_kernel<1>, dim3(p.n_blocks), dim3(64 * kTileWaves), Tile128x64::LDS_BYTES,
                          stream, p);
       CTCSPEC_HIP(err, hipGetLastError());
       if (timing) {

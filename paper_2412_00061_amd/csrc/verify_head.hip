@@ -3,9 +3,10 @@
 //
 // The head is the same stream over a [V, D] weight matrix as the draft head, but with up to 128 columns
 // (one per tree node) instead of 8, and all that is kept of a column is its best (logit, id) key:
-//   * verify_head_bf16_kernel    - bf16, D a multiple of 128: MFMA, 128 vocabulary rows x 128 columns
-//                                  per workgroup; all column blocks in one launch, those of a row block side by
-//                                  side on one XCD (the weights come from HBM once)
+//   * verify_head_bf16_kernel    - bf16, D a multiple of 128: MFMA, 128 vocabulary rows x 128 columns per
+//                                  workgroup (256 x 128 when there are several column blocks); all column blocks
+//                                  in one launch, those of a row block side by side on one XCD (the weights come
+//                                  from HBM once)
 //   * verify_head_generic_kernel - any dtype/shape: plain fp32 FMA, one atomic max per (row block, column)
 //   * verify_head_merge_kernel   - best key over the row blocks -> token id, -1 for rows without a node
 #include "gemm_tile.h"
@@ -16,10 +17,14 @@ constexpr int kVhCols = kVerifyCols;            // columns (tree nodes) per pass
 constexpr int kVhWaves = kTileWaves;
 constexpr int kVhDist = 4;                      // prefetch distance in steps = register stages per operand
 constexpr int kVhStepK = kTileStepK;
-constexpr int kVhLdsBytes = tile_lds_bytes<2>();
-constexpr int kVhZStride = kRowsPerBlock + 4;   // floats per column of the logit block
-static_assert(kVhCols == 128 && kRowsPerBlock == 128, "tile shape");
-static_assert(kVhCols * kVhZStride * 4 <= kVhLdsBytes, "logit block fits the staging area");
+// dynamic LDS of a tile shape: the staging buffers, or the logit block (column-major, 4 floats of pad per column)
+// when the caller asks for logits - whichever is larger
+template <typename SH>
+constexpr int vh_lds_bytes() {
+  return SH::LDS_BYTES > kVhCols * (SH::ROWS + 4) * 4 ? SH::LDS_BYTES : kVhCols * (SH::ROWS + 4) * 4;
+}
+static_assert(kVhCols == 128 && Tile128x128::COLS == kVhCols && Tile256x128::COLS == kVhCols, "tile shape");
+static_assert(vh_lds_bytes<Tile256x128>() <= 160 * 1024, "fits the compute unit's LDS");
 
 struct VerifyHeadParams {
   const void* hidden;   // [cols_total][D]
@@ -28,7 +33,7 @@ struct VerifyHeadParams {
   int cols_total;       // all columns of the call; the bf16 kernel covers them in one launch, block by block
   int col_blocks;       // ceil(cols_total / kVhCols)
   int D, V;
-  int n_blocks;         // row blocks of 128
+  int n_blocks;         // row blocks (of the tile shape's rows: 128 or 256)
   unsigned long long* pkey;  // [col_blocks][n_blocks][kVhCols] best key per (column block, row block, column)
   float* logits_out;    // [cols_total][V] or null
   const void* zeros;    // 256 bytes of zeros
@@ -38,13 +43,15 @@ struct VerifyHeadParams {
 };
 
 // ---- bf16 MFMA kernel: the shared 128 x 128 tile loop, then the best (logit, id) key per column -----------------
-template <int DIST>
+template <int DIST, typename SH>
 __global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyHeadParams p) {
+  constexpr int ROWS = SH::ROWS, CTW = SH::CTW, WR = SH::WR;
+  constexpr int ZSTRIDE = ROWS + 4;  // floats per column of the logit block
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int NTHREADS = 64 * kVhWaves;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wr = wave >> 2, wc = wave & 3;
+  const int wr = wave / SH::WC, wc = wave % SH::WC;
   const int c = lane & 15, g = lane >> 4;
   // Workgroup -> (row block, column block).  Workgroups are dealt to the 8 XCDs round robin, and each XCD has its
   // own L2: the column blocks of one row block get workgroup numbers that differ by multiples of 8 and are
@@ -56,12 +63,12 @@ __global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyH
   if (rb >= p.n_blocks) return;
   const int col0 = cb * kVhCols;
   const int cols = p.cols_total - col0 < kVhCols ? p.cols_total - col0 : kVhCols;
-  const int row_base = rb * kRowsPerBlock;
+  const int row_base = rb * ROWS;
   GemmTileArgs t;
   t.w = p.w; t.hidden = (const unsigned char*)p.hidden + (size_t)col0 * p.D * 2; t.zeros = p.zeros;
   t.D = p.D; t.V = p.V; t.cols = cols; t.row_base = row_base;
-  f32x4 acc[4][2];
-  gemm_tile_128<DIST, 2>(t, smem, acc);
+  f32x4 acc[4][CTW];
+  gemm_tile<DIST, SH>(t, smem, acc);
 
   // ---- best (logit, id) key per column ---------------------------------------------------------------------
   // (the loop's last barrier has every wavefront done with the LDS tiles)
@@ -71,20 +78,20 @@ __global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyH
 #pragma unroll
     for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct)
-        *(f32x4*)(zbuf + (wc * 32 + ct * 16 + c) * kVhZStride + wr * 64 + rt * 16 + g * 4) = acc[rt][ct];
+      for (int ct = 0; ct < CTW; ++ct)
+        *(f32x4*)(zbuf + (wc * 16 * CTW + ct * 16 + c) * ZSTRIDE + wr * 64 + rt * 16 + g * 4) = acc[rt][ct];
     __syncthreads();
-    for (int idx = tid; idx < cols * kRowsPerBlock; idx += NTHREADS) {
-      const int m = idx / kRowsPerBlock, r = idx % kRowsPerBlock;
-      if (row_base + r < p.V) p.logits_out[(size_t)(col0 + m) * p.V + row_base + r] = zbuf[m * kVhZStride + r];
+    for (int idx = tid; idx < cols * ROWS; idx += NTHREADS) {
+      const int m = idx / ROWS, r = idx % ROWS;
+      if (row_base + r < p.V) p.logits_out[(size_t)(col0 + m) * p.V + row_base + r] = zbuf[m * ZSTRIDE + r];
     }
     __syncthreads();
   }
-  // a lane holds 16 rows of two columns: best of those, then over the 4 lane groups (64 rows), then over the
-  // two wavefronts that share the columns
-  unsigned long long* kbuf = (unsigned long long*)smem;  // [2][128]
+  // a lane holds 16 rows of CTW columns: best of those, then over the 4 lane groups (64 rows), then over the
+  // WR wavefronts that share the columns
+  unsigned long long* kbuf = (unsigned long long*)smem;  // [WR][128]
 #pragma unroll
-  for (int ct = 0; ct < 2; ++ct) {
+  for (int ct = 0; ct < CTW; ++ct) {
     unsigned long long best = 0ull;
 #pragma unroll
     for (int rt = 0; rt < 4; ++rt)
@@ -98,12 +105,17 @@ __global__ __launch_bounds__(64 * kVhWaves) void verify_head_bf16_kernel(VerifyH
     best = o > best ? o : best;
     o = __shfl_xor(best, 32);
     best = o > best ? o : best;
-    if (g == 0) kbuf[wr * kVhCols + wc * 32 + ct * 16 + c] = best;
+    if (g == 0) kbuf[wr * kVhCols + wc * 16 * CTW + ct * 16 + c] = best;
   }
   __syncthreads();
   if (tid < cols) {
-    const unsigned long long k0 = kbuf[tid], k1 = kbuf[kVhCols + tid];
-    p.pkey[((size_t)cb * p.n_blocks + rb) * kVhCols + tid] = k0 > k1 ? k0 : k1;
+    unsigned long long best = kbuf[tid];
+#pragma unroll
+    for (int r = 1; r < WR; ++r) {
+      const unsigned long long o = kbuf[r * kVhCols + tid];
+      best = o > best ? o : best;
+    }
+    p.pkey[((size_t)cb * p.n_blocks + rb) * kVhCols + tid] = best;
   }
 }
 
@@ -205,8 +217,12 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(KvCommitParams p) {
 }
 
 hipError_t prepare_verify_head() {
-  return hipFuncSetAttribute((const void*)verify_head_bf16_kernel<kVhDist>,
-                             hipFuncAttributeMaxDynamicSharedMemorySize, kVhLdsBytes);
+  hipError_t e = hipFuncSetAttribute((const void*)verify_head_bf16_kernel<kVhDist, Tile128x128>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, vh_lds_bytes<Tile128x128>());
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute((const void*)verify_head_bf16_kernel<kVhDist, Tile256x128>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, vh_lds_bytes<Tile256x128>());
+  return e;
 }
 
 }  // namespace ctcspec
@@ -241,12 +257,21 @@ extern "C" int verify_head_argmax(ctcspec_ctx* ctx, ctcspec_dtype dt, const void
                   "verify_head_argmax: %lld columns exceed the context's workspace", cols_total);
   if (wide) {
     // one launch for every column block (the kernel's workgroup numbering keeps a row block's column blocks on
-    // one XCD), one merge launch over all columns
+    // one XCD), one merge launch over all columns.  One column block: 128-row tiles, one workgroup per compute
+    // unit, the stream from HBM sets the pace.  Several: 256-row tiles - the workgroups of a row block share the
+    // weight tile through L2 and the loop's own LDS traffic sets the pace, which the larger tile halves per flop.
     p.col0 = 0; p.cols = 0;
+    const bool tall = p.col_blocks > 1;
+    const int rows = tall ? Tile256x128::ROWS : Tile128x128::ROWS;
+    p.n_blocks = (V + rows - 1) / rows;
     const long long grid = (long long)((p.n_blocks + 7) / 8) * 8 * p.col_blocks;
     CTCSPEC_REQUIRE(ctx, grid <= 0x7fffffffLL, CTCSPEC_EUNSUPPORTED, "verify_head_argmax: grid too large");
-    hipLaunchKernelGGL(verify_head_bf16_kernel<kVhDist>, dim3((unsigned)grid), dim3(64 * kVhWaves), kVhLdsBytes,
-                       ctx->stream, p);
+    if (tall)
+      hipLaunchKernelGGL((verify_head_bf16_kernel<kVhDist, Tile256x128>), dim3((unsigned)grid), dim3(64 * kVhWaves),
+                         vh_lds_bytes<Tile256x128>(), ctx->stream, p);
+    else
+      hipLaunchKernelGGL((verify_head_bf16_kernel<kVhDist, Tile128x128>), dim3((unsigned)grid), dim3(64 * kVhWaves),
+                         vh_lds_bytes<Tile128x128>(), ctx->stream, p);
     CTCSPEC_HIP(ctx, hipGetLastError());
     hipLaunchKernelGGL(verify_head_merge_kernel, dim3((unsigned)cols_total), dim3(64), 0, ctx->stream, p);
     CTCSPEC_HIP(ctx, hipGetLastError());
