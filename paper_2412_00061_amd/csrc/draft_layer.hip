@@ -72,7 +72,9 @@ __global__ __launch_bounds__(64 * kSgWaves) void skinny_gemm_bf16_kernel(SkinnyP
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c = lane & 15, g = lane >> 4;
-  const int lrow = lane >> 5, lch = lane & 31;
+  // the chunks of a row in the lane order that lets the 16 lanes the LDS serves together (l .. l+7, l+16 .. l+23)
+  // write 256 consecutive bytes of the strip
+  const int lrow = lane >> 5, lch = (lane & 7) | ((lane & 16) >> 1) | ((lane & 8) << 1);
   const SkinnyPlan& pl = p.plan;
   // the k group of this workgroup (selected with compares: no indexed access to the kernel arguments)
   int Cg = pl.chunks[0], P = pl.per_wave[0], wave_begin = 0, chunk_begin = 0;

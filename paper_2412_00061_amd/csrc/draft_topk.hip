@@ -27,7 +27,11 @@
 namespace ctcspec {
 
 constexpr int kZStride = kRowsPerBlock + 4;  // floats per column in the LDS logit block
-constexpr int kWRowStride = 512 + 16;        // bytes per staged W row (256 bf16 + pad, conflict-free)
+// bytes per staged W row: 256 bf16 + pad.  The LDS serves a 16-byte access 16 lanes at a time - lanes l .. l+7 with
+// l+16 .. l+23 - so a fragment read (lane = row c, chunk g) is conflict-free when rows c .. c+7 at chunks g and g+1
+// fall on 16 different groups of 4 banks: pitch = 32 mod 64 bytes (with 16 bytes of pad the conflict counter read
+// 8200 cycles per workgroup)
+constexpr int kWRowStride = 512 + 32;
 constexpr int kWStageBytes = 16 * kWRowStride;  // per wave
 constexpr int kMfmaWaves = 8;
 
@@ -216,9 +220,11 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void lmhead_bf16_mfma_kernel(LmHea
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c = lane & 15, g = lane >> 4;
-  const int lrow = lane >> 5, lch = lane & 31;
+  // a load instruction covers two rows x 512 bytes; within a row the lanes take the 16-byte chunks in an order
+  // that lets the 16 lanes the LDS serves together (l .. l+7, l+16 .. l+23) write 256 consecutive bytes
+  const int lrow = lane >> 5, lch = (lane & 7) | ((lane & 16) >> 1) | ((lane & 8) << 1);
   unsigned char* hs = smem;
-  const int HSS = p.KC * 2 + 16;
+  const int HSS = p.KC * 2 + 32;
   unsigned char* wst = smem + p.hs_bytes + wave * kWStageBytes;
   const int row0 = blockIdx.x * kRowsPerBlock + wave * 16;
 
@@ -415,7 +421,7 @@ static int pick_kc(int BT, int D, int stages, int budget) {
   if (D % unit != 0) return 0;
   for (int kc = D; kc >= unit; kc -= unit) {
     if (D % kc != 0) continue;
-    if ((long long)BT * (2 * kc + 16) <= budget) return kc;
+    if ((long long)BT * (2 * kc + 32) <= budget) return kc;
   }
   return 0;
 }
@@ -558,7 +564,7 @@ static int draft_topk_launch(ctcspec_ctx* err, hipStream_t stream, const LmScrat
     }
     if (kc == D) {
       p.KC = kc;
-      p.hs_bytes = p.BT * (2 * kc + 16);
+      p.hs_bytes = p.BT * (2 * kc + 32);
       p.hs_magic = (unsigned int)((0x100000000ull + (unsigned)(kc / 8) - 1) / (unsigned)(kc / 8));
       int lds = p.hs_bytes + kMfmaWaves * kWStageBytes;
       int nt = (p.BT + 15) / 16;
