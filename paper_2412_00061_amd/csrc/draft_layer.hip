@@ -40,6 +40,10 @@ struct SkinnyPlan {
   int chunk_begin[kSgMaxGroups], chunks[kSgMaxGroups];  // in chunks of 256 hidden elements
   int wave_begin[kSgMaxGroups];                 // first wavefront (global index) that works on the group
   int per_wave[kSgMaxGroups];                   // units per wavefront (<= (kSgAcc - 1) * chunks of the group)
+  // ceil(2^32 / d) for d = per_wave and d = chunks of the group: n / d = umulhi(n, magic) for the unit numbers that
+  // occur (n * d < 2^32) - the kernels that add up the partial tiles divide per element, and a division by a
+  // number the compiler does not know costs about forty instructions
+  unsigned int magic_per_wave[kSgMaxGroups], magic_chunks[kSgMaxGroups];
   int total_waves;
   int hs_bytes;                                 // LDS bytes of the activation slice
 };
@@ -249,6 +253,11 @@ __global__ __launch_bounds__(64 * kSgWaves) void skinny_gemm_bf16_kernel(SkinnyP
     for (int nt = 0; nt < NT; ++nt) *(f32x4*)(out + (a * NT + nt) * 256) = acc[a][nt];
 }
 
+// n / d with the plan's magic number for d (ceil(2^32 / d) does not fit 32 bits for d = 1)
+__device__ __forceinline__ int sg_div(int n, int d, unsigned int magic) {
+  return d == 1 ? n : (int)__umulhi((unsigned)n, magic);
+}
+
 // Entry (col, row) of the product: the partial tiles of row tile row/16 - high and low part of the column -
 // added group by group and wavefront by wavefront in ascending order.
 __device__ __forceinline__ float sg_result(const float* __restrict__ part, const SkinnyPlan& pl, int col, int row) {
@@ -259,9 +268,10 @@ __device__ __forceinline__ float sg_result(const float* __restrict__ part, const
 #pragma unroll 1
   for (int q = 0; q < pl.groups; ++q) {
     const int Cg = pl.chunks[q], P = pl.per_wave[q];
-    const int first = (r * Cg) / P, last = (r * Cg + Cg - 1) / P;
+    const unsigned int mP = pl.magic_per_wave[q], mC = pl.magic_chunks[q];
+    const int first = sg_div(r * Cg, P, mP), last = sg_div(r * Cg + Cg - 1, P, mP);
     for (int w = first; w <= last; ++w) {
-      const int which = r - (w * P) / Cg;
+      const int which = r - sg_div(w * P, Cg, mC);
       const float* t = part + ((size_t)(pl.wave_begin[q] + w) * kSgAcc + which) * (pl.nt * 256);
       s += t[ohi] + t[olo];
     }
@@ -331,7 +341,7 @@ __device__ __forceinline__ float inv_rms(const float* __restrict__ ss, int col, 
 // q, k, v of the pass's columns: sum of the partial tiles times the norm's scalar (the first pass took x * gain and
 // left the sums of x^2), rotary embedding on q and k, bf16, head-major layout
 __global__ __launch_bounds__(256) void dl_qkv_finish_kernel(LayerParams p, SkinnyPlan pl) {
-  if (blockIdx.x == 0 && p.col0 == 0) {
+  if (blockIdx.x == 0 && blockIdx.y == 0 && p.col0 == 0) {
     // the row counts and the causal mask that the attention call takes
     for (int i = threadIdx.x; i < p.B; i += 256) p.n_rows[i] = p.T;
     for (int i = threadIdx.x; i < p.B * p.T; i += 256) {
@@ -339,14 +349,15 @@ __global__ __launch_bounds__(256) void dl_qkv_finish_kernel(LayerParams p, Skinn
       p.causal[i] = t >= 63 ? ~0ull : ((2ull << t) - 1ull);
     }
   }
+  // grid: (blocks over the column's 3 H dh / 2 pairs, column of the pass) - no division by a runtime number per
+  // element except the one that finds the head
   const int half = p.dh / 2;
   const int per_col = 3 * p.H * half;
-  for (int idx = blockIdx.x * 256 + threadIdx.x; idx < p.cols * per_col; idx += gridDim.x * 256) {
-    const int cl = idx / per_col, rem = idx - cl * per_col;
+  const int cl = blockIdx.y, col = p.col0 + cl, b = col / p.T, t = col - b * p.T;
+  const float inv = inv_rms(p.ss1, col, p.D / 256, p.D, p.eps);
+  for (int rem = blockIdx.x * 256 + threadIdx.x; rem < per_col; rem += gridDim.x * 256) {
     const int hq = rem / half, i = rem - hq * half;  // hq: 0..H-1 q heads, H..2H-1 k heads, 2H..3H-1 v heads
-    const int col = p.col0 + cl, b = col / p.T, t = col - b * p.T;
     const int row = hq * p.dh + i;
-    const float inv = inv_rms(p.ss1, col, p.D / 256, p.D, p.eps);
     float a = inv * sg_result(p.part, pl, cl, row), c = inv * sg_result(p.part, pl, cl, row + half);
     const int kind = hq / p.H, h = hq - kind * p.H;
     if (kind < 2) {
@@ -391,9 +402,9 @@ __global__ __launch_bounds__(256) void dl_oproj_finish_kernel(LayerParams p, Ski
 
 // act = silu(gate) * up; rows [0, F) of the fused matrix are the gate, rows [F, 2F) the up projection
 __global__ __launch_bounds__(256) void dl_gate_finish_kernel(LayerParams p, SkinnyPlan pl) {
-  for (int idx = blockIdx.x * 256 + threadIdx.x; idx < p.cols * p.F; idx += gridDim.x * 256) {
-    const int cl = idx / p.F, f = idx - cl * p.F;
-    const float inv = inv_rms(p.ss2, p.col0 + cl, p.D / 256, p.D, p.eps);
+  const int cl = blockIdx.y;  // grid: (blocks over F, column of the pass)
+  const float inv = inv_rms(p.ss2, p.col0 + cl, p.D / 256, p.D, p.eps);
+  for (int f = blockIdx.x * 256 + threadIdx.x; f < p.F; f += gridDim.x * 256) {
     const float gt = inv * sg_result(p.part, pl, cl, f), up = inv * sg_result(p.part, pl, cl, p.F + f);
     store_split(p.act, (size_t)p.B * p.T * p.F, (size_t)(p.col0 + cl) * p.F + f, gt / (1.0f + expf(-gt)) * up);
   }
@@ -401,8 +412,8 @@ __global__ __launch_bounds__(256) void dl_gate_finish_kernel(LayerParams p, Skin
 
 // out = h1 + feed-forward output
 __global__ __launch_bounds__(256) void dl_down_finish_kernel(LayerParams p, SkinnyPlan pl) {
-  for (int idx = blockIdx.x * 256 + threadIdx.x; idx < p.cols * p.D; idx += gridDim.x * 256) {
-    const int cl = idx / p.D, d = idx - cl * p.D;
+  const int cl = blockIdx.y;  // grid: (blocks over D, column of the pass)
+  for (int d = blockIdx.x * 256 + threadIdx.x; d < p.D; d += gridDim.x * 256) {
     const size_t o = (size_t)(p.col0 + cl) * p.D + d;
     const float v = p.h1[o] + sg_result(p.part, pl, cl, d);
     if (p.out_f32) p.out_f32[o] = v;
@@ -442,6 +453,7 @@ static bool make_plan(SkinnyPlan& pl, int N, int K, int cols, int cus) {
   for (int q = 0; q < kSgMaxGroups; ++q) {
     pl.chunk_begin[q] = pl.chunks[q] = pl.wave_begin[q] = 0;
     pl.per_wave[q] = 1;
+    pl.magic_per_wave[q] = pl.magic_chunks[q] = 0;
   }
   for (int q = 0; q < G; ++q) {
     const int cg = C / G + (q < C % G ? 1 : 0);
@@ -450,6 +462,10 @@ static bool make_plan(SkinnyPlan& pl, int N, int K, int cols, int cus) {
     pl.chunk_begin[q] = begin_chunk; pl.chunks[q] = cg;
     pl.wave_begin[q] = begin_wave;
     pl.per_wave[q] = (int)(((long long)pl.tiles * cg + waves - 1) / waves);
+    pl.magic_per_wave[q] = pl.per_wave[q] > 1 ? (unsigned int)(((1ull << 32) + pl.per_wave[q] - 1) / pl.per_wave[q]) : 0u;
+    pl.magic_chunks[q] = cg > 1 ? (unsigned int)(((1ull << 32) + cg - 1) / cg) : 0u;
+    // the magic numbers are exact while dividend * divisor < 2^32
+    if ((long long)pl.tiles * cg * (pl.per_wave[q] > cg ? pl.per_wave[q] : cg) >= (1LL << 31)) return false;
     begin_chunk += cg; begin_wave += waves;
     max_chunks = cg > max_chunks ? cg : max_chunks;
   }
@@ -582,7 +598,7 @@ extern "C" int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
   auto blocks_for = [](long long n) { long long b = (n + 255) / 256; return (unsigned)(b > 1024 ? 1024 : (b < 1 ? 1 : b)); };
 
   int rc = gemm_passes(w->wqkv, 3 * D, D, p.x, true, [&](const SkinnyPlan& pl) {
-    hipLaunchKernelGGL(dl_qkv_finish_kernel, dim3(blocks_for((long long)p.cols * 3 * H * (p.dh / 2))), dim3(256), 0, st, p, pl);
+    hipLaunchKernelGGL(dl_qkv_finish_kernel, dim3(blocks_for((long long)3 * H * (p.dh / 2)), p.cols), dim3(256), 0, st, p, pl);
   });
   if (rc != CTCSPEC_OK) return rc;
   int rows_written = 0;  // with key splits the attention's merge kernel writes the rows itself
@@ -599,11 +615,11 @@ extern "C" int draft_layer_forward(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
   });
   if (rc != CTCSPEC_OK) return rc;
   rc = gemm_passes(w->wgu, 2 * F, D, p.xn2, false, [&](const SkinnyPlan& pl) {
-    hipLaunchKernelGGL(dl_gate_finish_kernel, dim3(blocks_for((long long)p.cols * F)), dim3(256), 0, st, p, pl);
+    hipLaunchKernelGGL(dl_gate_finish_kernel, dim3(blocks_for((long long)F), p.cols), dim3(256), 0, st, p, pl);
   });
   if (rc != CTCSPEC_OK) return rc;
   rc = gemm_passes(w->wd, D, F, p.act, false, [&](const SkinnyPlan& pl) {
-    hipLaunchKernelGGL(dl_down_finish_kernel, dim3(blocks_for((long long)p.cols * D)), dim3(256), 0, st, p, pl);
+    hipLaunchKernelGGL(dl_down_finish_kernel, dim3(blocks_for((long long)D), p.cols), dim3(256), 0, st, p, pl);
   });
   return rc;
 }
