@@ -465,17 +465,18 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
 // merge inside the attention kernel was measured: one workgroup per query block then pulls all S
 // partials through a single compute unit, which takes longer than this second launch.)
 constexpr int kMergeThreads = 256;
-__global__ __launch_bounds__(kMergeThreads) void tree_attn_merge_kernel(AttnParams p, AttnSplit sp, int rows_per_block) {
+__global__ __launch_bounds__(kMergeThreads) void tree_attn_merge_kernel(AttnParams p, AttnSplit sp, int rows_shift) {
+  const int rows_per_block = 1 << rows_shift;  // 64 or 128 query rows per block
+  // grid: (blocks of 8 rows, head of a sequence) - the indices come from the block numbers, not from divisions
   const int tid = threadIdx.x;
-  const long long grow = (long long)blockIdx.x * (kMergeThreads / 32) + (tid >> 5);  // (b*H + h)*max_nodes + row
-  const int row = (int)(grow % p.max_nodes);
-  const long long bh = grow / p.max_nodes;
-  if (bh >= (long long)p.B * p.H) return;
-  const int b = (int)(bh / p.H);
+  const int row = blockIdx.x * (kMergeThreads / 32) + (tid >> 5);
+  const long long bh = blockIdx.y;  // b * H + h
+  if (row >= p.max_nodes) return;
+  const int b = (int)blockIdx.y / p.H;
   int n = p.n_nodes[b];
   n = n < 1 ? 1 : (n > p.max_nodes ? p.max_nodes : n);
   if (row >= n) return;
-  const int qb = row / rows_per_block, qr = row % rows_per_block;
+  const int qb = row >> rows_shift, qr = row & (rows_per_block - 1);
   const size_t unit0 = ((size_t)bh * sp.QB + qb) * sp.S;
   const int d4 = (tid & 31) * 4;
   float pmv[kMaxKvSplits], plv[kMaxKvSplits];
@@ -525,10 +526,11 @@ static hipError_t launch_attn_bf16(const AttnParams& p, const AttnSplit& sp, hip
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * NW), kAttnLdsBytes, stream, p, sp);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || sp.S == 1) return e;
-  const long long rows = (long long)p.B * p.H * p.max_nodes;
-  const long long mblocks = (rows + kMergeThreads / 32 - 1) / (kMergeThreads / 32);
-  hipLaunchKernelGGL(tree_attn_merge_kernel, dim3((unsigned)mblocks), dim3(kMergeThreads), 0, stream, p, sp,
-                     16 * QT * CW);
+  const unsigned mblocks = (unsigned)((p.max_nodes + kMergeThreads / 32 - 1) / (kMergeThreads / 32));
+  constexpr int kRows = 16 * QT * CW;
+  static_assert(kRows == 64 || kRows == 128, "the merge kernel takes the block size as a shift");
+  hipLaunchKernelGGL(tree_attn_merge_kernel, dim3(mblocks, (unsigned)(p.B * p.H)), dim3(kMergeThreads), 0, stream, p, sp,
+                     kRows == 64 ? 6 : 7);
   return hipGetLastError();
 }
 
@@ -595,7 +597,8 @@ int ctcspec::tree_verify_attn_rows(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
     sp.QB = rows64 ? 2 : 1;
     sp.S = (int)(rows64 ? s64 : s128);
     sp.po = ctx->attn_po; sp.pm = ctx->attn_pm; sp.pl = ctx->attn_pl;
-    CTCSPEC_REQUIRE(ctx, bh * sp.QB * sp.S <= 0x7fffffffLL && bh * max_nodes <= 0x7fffffffLL, CTCSPEC_EUNSUPPORTED,
+    CTCSPEC_REQUIRE(ctx, bh * sp.QB * sp.S <= 0x7fffffffLL && bh * max_nodes <= 0x7fffffffLL && bh <= 65535,
+                    CTCSPEC_EUNSUPPORTED,
                     "tree_verify_attn: grid too large");
     if (rows && sp.S > 1) {  // the merge kernel writes the rows instead of `out`
       p.rows = rows; p.rows_plane = rows_plane;
