@@ -64,6 +64,7 @@ def test_verify_head_full_size(pkg, cfg_index):
     (2, 100, 2048, 129, "bf16"),    # 200 columns: two column blocks, the second ragged; vocabulary barely past a block
     (3, 100, 1024, 1100, "bf16"),   # 300 columns: three column blocks over five row blocks of 256 (fewer than the 8 XCDs), ragged last one
     (5, 128, 512, 2200, "bf16"),    # five full column blocks, nine row blocks of 256: one XCD sees two row groups
+    (3, 100, 512, 5000, "bf16"),    # three column blocks over twenty row blocks of 256: several row groups per XCD
     (1, 5, 1024, 77, "bf16"),       # fewer rows than a block, few columns
     (3, 16, 512, 300, "bf16"),      # hidden size the MFMA kernel does not take: generic kernel
     (2, 9, 48, 11, "f32"),
