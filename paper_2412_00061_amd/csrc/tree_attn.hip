@@ -361,18 +361,23 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
 #pragma unroll
           for (int i = 0; i < 4; ++i) sv[kb * 4 + i] = ((vis >> (kb * 16 + i)) & 1u) ? sv[kb * 4 + i] : -INFINITY;
       }
-      float mx = max3_f32(max3_f32(sv[0], sv[1], sv[2]), max3_f32(sv[3], sv[4], sv[5]), fmaxf(sv[6], sv[7]));
-      mx = max_across_row_groups(mx);
+      const float mx8 = max3_f32(max3_f32(sv[0], sv[1], sv[2]), max3_f32(sv[3], sv[4], sv[5]), fmaxf(sv[6], sv[7]));
       // The softmax reference m_run only has to be NEAR the running max: it is moved (and O, l
       // rescaled) when the tile's max exceeds it by more than 2^8 in the exponent domain, so P stays
       // below 256 and the rescaling of the accumulators - by far the most expensive part of the
-      // step - happens about once per wavefront instead of once per tile.
-      if ((mx - m_run[qt]) * sl2 > 8.0f) {
-        const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - mx) * sl2);  // 0 on first use
-        l_run[qt] *= alpha;
+      // step - happens about once per wavefront instead of once per tile.  A column's maximum is
+      // spread over four lanes, but it exceeds the reference only if one of those lanes' own maxima
+      // does: a vote over the wavefront decides whether anything moves, and the exchange between the
+      // row groups (two LDS round trips in the middle of the tile's dependency chain) is only made then.
+      if (__builtin_amdgcn_ballot_w64((mx8 - m_run[qt]) * sl2 > 8.0f) != 0ull) {
+        const float mx = max_across_row_groups(mx8);
+        if ((mx - m_run[qt]) * sl2 > 8.0f) {
+          const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - mx) * sl2);  // 0 on first use
+          l_run[qt] *= alpha;
 #pragma unroll
-        for (int db = 0; db < 8; ++db) o[qt][db] *= alpha;
-        m_run[qt] = mx;
+          for (int db = 0; db < 8; ++db) o[qt][db] *= alpha;
+          m_run[qt] = mx;
+        }
       }
       const float ms = (m_run[qt] > -INFINITY ? m_run[qt] : 0.f) * sl2;
       float psum = 0.f;
