@@ -187,7 +187,8 @@ struct AttnSplit {
 };
 
 template <int QT, int NW, int CW, int PF>
-__global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int ROWS = 16 * QT * CW;  // the first CW wavefronts own query rows; all NW fetch tiles
   constexpr int kThreadsA = 64 * NW;
@@ -261,6 +262,16 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
   int koff[4];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) koff[kk] = c * 256 + (((kk * 4 + g) ^ c) << 4);
+  // The read addresses are kept as complete LDS addresses that the compiler cannot take apart again: as
+  // "start of the dynamic LDS block + offset" it recomputes all twelve inside the loop instead of keeping them
+  // in registers.
+  typedef __attribute__((address_space(3))) unsigned char lds_byte;
+  const unsigned int lds0 = (unsigned int)(size_t)(lds_byte*)smem;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    koff[kk] += lds0;
+    asm volatile("" : "+v"(koff[kk]));
+  }
   // V, transposing read: lane 16g + s fetches 8 bytes of row kb*16 + 4g + (s >> 2), dh 16db + 4(s & 3)..+3;
   // the 16 lanes of a row group then hold dh 16db + s, keys kb*16 + 4g .. + 3
   int toff[8];
@@ -269,7 +280,10 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
     const int x7 = ((4 * (g & 1) + s4) << 1) << 4;  // swizzle term of that row, in bytes
     const int rbase = kTileBytes + (4 * g + s4) * 256 + ((c & 2) ? 16 : 0) + ((c & 1) ? 8 : 0);
 #pragma unroll
-    for (int db = 0; db < 8; ++db) toff[db] = rbase + ((db << 5) ^ x7);
+    for (int db = 0; db < 8; ++db) {
+      toff[db] = lds0 + rbase + ((db << 5) ^ x7);
+      asm volatile("" : "+v"(toff[db]));
+    }
   }
 
   // ---- this wavefront's query columns: Q fragments (B operand of K.Q^T) and mask words -------------
@@ -306,12 +320,12 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
     for (int db = 0; db < 8; ++db) o[qt][db] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  auto compute = [&](int j, int stage) __attribute__((always_inline)) {
+  auto compute = [&](int j, auto stage_tag) __attribute__((always_inline)) {
     const int t = split + j * sp.S;
     const bool tree = t >= ctxT;
     const int row0 = (tree ? t - ctxT : t) * kTileKeys;
     const bool full = !tree && row0 + kTileKeys <= L;  // every key of the tile is visible to every row
-    const int sbase = stage * kStageBytes;  // plain integer offsets: they fold into the instructions' offset fields
+    constexpr int sbase = decltype(stage_tag)::value * kStageBytes;  // folds into the instructions' offset fields
     // S^T = K.Q^T for the two blocks of 16 keys, all query tiles
     f32x4 s[QT][2];
 #pragma unroll
@@ -323,7 +337,8 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(smem + (koff[kk] + sbase + kb * 4096)));
+        const bf16x8 a = __builtin_bit_cast(
+            bf16x8, *(const __attribute__((address_space(3))) u32x4*)(unsigned int)(koff[kk] + (sbase + kb * 4096)));
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt)
           s[qt][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[qt][kk], s[qt][kb], 0, 0, 0);
@@ -333,9 +348,9 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
       const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) s16x4*)(smem + (toff[db] + sbase)));
+          (__attribute__((address_space(3))) s16x4*)(unsigned int)(toff[db] + sbase));
       const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) s16x4*)(smem + (toff[db] + sbase + 4096)));
+          (__attribute__((address_space(3))) s16x4*)(unsigned int)(toff[db] + (sbase + 4096)));
       va[db] = s16x8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
     }
     // online softmax per query tile
@@ -432,7 +447,7 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_bf16_kernel(AttnParams p, A
         const int j = j0 + JJ;
         commit(std::integral_constant<int, (JJ + 1) % PF>{}, (JJ + 1) & 1);
         issue(j + PF, jj_tag);
-        if (live_wave && j < nloc) compute(j, JJ & 1);
+        if (live_wave && j < nloc) compute(j, std::integral_constant<int, (JJ & 1)>{});
         lds_barrier();  // not __syncthreads(): the prefetched tiles must stay in flight
       });
     }
