@@ -230,13 +230,18 @@ void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
     const unsigned char* ks = tree ? kt : kc;
     const unsigned char* vs = tree ? vt : vc;
     const int row0 = (tree ? t - ctxT : t) * kTileKeys, limit = tree ? n : L;
+    // tile start as a wavefront-uniform address (scalar arithmetic), the thread's place in the tile as a
+    // 32-bit offset: two vector instructions per tile instead of 64-bit address arithmetic per thread
+    const unsigned char* kt0 = ks + (size_t)row0 * 256;
+    const unsigned char* vt0 = vs + (size_t)row0 * 256;
+    const int last = limit - 1 - row0;  // >= 0: rows past the end re-read the last valid row (masked later)
 #pragma unroll
     for (int u = 0; u < LU; ++u) {
       const int q = tid + kThreadsA * u;
-      int row = row0 + (q >> 4);
-      row = row < limit ? row : limit - 1;  // rows past the end re-read the last valid row (masked later)
-      ld[SET][u] = *(const u32x4*)(ks + (size_t)row * 256 + (q & 15) * 16);
-      ld[SET][LU + u] = *(const u32x4*)(vs + (size_t)row * 256 + (q & 15) * 16);
+      const int r = q >> 4;
+      const unsigned int off = (unsigned int)((r < last ? r : last) * 256 + (q & 15) * 16);
+      ld[SET][u] = *(const u32x4*)(kt0 + off);
+      ld[SET][LU + u] = *(const u32x4*)(vt0 + off);
     }
   };
   int coff_k[LU], coff_v[LU];
