@@ -606,9 +606,10 @@ int ctcspec::tree_verify_attn_rows(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
     // Launch shape.  A workgroup has 8 wavefronts that all fetch tiles; 8 or 4 of them own 16 query rows
     // each (blocks of 128 or 64 rows per (sequence, head)); S key splits, so that about 256 workgroups
     // exist and each still has a few tiles of 32 keys to stream.  64-row blocks halve the partial results
-    // (fewer splits) at the price of a second pass over K/V through L2; they are taken when they fill
-    // more compute units, or as many with at least 4 splits.  Trees of 64 nodes or fewer use one block,
-    // its upper wavefronts only fetching.
+    // (fewer splits) at the price of a second pass over K/V through L2 and of one computing wavefront
+    // per SIMD instead of two; they are taken only when they fill more compute units (when both shapes
+    // fill as many, the 128-row one measured 0.6 us faster for kernel and merge together).  Trees of 64
+    // nodes or fewer use one block, its upper wavefronts only fetching.
     const long long bh = (long long)B * H;
     const int key_tiles = (kv_cap + max_nodes + kTileKeys - 1) / kTileKeys;
     auto splits_for = [&](long long qblocks) {
@@ -619,7 +620,7 @@ int ctcspec::tree_verify_attn_rows(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
       return S < 1 ? 1LL : S;
     };
     const long long s128 = splits_for(1), s64 = splits_for(2);
-    const bool rows64 = max_nodes > 64 && (2 * s64 > s128 || (2 * s64 == s128 && s64 >= 4));
+    const bool rows64 = max_nodes > 64 && 2 * s64 > s128;
     AttnSplit sp;
     sp.QB = rows64 ? 2 : 1;
     sp.S = (int)(rows64 ? s64 : s128);

@@ -96,10 +96,12 @@ def _run(pkg, case, trees, B, H, N, dh):
     return moved
 
 
-# (B, H, max_nodes, kv_cap, ctx_len, tree kind): the 7B step's shape (two query blocks, four key splits), twice its
-# heads (one 128-row block), the ragged batch (one key range per workgroup), and the draft layer's 8 causal rows
+# (B, H, max_nodes, kv_cap, ctx_len, tree kind): the 7B step's shape (one 128-row block, eight key splits), the same
+# heads over a short context (two 64-row blocks, four key splits: the upper wavefronts only fetch), twice the heads
+# (128-row block, four splits), the ragged batch (one key range per workgroup), and the draft layer's 8 causal rows
 SHAPES = {
     "7b_ctx2048": (1, 32, 128, 2048, [2048], "beam"),
+    "7b_ctx512": (1, 32, 128, 512, [512], "beam"),
     "64_heads": (1, 64, 128, 1024, [1000], "beam"),
     "batch8_ragged": (8, 32, 64, 2048, [256, 2048, 1111, 777, 1999, 300, 1280, 95], "beam"),
     "draft_layer_rows": (1, 32, 8, 2048, [2048], "chain"),
