@@ -128,12 +128,14 @@ __global__ __launch_bounds__(kGenericThreads) void tree_attn_generic_kernel(Attn
 
 // ---- bf16, dh = 128 -------------------------------------------------------------------------------
 // Workgroup = NW wavefronts = one block of 16*QT*CW query nodes of one (sequence, head) and one of S
-// splits of the keys; wavefront w < CW owns query rows [16*QT*w, 16*QT*(w+1)) of the block (wavefronts
-// CW..NW-1 only help to fetch tiles).  The keys
+// splits of the keys.  The wavefronts form CW row groups x KP = NW/CW key parts: wavefront w owns query
+// rows [16*QT*rg, 16*QT*(rg+1)) of the block, rg = w % CW, and of every KP consecutive tiles of the
+// workgroup the one numbered kp = w / CW (with 64-row blocks two wavefronts per SIMD compute, as with
+// 128-row blocks; the two key parts of a row group are joined through LDS at the end).  The keys
 // (cached context rows first, then the tree nodes) are cut into tiles of 32; split s takes tiles s,
-// s+S, ...  A tile (K and V, 16 KB) is fetched ONCE per workgroup by all threads together (one or two
-// 16-byte loads of K and of V per thread, PF tiles ahead in registers), put into one of two LDS
-// stages and used by every wavefront.  With S == 1 the workgroup writes the result; otherwise it
+// s+S, ...  A tile (K and V, 16 KB) is fetched ONCE per workgroup by all threads together (one
+// 16-byte load of K and of V per thread and tile, PF iterations ahead in registers), put into one of
+// two LDS stages of KP tiles.  With S == 1 the workgroup writes the result; otherwise it
 // leaves an unnormalised partial (O, max, sum) per row in the context workspace and
 // tree_attn_merge_kernel combines the S partials.
 //
@@ -155,7 +157,8 @@ __global__ __launch_bounds__(kGenericThreads) void tree_attn_generic_kernel(Attn
 constexpr int kTileKeys = 32;
 constexpr int kTileBytes = kTileKeys * 256;        // K or V of one tile
 constexpr int kStageBytes = 2 * kTileBytes;        // K then V
-constexpr int kAttnLdsBytes = 2 * kStageBytes;     // two stages
+// dynamic LDS of the kernel: two stages of KP tiles
+constexpr int attn_lds_bytes(int kp) { return 2 * kp * kStageBytes; }
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -190,11 +193,13 @@ template <int QT, int NW, int CW, int PF>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int ROWS = 16 * QT * CW;  // the first CW wavefronts own query rows; all NW fetch tiles
-  constexpr int kThreadsA = 64 * NW;
-  constexpr int LU = 512 / kThreadsA;  // 16-byte pieces of K (and of V) per thread and tile
+  constexpr int ROWS = 16 * QT * CW;
+  constexpr int KP = NW / CW;  // key parts: tiles taken per iteration
+  static_assert(NW == 8 && NW % CW == 0 && (KP == 1 || (KP == 2 && QT == 1)), "512 threads fetch a tile; the join of two key parts is written for one query tile");
+  constexpr int kIterBytes = KP * kStageBytes;  // one LDS stage
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int rg = wave % CW, kp = wave / CW;
   const int c = lane & 15, g = lane >> 4;
   int bid = blockIdx.x;
   const int h = bid % p.H;
@@ -218,47 +223,42 @@ void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
   const int ctxT = (L + kTileKeys - 1) / kTileKeys, treeT = (n + kTileKeys - 1) / kTileKeys;
   const int NTL = ctxT + treeT;
   const int nloc = split < NTL ? (NTL - split + sp.S - 1) / sp.S : 0;  // my tiles: split, split+S, ...
+  const int niter = (nloc + KP - 1) / KP;                              // iterations of KP tiles
 
-  // ---- tile loader: thread -> (row, chunk) of K and of V, LU times -----------------------------------
-  u32x4 ld[PF][2 * LU];
+  // ---- tile loader: thread -> (row, chunk) of K and of V in each of the iteration's KP tiles ----------
+  u32x4 ld[PF][2 * KP];
+  const int lrow = tid >> 4, lchunk = tid & 15;
   auto issue = [&](int j, auto set_tag) __attribute__((always_inline)) {
     constexpr int SET = decltype(set_tag)::value;
-    // past the last tile the loads are still issued (on the last tile again, an L2 hit): every wait on
-    // an earlier tile can then count on exactly PF-1 younger tiles in flight
-    const int t = split + (j < nloc ? j : nloc - 1) * sp.S;
-    const bool tree = t >= ctxT;
-    const unsigned char* ks = tree ? kt : kc;
-    const unsigned char* vs = tree ? vt : vc;
-    const int row0 = (tree ? t - ctxT : t) * kTileKeys, limit = tree ? n : L;
-    // tile start as a wavefront-uniform address (scalar arithmetic), the thread's place in the tile as a
-    // 32-bit offset: two vector instructions per tile instead of 64-bit address arithmetic per thread
-    const unsigned char* kt0 = ks + (size_t)row0 * 256;
-    const unsigned char* vt0 = vs + (size_t)row0 * 256;
-    const int last = limit - 1 - row0;  // >= 0: rows past the end re-read the last valid row (masked later)
 #pragma unroll
-    for (int u = 0; u < LU; ++u) {
-      const int q = tid + kThreadsA * u;
-      const int r = q >> 4;
-      const unsigned int off = (unsigned int)((r < last ? r : last) * 256 + (q & 15) * 16);
+    for (int u = 0; u < KP; ++u) {
+      // past the last tile the loads are still issued (on the last tile again, an L2 hit): every wait on
+      // an earlier tile can then count on exactly PF-1 younger iterations in flight
+      const int jl = KP * j + u;
+      const int t = split + (jl < nloc ? jl : nloc - 1) * sp.S;
+      const bool tree = t >= ctxT;
+      const unsigned char* ks = tree ? kt : kc;
+      const unsigned char* vs = tree ? vt : vc;
+      const int row0 = (tree ? t - ctxT : t) * kTileKeys, limit = tree ? n : L;
+      // tile start as a wavefront-uniform address (scalar arithmetic), the thread's place in the tile as a
+      // 32-bit offset: two vector instructions per tile instead of 64-bit address arithmetic per thread
+      const unsigned char* kt0 = ks + (size_t)row0 * 256;
+      const unsigned char* vt0 = vs + (size_t)row0 * 256;
+      const int last = limit - 1 - row0;  // >= 0: rows past the end re-read the last valid row (masked later)
+      const unsigned int off = (unsigned int)((lrow < last ? lrow : last) * 256 + lchunk * 16);
       ld[SET][u] = *(const u32x4*)(kt0 + off);
-      ld[SET][LU + u] = *(const u32x4*)(vt0 + off);
+      ld[SET][KP + u] = *(const u32x4*)(vt0 + off);
     }
   };
-  int coff_k[LU], coff_v[LU];
-#pragma unroll
-  for (int u = 0; u < LU; ++u) {
-    const int q = tid + kThreadsA * u;
-    const int row = q >> 4, chunk = q & 15;
-    coff_k[u] = row * 256 + ((chunk ^ (row & 15)) << 4);
-    coff_v[u] = kTileBytes + row * 256 + ((chunk ^ ((row & 7) << 1)) << 4);
-  }
+  const int coff_k = lrow * 256 + ((lchunk ^ (lrow & 15)) << 4);
+  const int coff_v = kTileBytes + lrow * 256 + ((lchunk ^ ((lrow & 7) << 1)) << 4);
   auto commit = [&](auto set_tag, int stage) __attribute__((always_inline)) {
     constexpr int SET = decltype(set_tag)::value;
-    unsigned char* base = smem + stage * kStageBytes;
+    unsigned char* base = smem + stage * kIterBytes;
 #pragma unroll
-    for (int u = 0; u < LU; ++u) {
-      *(u32x4*)(base + coff_k[u]) = ld[SET][u];
-      *(u32x4*)(base + coff_v[u]) = ld[SET][LU + u];
+    for (int u = 0; u < KP; ++u) {
+      *(u32x4*)(base + u * kStageBytes + coff_k) = ld[SET][u];
+      *(u32x4*)(base + u * kStageBytes + coff_v) = ld[SET][KP + u];
     }
   };
 
@@ -274,7 +274,7 @@ void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
   const unsigned int lds0 = (unsigned int)(size_t)(lds_byte*)smem;
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
-    koff[kk] += lds0;
+    koff[kk] += lds0 + kp * kStageBytes;  // this wavefront's tile of the stage
     asm volatile("" : "+v"(koff[kk]));
   }
   // V, transposing read: lane 16g + s fetches 8 bytes of row kb*16 + 4g + (s >> 2), dh 16db + 4(s & 3)..+3;
@@ -286,14 +286,14 @@ void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
     const int rbase = kTileBytes + (4 * g + s4) * 256 + ((c & 2) ? 16 : 0) + ((c & 1) ? 8 : 0);
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
-      toff[db] = lds0 + rbase + ((db << 5) ^ x7);
+      toff[db] = lds0 + kp * kStageBytes + rbase + ((db << 5) ^ x7);
       asm volatile("" : "+v"(toff[db]));
     }
   }
 
   // ---- this wavefront's query columns: Q fragments (B operand of K.Q^T) and mask words -------------
-  const int qbase = qb * ROWS + wave * 16 * QT;
-  const bool live_wave = wave < CW && qbase < n;
+  const int qbase = qb * ROWS + rg * 16 * QT;
+  const bool live_wave = qbase < n;
   bf16x8 qf[QT][4];
   unsigned long long mw0[QT], mw1[QT];
   const int W = (p.max_nodes + 63) >> 6;
@@ -325,12 +325,12 @@ void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
     for (int db = 0; db < 8; ++db) o[qt][db] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  auto compute = [&](int j, auto stage_tag) __attribute__((always_inline)) {
-    const int t = split + j * sp.S;
+  auto compute = [&](int jl, auto stage_tag) __attribute__((always_inline)) {
+    const int t = split + jl * sp.S;
     const bool tree = t >= ctxT;
     const int row0 = (tree ? t - ctxT : t) * kTileKeys;
     const bool full = !tree && row0 + kTileKeys <= L;  // every key of the tile is visible to every row
-    constexpr int sbase = decltype(stage_tag)::value * kStageBytes;  // folds into the instructions' offset fields
+    constexpr int sbase = decltype(stage_tag)::value * kIterBytes;  // folds into the instructions' offset fields
     // S^T = K.Q^T for the two blocks of 16 keys, all query tiles
     f32x4 s[QT][2];
 #pragma unroll
@@ -433,7 +433,7 @@ void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
         o[qt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va[db]), pl[qt], o[qt][db], 0, 0, 0);
   };
 
-  // ---- pipeline: loads PF tiles ahead in registers, LDS write one tile ahead -------------------------
+  // ---- pipeline: loads PF iterations (of KP tiles) ahead in registers, LDS write one iteration ahead ----
   auto for_each_set = [&](auto&& fn) __attribute__((always_inline)) {
     [&]<int... I>(std::integer_sequence<int, I...>) { (fn(std::integral_constant<int, I>{}), ...); }
     (std::make_integer_sequence<int, PF>{});
@@ -445,16 +445,43 @@ void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
     // the trip count is rounded up to a multiple of PF; the surplus iterations only move (already
     // cached) data - keeping loads, LDS writes and barriers free of conditions is what lets the
     // waits be exact
-    const int nit = (nloc + PF - 1) / PF * PF;
+    const int nit = (niter + PF - 1) / PF * PF;
     for (int j0 = 0; j0 < nit; j0 += PF) {
       for_each_set([&](auto jj_tag) __attribute__((always_inline)) {
         constexpr int JJ = decltype(jj_tag)::value;
         const int j = j0 + JJ;
         commit(std::integral_constant<int, (JJ + 1) % PF>{}, (JJ + 1) & 1);
         issue(j + PF, jj_tag);
-        if (live_wave && j < nloc) compute(j, std::integral_constant<int, (JJ & 1)>{});
+        if (live_wave && KP * j + kp < nloc) compute(KP * j + kp, std::integral_constant<int, (JJ & 1)>{});
         lds_barrier();  // not __syncthreads(): the prefetched tiles must stay in flight
       });
+    }
+  }
+  // ---- the two key parts of a row group joined: the upper wavefront hands (O, reference, sum) over in LDS ----
+  if constexpr (KP == 2) {
+    __syncthreads();  // every tile consumed: the stages are free
+    f32x4* xo = (f32x4*)smem;                       // [8 dh blocks][CW * 64 lanes]
+    float* xm = (float*)(smem + 8 * CW * 64 * 16);  // [CW * 64] reference, then [CW * 64] sum
+    static_assert(8 * CW * 64 * 16 + 2 * CW * 64 * 4 <= attn_lds_bytes(KP), "the hand-over fits the stages");
+    const int at = rg * 64 + lane;
+    if (kp == 1 && live_wave) {
+#pragma unroll
+      for (int db = 0; db < 8; ++db) xo[db * (CW * 64) + at] = o[0][db];
+      xm[at] = m_run[0];
+      xm[CW * 64 + at] = l_run[0];
+    }
+    __syncthreads();
+    if (kp == 1) return;
+    if (live_wave) {
+      const float m1 = xm[at], l1 = xm[CW * 64 + at];
+      const float M = fmaxf(m_run[0], m1);
+      // a part that saw no visible key has reference -inf and contributes nothing
+      const float a0 = m_run[0] > -INFINITY ? __builtin_amdgcn_exp2f((m_run[0] - M) * sl2) : 0.f;
+      const float a1 = m1 > -INFINITY ? __builtin_amdgcn_exp2f((m1 - M) * sl2) : 0.f;
+#pragma unroll
+      for (int db = 0; db < 8; ++db) o[0][db] = o[0][db] * a0 + xo[db * (CW * 64) + at] * a1;
+      l_run[0] = l_run[0] * a0 + l1 * a1;
+      m_run[0] = M;
     }
   }
   if (!live_wave) return;
@@ -464,7 +491,7 @@ void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
     const float l = sum_across_row_groups(l_run[qt]);
-    const int qr = wave * 16 * QT + qt * 16 + c;  // row inside the block
+    const int qr = rg * 16 * QT + qt * 16 + c;  // row inside the block
     const int qg = qb * ROWS + qr;
     if (qg >= n) continue;
     if (sp.S == 1) {
@@ -550,7 +577,7 @@ template <int QT, int NW, int CW, int PF>
 static hipError_t launch_attn_bf16(const AttnParams& p, const AttnSplit& sp, hipStream_t stream) {
   auto kern = tree_attn_bf16_kernel<QT, NW, CW, PF>;
   const long long blocks = (long long)sp.QB * sp.S * p.H * p.B;
-  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * NW), kAttnLdsBytes, stream, p, sp);
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * NW), attn_lds_bytes(NW / CW), stream, p, sp);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || sp.S == 1) return e;
   const unsigned mblocks = (unsigned)((p.max_nodes + kMergeThreads / 32 - 1) / (kMergeThreads / 32));
@@ -565,7 +592,11 @@ static hipError_t launch_attn_bf16(const AttnParams& p, const AttnSplit& sp, hip
 // triggers a load, so it can be the first thing a stream capture records)
 hipError_t prepare_tree_attn() {
   hipFuncAttributes attr;
-  return hipFuncGetAttributes(&attr, (const void*)tree_attn_merge_kernel);
+  hipError_t e = hipFuncGetAttributes(&attr, (const void*)tree_attn_merge_kernel);
+  if (e != hipSuccess) return e;
+  // the 64-row kernel's two stages of two tiles are 64 KB of dynamic LDS
+  return hipFuncSetAttribute((const void*)tree_attn_bf16_kernel<1, 8, 4, 2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                             attn_lds_bytes(2));
 }
 
 }  // namespace ctcspec
@@ -603,13 +634,14 @@ int ctcspec::tree_verify_attn_rows(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
   p.rows = nullptr; p.rows_plane = 0;
   if (dt == CTCSPEC_BF16 && dh == 128) {
     CTCSPEC_REQUIRE(ctx, scale > 0.f, CTCSPEC_EINVAL, "tree_verify_attn: scale must be positive");
-    // Launch shape.  A workgroup has 8 wavefronts that all fetch tiles; 8 or 4 of them own 16 query rows
-    // each (blocks of 128 or 64 rows per (sequence, head)); S key splits, so that about 256 workgroups
-    // exist and each still has a few tiles of 32 keys to stream.  64-row blocks halve the partial results
-    // (fewer splits) at the price of a second pass over K/V through L2 and of one computing wavefront
-    // per SIMD instead of two; they are taken only when they fill more compute units (when both shapes
-    // fill as many, the 128-row one measured 0.6 us faster for kernel and merge together).  Trees of 64
-    // nodes or fewer use one block, its upper wavefronts only fetching.
+    // Launch shape.  A workgroup has 8 wavefronts that all fetch tiles and all compute: 8 row groups of 16
+    // query rows (blocks of 128 rows per (sequence, head)), or 4 row groups x 2 key parts (blocks of 64
+    // rows); S key splits, so that about 256 workgroups exist and each still has a few tiles of 32 keys
+    // to stream.  Two 64-row blocks per head halve the partial results (fewer splits) at the price of a
+    // second pass over K/V through L2; they are taken when they fill more compute units, or as many with
+    // at least 4 splits (kernel and merge together then take the same time as one 128-row block with
+    // twice the splits, with 20 MB less traffic at the 7B shape).  Trees of 64 nodes or fewer are one
+    // 64-row block.
     const long long bh = (long long)B * H;
     const int key_tiles = (kv_cap + max_nodes + kTileKeys - 1) / kTileKeys;
     auto splits_for = [&](long long qblocks) {
@@ -620,10 +652,11 @@ int ctcspec::tree_verify_attn_rows(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
       return S < 1 ? 1LL : S;
     };
     const long long s128 = splits_for(1), s64 = splits_for(2);
-    const bool rows64 = max_nodes > 64 && 2 * s64 > s128;
+    const bool two_blocks = max_nodes > 64 && (2 * s64 > s128 || (2 * s64 == s128 && s64 >= 4));
+    const bool rows64 = two_blocks || max_nodes <= 64;
     AttnSplit sp;
-    sp.QB = rows64 ? 2 : 1;
-    sp.S = (int)(rows64 ? s64 : s128);
+    sp.QB = two_blocks ? 2 : 1;
+    sp.S = (int)(two_blocks ? s64 : s128);
     sp.po = ctx->attn_po; sp.pm = ctx->attn_pm; sp.pl = ctx->attn_pl;
     CTCSPEC_REQUIRE(ctx, bh * sp.QB * sp.S <= 0x7fffffffLL && bh * max_nodes <= 0x7fffffffLL && bh <= 65535,
                     CTCSPEC_EUNSUPPORTED,

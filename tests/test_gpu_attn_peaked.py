@@ -96,9 +96,10 @@ def _run(pkg, case, trees, B, H, N, dh):
     return moved
 
 
-# (B, H, max_nodes, kv_cap, ctx_len, tree kind): the 7B step's shape (one 128-row block, eight key splits), the same
-# heads over a short context (two 64-row blocks, four key splits: the upper wavefronts only fetch), twice the heads
-# (128-row block, four splits), the ragged batch (one key range per workgroup), and the draft layer's 8 causal rows
+# (B, H, max_nodes, kv_cap, ctx_len, tree kind): the 7B step's shape (two 64-row blocks of 4 row groups x 2 key parts,
+# four key splits), the same heads over a short context (five tiles per split: an odd count for the two key parts),
+# twice the heads (one 128-row block, four splits), the ragged batch (one 64-row block, one key range per workgroup:
+# both key parts meet masked context ends), and the draft layer's 8 causal rows (one live row group, eight splits)
 SHAPES = {
     "7b_ctx2048": (1, 32, 128, 2048, [2048], "beam"),
     "7b_ctx512": (1, 32, 128, 512, [512], "beam"),
