@@ -442,18 +442,19 @@ void tree_attn_bf16_kernel(AttnParams p, AttnSplit sp) {
     for_each_set([&](auto jj_tag) __attribute__((always_inline)) { issue(decltype(jj_tag)::value, jj_tag); });
     commit(std::integral_constant<int, 0>{}, 0);
     lds_barrier();
-    // the trip count is rounded up to a multiple of PF; the surplus iterations only move (already
-    // cached) data - keeping loads, LDS writes and barriers free of conditions is what lets the
-    // waits be exact
-    const int nit = (niter + PF - 1) / PF * PF;
-    for (int j0 = 0; j0 < nit; j0 += PF) {
+    // loads, LDS writes and barriers are free of conditions inside an iteration (tile indices clamped), which is
+    // what lets the waits be exact; the unrolled body is left after any of its PF steps
+    bool more = true;
+    for (int j0 = 0; more; j0 += PF) {
       for_each_set([&](auto jj_tag) __attribute__((always_inline)) {
         constexpr int JJ = decltype(jj_tag)::value;
         const int j = j0 + JJ;
+        if (!more) return;
         commit(std::integral_constant<int, (JJ + 1) % PF>{}, (JJ + 1) & 1);
         issue(j + PF, jj_tag);
         if (live_wave && KP * j + kp < nloc) compute(KP * j + kp, std::integral_constant<int, (JJ & 1)>{});
         lds_barrier();  // not __syncthreads(): the prefetched tiles must stay in flight
+        more = j + 1 < niter;
       });
     }
   }
