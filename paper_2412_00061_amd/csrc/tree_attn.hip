@@ -641,7 +641,7 @@ int ctcspec::tree_verify_attn_rows(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
     // to stream.  Two 64-row blocks per head halve the partial results (fewer splits) at the price of a
     // second pass over K/V through L2; they are taken when they fill more compute units, or as many with
     // at least 4 splits (kernel and merge together then take the same time as one 128-row block with
-    // twice the splits, with 20 MB less traffic at the 7B shape).  Trees of 64 nodes or fewer are one
+    // twice the splits, with 20 MB less traffic at the 7B shape).  Trees of 17 to 64 nodes are one
     // 64-row block.
     const long long bh = (long long)B * H;
     const int key_tiles = (kv_cap + max_nodes + kTileKeys - 1) / kTileKeys;
@@ -654,7 +654,9 @@ int ctcspec::tree_verify_attn_rows(ctcspec_ctx* ctx, ctcspec_dtype dt, const voi
     };
     const long long s128 = splits_for(1), s64 = splits_for(2);
     const bool two_blocks = max_nodes > 64 && (2 * s64 > s128 || (2 * s64 == s128 && s64 >= 4));
-    const bool rows64 = two_blocks || max_nodes <= 64;
+    // (up to 16 rows, a single row group: the one-tile-per-iteration kernel, whose first tile is in LDS sooner -
+    // 9.1 against 9.9 us for the draft layer's 8 rows)
+    const bool rows64 = two_blocks || (max_nodes <= 64 && max_nodes > 16);
     AttnSplit sp;
     sp.QB = two_blocks ? 2 : 1;
     sp.S = (int)(two_blocks ? s64 : s128);
